@@ -1,0 +1,168 @@
+/*
+ * deinfer.h - C ABI of the MI355X (gfx950) low-rank linear-layer library.
+ *
+ * A decomposed LLM replaces every dense projection W[d_in x d_out] by a factor
+ * pair W ~= U . V (DeInfer paper, Sec. 2.1, Eq. 1: W ~= A B with A = U_k sqrt(S_k),
+ * B = sqrt(S_k) V_k^T).  The layer then computes two chained products,
+ *     t = x . U   (downward projection into the rank space, width r)
+ *     y = t . V   (upward projection)
+ * (Sec. 4.1).  Naming: U here is the FIRST / downward factor (the paper's A, its
+ * "x_v"); V is the SECOND / upward factor (the paper's B, its "x_u").  Row-vector
+ * convention y = x U V; every matrix is row-major.
+ *
+ * General rules for every call
+ *  - All data pointers are DEVICE pointers on the calling thread's current HIP
+ *    device, owned by the caller, and must stay valid until the stream work is done.
+ *  - Calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL =
+ *    default stream); they never synchronise the device and never allocate.
+ *  - Outputs must not alias inputs or the workspace.
+ *  - Return value: DEINFER_OK or a negative deinfer_status_t; on error nothing is
+ *    enqueued and deinfer_last_error() describes the problem.  Argument validation
+ *    happens on the host before any device call.
+ *  - T == 0 is a successful no-op.  A pair with r == 0 yields an all-zero output.
+ *  - No bias term (the paper's layers carry none).
+ */
+#ifndef DEINFER_H
+#define DEINFER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DEINFER_OK = 0,
+  DEINFER_ERR_INVALID_ARG = -1,  /* NULL pointer, negative size, inconsistent shapes */
+  DEINFER_ERR_UNSUPPORTED = -2,  /* dtype / layout / feature combination not available */
+  DEINFER_ERR_MISALIGNED = -3,   /* pointer or leading dimension breaks an alignment rule */
+  DEINFER_ERR_WORKSPACE = -4,    /* workspace missing or too small */
+  DEINFER_ERR_DEVICE = -5        /* the HIP runtime reported an error (no GPU, bad launch) */
+} deinfer_status_t;
+
+typedef enum { DEINFER_F32 = 0, DEINFER_BF16 = 1 } deinfer_dtype_t;
+
+typedef enum {
+  DEINFER_LAYOUT_RAW = 0,    /* U[d_in x r] (ldu), V[r x d_out] (ldv), row-major          */
+  DEINFER_LAYOUT_PACKED = 1  /* produced by deinfer_pack_factors (bf16 only), see below   */
+} deinfer_layout_t;
+
+/*
+ * One factor pair (Sec. 2.1: an m x n weight becomes (m + n) k parameters; here
+ * m = d_in, n = d_out, k = r).  Each pair carries its own rank: different layers,
+ * and q / k / v inside one layer, may use different ratios (Sec. 4.3).
+ */
+typedef struct deinfer_factors {
+  const void *U;           /* device; RAW: d_in x r elements, row pitch ldu            */
+  const void *V;           /* device; RAW: r x d_out elements, row pitch ldv            */
+  int64_t d_in, d_out, r;  /* logical sizes; r >= 0                                     */
+  int64_t ldu, ldv;        /* RAW: leading dimensions in elements (>= r, >= d_out).
+                              PACKED: ignored                                           */
+  int32_t dtype;           /* deinfer_dtype_t of U, V, the activations and the outputs  */
+  int32_t layout;          /* deinfer_layout_t                                          */
+  double param_reduction;  /* informational: the compression ratio this rank came from  */
+} deinfer_factors_t;
+
+/* Human-readable text for the last error on this thread (static storage, never NULL). */
+const char *deinfer_last_error(void);
+
+/* Library version, major * 1000 + minor. */
+int deinfer_version(void);
+
+/*
+ * Rank that keeps a fraction (1 - param_reduction) of the m*n parameters of a weight:
+ *     r = floor((1 - param_reduction) * m * n / (m + n))
+ * since a pair of inner size k holds (m + n) k parameters (Sec. 2.1).  The ratio is
+ * taken at a resolution of 1e-6 and the division is exact integer arithmetic.
+ * Host-only.  Errors: INVALID_ARG for m, n <= 0, ratio outside [0, 1] or NULL r_out.
+ */
+int deinfer_rank_for_ratio(int64_t m, int64_t n, double param_reduction, int64_t *r_out);
+
+/*
+ * Packed weight format (bf16 only).  Weights are static, so they are re-laid once
+ * for the matrix cores: each factor is stored transposed ("feature" rows, reduction
+ * index contiguous), zero-padded (r to a multiple of 32, feature counts to 16,
+ * d_in to 32), and cut into 16-feature x 32-k fragments of 1 KiB held in the lane
+ * order of the gfx950 16x16x32 bf16 MFMA operand, fragment (tile, kblock) at
+ * ((tile * n_kblocks) + kblock) KiB.  A wavefront then reads one fragment with a
+ * single fully coalesced 16-byte-per-lane load.  Zero rank rows are exact no-ops.
+ *
+ * deinfer_packed_bytes: size of the packed image of `raw` (host-only).
+ * deinfer_pack_factors: enqueue the re-layout of `raw` (RAW, bf16) into dst
+ *   (device, 256-byte aligned, >= packed bytes) and fill *packed (host struct) with
+ *   a descriptor that points into dst.  dst must outlive every use of *packed.
+ */
+int deinfer_packed_bytes(const deinfer_factors_t *raw, size_t *bytes);
+int deinfer_pack_factors(const deinfer_factors_t *raw, void *dst, size_t dst_bytes,
+                         deinfer_factors_t *packed, void *stream);
+
+/*
+ * Workspace.  The library never allocates: the rank-space intermediate t (Sec. 4.1)
+ * and the cross-workgroup synchronisation words live in a caller-provided device
+ * buffer.
+ *  deinfer_workspace_bytes: bytes needed for a call with T tokens over the given
+ *    pairs (all pairs of one entry-point call).  Host-only.  Take the maximum over
+ *    the calls that will share the workspace.
+ *  deinfer_workspace_init: must be enqueued ONCE on a fresh workspace (and after a
+ *    call was aborted) before its first use; clears the synchronisation words with
+ *    a fill kernel (safe under stream capture).  Calls leave them cleared again.
+ *  deinfer_workspace_check: synchronises `stream`, reads the workspace status word
+ *    back and returns DEINFER_ERR_DEVICE if a kernel gave up waiting on its
+ *    cross-workgroup barrier (results of that call are then invalid).
+ * A workspace is 256-byte aligned and serves one call at a time: calls that overlap
+ * in time (different streams) need different workspaces.
+ */
+int deinfer_workspace_bytes(int64_t T, const deinfer_factors_t *const *pairs, int n_pairs,
+                            size_t *bytes);
+int deinfer_workspace_init(void *ws, size_t ws_bytes, void *stream);
+int deinfer_workspace_check(void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * y[T x d_out] = (x[T x d_in] . U) . V            (Sec. 2.1 Eq. 1, Sec. 4.1)
+ * One decomposed projection (also the attention O projection).  x, y have the
+ * pair's dtype; ldx >= d_in, ldy >= d_out in elements.  Accumulation is fp32; the
+ * output is rounded once (nearest-even) to the dtype.
+ * PACKED pairs additionally need x 16-byte aligned, ldx % 8 == 0, d_in % 8 == 0.
+ */
+int deinfer_lowrank_linear(const void *x, int64_t T, int64_t ldx, const deinfer_factors_t *f,
+                           void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Attention first sub-layer (Sec. 4.1): the three downward projections are applied
+ * as one concatenated product x . [U_q | U_k | U_v], reading x once; each low-rank
+ * result is then multiplied by its own upward matrix:
+ *   q = (x U_q) V_q,  k = (x U_k) V_k,  v = (x U_v) V_v.
+ * The pairs share d_in, dtype and layout; ranks and output widths may differ (GQA,
+ * per-matrix ratios).  t_k / t_v (optional, may be NULL) receive the rank-space
+ * intermediates x U_k and x U_v, T x r_k and T x r_v with pitches ldtk / ldtv:
+ * the low-rank KV cache of Sec. 2.1.
+ */
+int deinfer_lowrank_qkv(const void *x, int64_t T, int64_t ldx,
+                        const deinfer_factors_t *fq, const deinfer_factors_t *fk,
+                        const deinfer_factors_t *fv,
+                        void *q, int64_t ldq, void *k, int64_t ldk, void *v, int64_t ldv,
+                        void *t_k, int64_t ldtk, void *t_v, int64_t ldtv,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * GLU-type MLP first sub-layer (Sec. 4.1 "activation computation", Table 2 GLU-based):
+ *   h = silu((x U_g) V_g) * ((x U_u) V_u),   silu(z) = z / (1 + exp(-z)),
+ * element-wise product, evaluated in fp32 and rounded once.  Both pairs share d_in
+ * and d_out (= FFN width); the full-width gate and up results never reach memory.
+ */
+int deinfer_lowrank_gateup_silu(const void *x, int64_t T, int64_t ldx,
+                                const deinfer_factors_t *fgate, const deinfer_factors_t *fup,
+                                void *h, int64_t ldh, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * MLP second sub-layer (Sec. 4.1): y = (h U_d) V_d with d_in = FFN width.
+ * Same contract as deinfer_lowrank_linear.
+ */
+int deinfer_lowrank_down(const void *h, int64_t T, int64_t ldh, const deinfer_factors_t *fdown,
+                         void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEINFER_H */

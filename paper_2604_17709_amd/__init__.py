@@ -1,0 +1,268 @@
+"""Python binding of the gfx950 low-rank linear-layer library (``include/deinfer.h``).
+
+Argument marshalling only: every function here turns torch tensors into device
+pointers and sizes and calls the C entry point of the same name; all arithmetic runs
+in the HIP kernels of ``libdeinfer.so``.  PyTorch is used for device memory and
+streams.  There is no CPU fallback: if the shared library is missing the first call
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdeinfer.so")
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_UNSUPPORTED = -2
+ERR_MISALIGNED = -3
+ERR_WORKSPACE = -4
+ERR_DEVICE = -5
+
+F32 = 0
+BF16 = 1
+LAYOUT_RAW = 0
+LAYOUT_PACKED = 1
+
+_i64 = ctypes.c_int64
+_vp = ctypes.c_void_p
+_sz = ctypes.c_size_t
+
+
+class Factors(ctypes.Structure):
+    """Mirror of ``deinfer_factors_t``."""
+    _fields_ = [("U", _vp), ("V", _vp),
+                ("d_in", _i64), ("d_out", _i64), ("r", _i64),
+                ("ldu", _i64), ("ldv", _i64),
+                ("dtype", ctypes.c_int32), ("layout", ctypes.c_int32),
+                ("param_reduction", ctypes.c_double)]
+
+
+class DeinferError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"deinfer error {code}: {text}")
+        self.code = code
+
+
+EXPORTS = [
+    "deinfer_last_error", "deinfer_version", "deinfer_rank_for_ratio",
+    "deinfer_packed_bytes", "deinfer_pack_factors",
+    "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
+    "deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
+    "deinfer_lowrank_down",
+]
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load ``libdeinfer.so`` (built by ``python -m paper_2604_17709_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2604_17709_amd.build` (there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        FP = ctypes.POINTER(Factors)
+        L.deinfer_last_error.restype = ctypes.c_char_p
+        L.deinfer_version.restype = ctypes.c_int
+        L.deinfer_rank_for_ratio.argtypes = [_i64, _i64, ctypes.c_double, ctypes.POINTER(_i64)]
+        L.deinfer_packed_bytes.argtypes = [FP, ctypes.POINTER(_sz)]
+        L.deinfer_pack_factors.argtypes = [FP, _vp, _sz, FP, _vp]
+        L.deinfer_workspace_bytes.argtypes = [_i64, ctypes.POINTER(FP), ctypes.c_int, ctypes.POINTER(_sz)]
+        L.deinfer_workspace_init.argtypes = [_vp, _sz, _vp]
+        L.deinfer_workspace_check.argtypes = [_vp, _sz, _vp]
+        L.deinfer_lowrank_linear.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
+        L.deinfer_lowrank_down.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
+        L.deinfer_lowrank_qkv.argtypes = [_vp, _i64, _i64, FP, FP, FP,
+                                          _vp, _i64, _vp, _i64, _vp, _i64,
+                                          _vp, _i64, _vp, _i64, _vp, _sz, _vp]
+        L.deinfer_lowrank_gateup_silu.argtypes = [_vp, _i64, _i64, FP, FP, _vp, _i64, _vp, _sz, _vp]
+        for name in EXPORTS:
+            if name not in ("deinfer_last_error",):
+                getattr(L, name).restype = ctypes.c_int
+        L.deinfer_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().deinfer_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise DeinferError(rc, last_error())
+
+
+# ------------------------------------------------------------------ host-only helpers
+def deinfer_rank_for_ratio(m: int, n: int, param_reduction: float) -> int:
+    r = _i64(0)
+    _check(lib().deinfer_rank_for_ratio(m, n, float(param_reduction), ctypes.byref(r)))
+    return int(r.value)
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    h = int(stream.cuda_stream)
+    return h if h else None
+
+
+class Pair:
+    """A factor pair on the device: the ctypes descriptor plus references that keep the
+    tensors it points into alive."""
+
+    def __init__(self, desc: Factors, keep: Sequence):
+        self.desc = desc
+        self._keep = list(keep)
+
+    @property
+    def d_in(self): return int(self.desc.d_in)
+    @property
+    def d_out(self): return int(self.desc.d_out)
+    @property
+    def r(self): return int(self.desc.r)
+    @property
+    def packed(self): return self.desc.layout == LAYOUT_PACKED
+
+
+def raw_pair(U, V, param_reduction: float = 0.0) -> Pair:
+    """Describe row-major device tensors U[d_in x r], V[r x d_out] (last stride 1)."""
+    if U.dim() != 2 or V.dim() != 2 or U.shape[1] != V.shape[0]:
+        raise ValueError("U must be [d_in x r] and V [r x d_out]")
+    if U.dtype != V.dtype:
+        raise TypeError("U and V must share a dtype")
+    if (U.shape[1] and U.stride(1) != 1) or (V.shape[1] and V.stride(1) != 1):
+        raise ValueError("U and V must be row-major")
+    d = Factors()
+    d.U, d.V = _ptr(U), _ptr(V)
+    d.d_in, d.r, d.d_out = U.shape[0], U.shape[1], V.shape[1]
+    d.ldu = U.stride(0) if U.shape[0] > 1 else max(U.shape[1], 1)
+    d.ldv = V.stride(0) if V.shape[0] > 1 else max(V.shape[1], 1)
+    d.dtype = _dtype_code(U)
+    d.layout = LAYOUT_RAW
+    d.param_reduction = float(param_reduction)
+    return Pair(d, [U, V])
+
+
+def deinfer_packed_bytes(pair: Pair) -> int:
+    n = _sz(0)
+    _check(lib().deinfer_packed_bytes(ctypes.byref(pair.desc), ctypes.byref(n)))
+    return int(n.value)
+
+
+def deinfer_pack_factors(pair: Pair, stream=None) -> Pair:
+    """Re-lay a RAW bf16 pair into the packed MFMA-fragment format (device buffer owned
+    by the returned Pair)."""
+    import torch
+    nbytes = deinfer_packed_bytes(pair)
+    dev = pair._keep[0].device
+    buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    out = Factors()
+    _check(lib().deinfer_pack_factors(ctypes.byref(pair.desc), _ptr(buf), nbytes,
+                                      ctypes.byref(out), _stream(stream)))
+    return Pair(out, [buf])
+
+
+class Workspace:
+    """Caller-owned scratch for the library (rank-space intermediate + sync words)."""
+
+    def __init__(self, nbytes: int, device="cuda", stream=None):
+        import torch
+        self.nbytes = int(nbytes)
+        self.buf = torch.empty(self.nbytes, dtype=torch.uint8, device=device)
+        _check(lib().deinfer_workspace_init(_ptr(self.buf), self.nbytes, _stream(stream)))
+
+    @staticmethod
+    def bytes_for(T: int, pairs: Sequence[Pair]) -> int:
+        return deinfer_workspace_bytes(T, pairs)
+
+    def check(self, stream=None) -> None:
+        _check(lib().deinfer_workspace_check(_ptr(self.buf), self.nbytes, _stream(stream)))
+
+
+def deinfer_workspace_bytes(T: int, pairs: Sequence[Pair]) -> int:
+    FP = ctypes.POINTER(Factors)
+    arr = (FP * len(pairs))(*[ctypes.pointer(p.desc) for p in pairs])
+    n = _sz(0)
+    _check(lib().deinfer_workspace_bytes(int(T), arr, len(pairs), ctypes.byref(n)))
+    return int(n.value)
+
+
+def _ld(t) -> int:
+    return int(t.stride(0)) if t.shape[0] > 1 else max(int(t.shape[1]), 1)
+
+
+def _rows(x, what: str):
+    if x.dim() != 2 or (x.shape[1] and x.stride(1) != 1):
+        raise ValueError(f"{what} must be a row-major 2-D tensor")
+    return int(x.shape[0])
+
+
+# ------------------------------------------------------------------ the four entry points
+def deinfer_lowrank_linear(x, pair: Pair, ws: Workspace, out=None, stream=None):
+    """y = (x U) V."""
+    import torch
+    T = _rows(x, "x")
+    if out is None:
+        out = torch.empty((T, pair.d_out), dtype=x.dtype, device=x.device)
+    _check(lib().deinfer_lowrank_linear(_ptr(x), T, _ld(x), ctypes.byref(pair.desc),
+                                        _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
+    return out
+
+
+def deinfer_lowrank_down(h, pair: Pair, ws: Workspace, out=None, stream=None):
+    """y = (h U_d) V_d."""
+    import torch
+    T = _rows(h, "h")
+    if out is None:
+        out = torch.empty((T, pair.d_out), dtype=h.dtype, device=h.device)
+    _check(lib().deinfer_lowrank_down(_ptr(h), T, _ld(h), ctypes.byref(pair.desc),
+                                      _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
+    return out
+
+
+def deinfer_lowrank_qkv(x, fq: Pair, fk: Pair, fv: Pair, ws: Workspace,
+                        out=None, t_k=None, t_v=None, stream=None):
+    """q, k, v = (x U_q) V_q, (x U_k) V_k, (x U_v) V_v; optional rank-space outputs t_k, t_v."""
+    import torch
+    T = _rows(x, "x")
+    if out is None:
+        out = tuple(torch.empty((T, p.d_out), dtype=x.dtype, device=x.device) for p in (fq, fk, fv))
+    q, k, v = out
+    _check(lib().deinfer_lowrank_qkv(
+        _ptr(x), T, _ld(x), ctypes.byref(fq.desc), ctypes.byref(fk.desc), ctypes.byref(fv.desc),
+        _ptr(q), _ld(q), _ptr(k), _ld(k), _ptr(v), _ld(v),
+        _ptr(t_k), _ld(t_k) if t_k is not None else 0, _ptr(t_v), _ld(t_v) if t_v is not None else 0,
+        _ptr(ws.buf), ws.nbytes, _stream(stream)))
+    return q, k, v
+
+
+def deinfer_lowrank_gateup_silu(x, fgate: Pair, fup: Pair, ws: Workspace, out=None, stream=None):
+    """h = silu((x U_g) V_g) * ((x U_u) V_u)."""
+    import torch
+    T = _rows(x, "x")
+    if out is None:
+        out = torch.empty((T, fgate.d_out), dtype=x.dtype, device=x.device)
+    _check(lib().deinfer_lowrank_gateup_silu(_ptr(x), T, _ld(x), ctypes.byref(fgate.desc),
+                                             ctypes.byref(fup.desc), _ptr(out), _ld(out),
+                                             _ptr(ws.buf), ws.nbytes, _stream(stream)))
+    return out

@@ -1,0 +1,466 @@
+// Host side of the C ABI declared in include/deinfer.h: argument validation (host only,
+// before any device call), workspace carving, kernel selection and launch.
+#include "../../include/deinfer.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.h"
+#include "decode_kernel.h"
+#include "generic_kernels.h"
+#include "pack_kernels.h"
+#include "prefill_kernel.h"
+
+using namespace deinfer;
+
+namespace {
+
+thread_local char g_err[512] = "no error";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t elem_size(int dtype) { return dtype == DEINFER_BF16 ? 2 : 4; }
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// ---- workspace layout -------------------------------------------------------------
+// [0, 256)       barrier words: arrivals, generation, error
+// [256, 4352)    one flag word per workgroup (DEC_MAX_GRID)
+// [8192, ...)    scratch: decode slots + t (bf16), or prefill t (bf16), or generic t (fp32)
+constexpr size_t WS_HEADER = 8192;
+constexpr size_t WS_FLAGS_OFF = 256;
+
+struct Geometry {          // derived sizes of one pair
+  int64_t r_pad, KB1, KB2, n_rtiles, n_otiles;
+  size_t u_bytes, v_bytes;
+};
+Geometry geometry(const deinfer_factors_t *f) {
+  Geometry g;
+  g.r_pad = round_up(f->r, 32);
+  g.KB1 = ceil_div(f->d_in, 32);
+  g.KB2 = g.r_pad / 32;
+  g.n_rtiles = g.r_pad / 16;
+  g.n_otiles = ceil_div(f->d_out, 16);
+  g.u_bytes = (size_t)g.n_rtiles * g.KB1 * 1024;
+  g.v_bytes = (size_t)g.n_otiles * g.KB2 * 1024;
+  return g;
+}
+
+int token_tiles(int64_t T) {   // padded 16-token tiles of a decode call: 1, 2, 4 or 8
+  int nt = (int)ceil_div(T, 16);
+  return nt <= 1 ? 1 : nt <= 2 ? 2 : nt <= 4 ? 4 : 8;
+}
+
+int validate_pair(const deinfer_factors_t *f, const char *name) {
+  if (!f) return fail(DEINFER_ERR_INVALID_ARG, "%s: factor descriptor is NULL", name);
+  if (f->d_in <= 0 || f->d_out <= 0 || f->r < 0)
+    return fail(DEINFER_ERR_INVALID_ARG, "%s: bad sizes d_in=%lld d_out=%lld r=%lld", name,
+                (long long)f->d_in, (long long)f->d_out, (long long)f->r);
+  if (f->d_in > (1 << 30) || f->d_out > (1 << 30) || f->r > (1 << 30))
+    return fail(DEINFER_ERR_INVALID_ARG, "%s: sizes above 2^30 are not supported", name);
+  if (f->dtype != DEINFER_F32 && f->dtype != DEINFER_BF16)
+    return fail(DEINFER_ERR_UNSUPPORTED, "%s: unknown dtype %d", name, f->dtype);
+  if (f->layout != DEINFER_LAYOUT_RAW && f->layout != DEINFER_LAYOUT_PACKED)
+    return fail(DEINFER_ERR_UNSUPPORTED, "%s: unknown layout %d", name, f->layout);
+  if (f->r > 0 && (!f->U || !f->V)) return fail(DEINFER_ERR_INVALID_ARG, "%s: U or V is NULL", name);
+  if (f->layout == DEINFER_LAYOUT_RAW) {
+    if (f->r > 0 && (f->ldu < f->r || f->ldv < f->d_out))
+      return fail(DEINFER_ERR_INVALID_ARG, "%s: leading dimension too small (ldu=%lld r=%lld ldv=%lld d_out=%lld)",
+                  name, (long long)f->ldu, (long long)f->r, (long long)f->ldv, (long long)f->d_out);
+    if (f->r > 0 && (!aligned(f->U, elem_size(f->dtype)) || !aligned(f->V, elem_size(f->dtype))))
+      return fail(DEINFER_ERR_MISALIGNED, "%s: U / V not aligned to the element size", name);
+  } else {
+    if (f->dtype != DEINFER_BF16) return fail(DEINFER_ERR_UNSUPPORTED, "%s: packed layout is bf16 only", name);
+    if (f->r > 0 && (!aligned(f->U, 16) || !aligned(f->V, 16)))
+      return fail(DEINFER_ERR_MISALIGNED, "%s: packed U / V must be 16-byte aligned", name);
+  }
+  return DEINFER_OK;
+}
+
+size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
+  int64_t rtot = 0, rtot_pad = 0;
+  for (int i = 0; i < n; ++i) { rtot += pairs[i]->r; rtot_pad += round_up(pairs[i]->r, 32); }
+  const bool packed = pairs[0]->layout == DEINFER_LAYOUT_PACKED;
+  size_t scratch;
+  if (!packed) {
+    scratch = (size_t)T * (size_t)(rtot > 0 ? rtot : 1) * sizeof(float);
+  } else {
+    const int64_t Tc = T <= 128 ? T : 128;                       // decode-sized chunk
+    const int nt = token_tiles(Tc);
+    const size_t slots = (size_t)DEC_MAX_GRID * nt * kWave * sizeof(float4);
+    const size_t tdec = (size_t)nt * 16 * (size_t)(rtot_pad > 0 ? rtot_pad : 32) * 2;
+    const size_t tpre = T > 128 ? (size_t)round_up(T, 256) * (size_t)(rtot_pad > 0 ? rtot_pad : 32) * 2 : 0;
+    scratch = round_up((int64_t)slots, 256) + round_up((int64_t)tdec, 256) + round_up((int64_t)tpre, 256);
+  }
+  return WS_HEADER + (size_t)round_up((int64_t)scratch, 256);
+}
+
+int device_cus() {
+  static int cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return -1;
+  if (dev < 0 || dev >= 64) return -1;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+int check_launch(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(DEINFER_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+  return DEINFER_OK;
+}
+
+template <typename TC>
+int zero_output(void *y, int64_t ldy, int64_t T, int64_t n, hipStream_t s) {
+  const int64_t cnt = T * n;
+  hipLaunchKernelGGL((zero2d_kernel<TC>), dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, s,
+                     static_cast<TC *>(y), ldy, (int)T, (int)n);
+  return check_launch("zero-fill");
+}
+
+// ---- one call = a group of 1..3 pairs that share x --------------------------------
+struct Group {
+  const void *x; int64_t T, ldx;
+  int n;                                   // pairs
+  const deinfer_factors_t *f[3];
+  void *out[3]; int64_t ldo[3];            // per pair output (GLU: only [0])
+  void *t_out[3]; int64_t ldt[3];          // optional rank-space outputs
+  bool glu;
+  void *ws; size_t ws_bytes; hipStream_t stream;
+};
+
+template <int NT>
+int launch_decode_nt(const DecParams &P, bool glu, int grid, hipStream_t s) {
+  if (glu) hipLaunchKernelGGL((decode_kernel<NT, true>), dim3(grid), dim3(DEC_THREADS), 0, s, P);
+  else     hipLaunchKernelGGL((decode_kernel<NT, false>), dim3(grid), dim3(DEC_THREADS), 0, s, P);
+  return check_launch("decode kernel");
+}
+
+// Decode-sized call (T <= 128) on packed pairs; rows [row0, row0 + T) of the group's tensors.
+int run_decode(const Group &gq, int64_t row0, int64_t T) {
+  const int cus = device_cus();
+  if (cus <= 0) return fail(DEINFER_ERR_DEVICE, "no usable HIP device");
+  const int grid = cus < DEC_MAX_GRID ? cus : DEC_MAX_GRID;
+  const int nt = token_tiles(T);
+  char *ws = static_cast<char *>(gq.ws);
+  DecParams P;
+  memset(&P, 0, sizeof(P));
+  P.x = static_cast<const uint16_t *>(gq.x) + row0 * gq.ldx;
+  P.ldx = gq.ldx; P.T = (int)T; P.d_in = (int)gq.f[0]->d_in; P.KB1 = (int)ceil_div(gq.f[0]->d_in, 32);
+  P.n_pairs = gq.n;
+  int tile0 = 0, items = 0;
+  for (int i = 0; i < gq.n; ++i) {
+    const Geometry ge = geometry(gq.f[i]);
+    DecPair &d = P.p[i];
+    d.Up = static_cast<const uint4 *>(gq.f[i]->U);
+    d.Vp = static_cast<const uint4 *>(gq.f[i]->V);
+    d.y = gq.out[i] ? static_cast<uint16_t *>(gq.out[i]) + row0 * gq.ldo[i] : nullptr;
+    d.ldy = gq.ldo[i];
+    d.t_out = gq.t_out[i] ? static_cast<uint16_t *>(gq.t_out[i]) + row0 * gq.ldt[i] : nullptr;
+    d.ldt_out = gq.ldt[i];
+    d.r = (int)gq.f[i]->r; d.r_pad = (int)ge.r_pad; d.d_out = (int)gq.f[i]->d_out;
+    d.n_otiles = (int)ge.n_otiles; d.tile0 = tile0;
+    tile0 += (int)ge.n_rtiles;
+    items += (int)ge.n_otiles;
+  }
+  P.n_rtiles = tile0;
+  P.Rtot_pad = tile0 * 16;
+  P.n_items2 = gq.glu ? P.p[0].n_otiles : items;
+  const long long total = (long long)P.n_rtiles * P.KB1;
+  P.G1 = (int)(total < grid ? total : grid);
+  P.bar = reinterpret_cast<unsigned *>(ws);
+  P.flags = reinterpret_cast<unsigned *>(ws + WS_FLAGS_OFF);
+  P.slots = reinterpret_cast<float4 *>(ws + WS_HEADER);
+  const size_t slots_bytes = (size_t)round_up((int64_t)DEC_MAX_GRID * nt * kWave * sizeof(float4), 256);
+  P.t = reinterpret_cast<uint16_t *>(ws + WS_HEADER + slots_bytes);
+  switch (nt) {
+    case 1: return launch_decode_nt<1>(P, gq.glu, grid, gq.stream);
+    case 2: return launch_decode_nt<2>(P, gq.glu, grid, gq.stream);
+    case 4: return launch_decode_nt<4>(P, gq.glu, grid, gq.stream);
+    default: return launch_decode_nt<8>(P, gq.glu, grid, gq.stream);
+  }
+}
+
+template <typename TE>
+int run_generic(const Group &gq) {
+  const int64_t T = gq.T;
+  int64_t rtot = 0;
+  for (int i = 0; i < gq.n; ++i) rtot += gq.f[i]->r;
+  float *t32 = reinterpret_cast<float *>(static_cast<char *>(gq.ws) + WS_HEADER);
+  const int64_t ldt = rtot;
+  const TE *x = static_cast<const TE *>(gq.x);
+  int64_t off[3] = {0, 0, 0};
+  int64_t acc = 0;
+  for (int i = 0; i < gq.n; ++i) { off[i] = acc; acc += gq.f[i]->r; }
+  // stage 1: t[:, off_i : off_i + r_i] = x . U_i   (downward projections, Sec. 4.1)
+  for (int i = 0; i < gq.n; ++i) {
+    const deinfer_factors_t *f = gq.f[i];
+    dim3 grid((unsigned)ceil_div(f->r, GT), (unsigned)ceil_div(T, GT));
+    hipLaunchKernelGGL((gemm_generic_kernel<TE, TE, float, false>), grid, dim3(GTHREADS), 0, gq.stream,
+                       x, gq.ldx, static_cast<const TE *>(f->U), f->ldu, (int)f->d_in,
+                       (const TE *)nullptr, (int64_t)0, (const TE *)nullptr, (int64_t)0, 0,
+                       t32 + off[i], ldt, (int)T, (int)f->r);
+    if (int rc = check_launch("generic stage 1")) return rc;
+    if (gq.t_out[i]) {
+      const int64_t cnt = T * f->r;
+      hipLaunchKernelGGL((copy2d_kernel<float, TE>), dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, gq.stream,
+                         t32 + off[i], ldt, static_cast<TE *>(gq.t_out[i]), gq.ldt[i], (int)T, (int)f->r);
+      if (int rc = check_launch("rank-space copy")) return rc;
+    }
+  }
+  // stage 2: upward projections
+  if (gq.glu) {
+    const deinfer_factors_t *fg = gq.f[0], *fu = gq.f[1];
+    dim3 grid((unsigned)ceil_div(fg->d_out, GT), (unsigned)ceil_div(T, GT));
+    hipLaunchKernelGGL((gemm_generic_kernel<float, TE, TE, true>), grid, dim3(GTHREADS), 0, gq.stream,
+                       t32 + off[0], ldt, static_cast<const TE *>(fg->V), fg->ldv, (int)fg->r,
+                       t32 + off[1], ldt, static_cast<const TE *>(fu->V), fu->ldv, (int)fu->r,
+                       static_cast<TE *>(gq.out[0]), gq.ldo[0], (int)T, (int)fg->d_out);
+    return check_launch("generic GLU stage 2");
+  }
+  for (int i = 0; i < gq.n; ++i) {
+    const deinfer_factors_t *f = gq.f[i];
+    dim3 grid((unsigned)ceil_div(f->d_out, GT), (unsigned)ceil_div(T, GT));
+    hipLaunchKernelGGL((gemm_generic_kernel<float, TE, TE, false>), grid, dim3(GTHREADS), 0, gq.stream,
+                       t32 + off[i], ldt, static_cast<const TE *>(f->V), f->ldv, (int)f->r,
+                       (const float *)nullptr, (int64_t)0, (const TE *)nullptr, (int64_t)0, 0,
+                       static_cast<TE *>(gq.out[i]), gq.ldo[i], (int)T, (int)f->d_out);
+    if (int rc = check_launch("generic stage 2")) return rc;
+  }
+  return DEINFER_OK;
+}
+
+// The compute-bound path (T > 128) lives in its own file; it uses Group and the helpers above.
+#include "prefill_host.inc"
+
+int run_group(Group gq) {
+  // ---- validation (host only)
+  if (gq.T < 0) return fail(DEINFER_ERR_INVALID_ARG, "T is negative");
+  for (int i = 0; i < gq.n; ++i) {
+    static const char *names[3] = {"pair 0", "pair 1", "pair 2"};
+    if (int rc = validate_pair(gq.f[i], names[i])) return rc;
+    if (gq.f[i]->d_in != gq.f[0]->d_in || gq.f[i]->dtype != gq.f[0]->dtype || gq.f[i]->layout != gq.f[0]->layout)
+      return fail(DEINFER_ERR_INVALID_ARG, "pairs of one call must share d_in, dtype and layout");
+  }
+  if (gq.glu && gq.f[0]->d_out != gq.f[1]->d_out)
+    return fail(DEINFER_ERR_INVALID_ARG, "gate and up must have the same output width");
+  if (gq.T == 0) return DEINFER_OK;
+  const int dtype = gq.f[0]->dtype;
+  const size_t es = elem_size(dtype);
+  if (!gq.x) return fail(DEINFER_ERR_INVALID_ARG, "activation pointer is NULL");
+  if (gq.ldx < gq.f[0]->d_in) return fail(DEINFER_ERR_INVALID_ARG, "ldx smaller than d_in");
+  if (!aligned(gq.x, es)) return fail(DEINFER_ERR_MISALIGNED, "activation pointer not aligned to the element size");
+  const int n_out = gq.glu ? 1 : gq.n;
+  for (int i = 0; i < n_out; ++i) {
+    if (!gq.out[i]) return fail(DEINFER_ERR_INVALID_ARG, "output pointer %d is NULL", i);
+    if (gq.ldo[i] < gq.f[i]->d_out) return fail(DEINFER_ERR_INVALID_ARG, "output %d: leading dimension smaller than d_out", i);
+    if (!aligned(gq.out[i], es)) return fail(DEINFER_ERR_MISALIGNED, "output %d not aligned to the element size", i);
+  }
+  for (int i = 0; i < gq.n; ++i)
+    if (gq.t_out[i]) {
+      if (gq.ldt[i] < gq.f[i]->r) return fail(DEINFER_ERR_INVALID_ARG, "rank-space output %d: leading dimension smaller than r", i);
+      if (!aligned(gq.t_out[i], es)) return fail(DEINFER_ERR_MISALIGNED, "rank-space output %d misaligned", i);
+    }
+  if (!gq.ws) return fail(DEINFER_ERR_WORKSPACE, "workspace pointer is NULL");
+  if (!aligned(gq.ws, 256)) return fail(DEINFER_ERR_MISALIGNED, "workspace must be 256-byte aligned");
+  const size_t need = workspace_need(gq.T, gq.f, gq.n);
+  if (gq.ws_bytes < need)
+    return fail(DEINFER_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", gq.ws_bytes, need);
+  const bool packed = gq.f[0]->layout == DEINFER_LAYOUT_PACKED;
+  if (packed) {
+    if (!aligned(gq.x, 16) || gq.ldx % 8 != 0 || gq.f[0]->d_in % 8 != 0)
+      return fail(DEINFER_ERR_MISALIGNED,
+                  "packed pairs need 16-byte aligned activations, ldx %% 8 == 0 and d_in %% 8 == 0");
+  }
+
+  // ---- pairs of rank 0: the output is exactly zero (empty sum)
+  bool any_zero = false;
+  for (int i = 0; i < gq.n; ++i) any_zero |= (gq.f[i]->r == 0);
+  if (any_zero) {
+    if (gq.glu) {   // silu(0) * u == 0 and silu(g) * 0 == 0
+      return dtype == DEINFER_BF16 ? zero_output<uint16_t>(gq.out[0], gq.ldo[0], gq.T, gq.f[0]->d_out, gq.stream)
+                                   : zero_output<float>(gq.out[0], gq.ldo[0], gq.T, gq.f[0]->d_out, gq.stream);
+    }
+    Group rest = gq;
+    rest.n = 0;
+    for (int i = 0; i < gq.n; ++i) {
+      if (gq.f[i]->r == 0) {
+        int rc = dtype == DEINFER_BF16 ? zero_output<uint16_t>(gq.out[i], gq.ldo[i], gq.T, gq.f[i]->d_out, gq.stream)
+                                       : zero_output<float>(gq.out[i], gq.ldo[i], gq.T, gq.f[i]->d_out, gq.stream);
+        if (rc) return rc;
+      } else {
+        rest.f[rest.n] = gq.f[i]; rest.out[rest.n] = gq.out[i]; rest.ldo[rest.n] = gq.ldo[i];
+        rest.t_out[rest.n] = gq.t_out[i]; rest.ldt[rest.n] = gq.ldt[i];
+        ++rest.n;
+      }
+    }
+    if (rest.n == 0) return DEINFER_OK;
+    gq = rest;
+  }
+
+  // ---- dispatch
+  if (!packed) return dtype == DEINFER_BF16 ? run_generic<uint16_t>(gq) : run_generic<float>(gq);
+  if (gq.T <= 128) return run_decode(gq, 0, gq.T);
+  return run_prefill(gq);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *deinfer_last_error(void) { return g_err; }
+
+int deinfer_version(void) { return 1000; }
+
+int deinfer_rank_for_ratio(int64_t m, int64_t n, double param_reduction, int64_t *r_out) {
+  if (!r_out) return fail(DEINFER_ERR_INVALID_ARG, "r_out is NULL");
+  if (m <= 0 || n <= 0) return fail(DEINFER_ERR_INVALID_ARG, "m and n must be positive");
+  if (!(param_reduction >= 0.0 && param_reduction <= 1.0))
+    return fail(DEINFER_ERR_INVALID_ARG, "param_reduction must lie in [0, 1]");
+  const long long keep_ppm = llround((1.0 - param_reduction) * 1.0e6);
+  const __int128 num = (__int128)keep_ppm * (__int128)m * (__int128)n;
+  const __int128 den = (__int128)1000000 * ((__int128)m + (__int128)n);
+  *r_out = (int64_t)(num / den);
+  return DEINFER_OK;
+}
+
+int deinfer_packed_bytes(const deinfer_factors_t *raw, size_t *bytes) {
+  if (!bytes) return fail(DEINFER_ERR_INVALID_ARG, "bytes is NULL");
+  if (!raw) return fail(DEINFER_ERR_INVALID_ARG, "raw descriptor is NULL");
+  if (raw->d_in <= 0 || raw->d_out <= 0 || raw->r < 0) return fail(DEINFER_ERR_INVALID_ARG, "bad sizes");
+  const Geometry g = geometry(raw);
+  *bytes = (size_t)round_up((int64_t)g.u_bytes, 256) + (size_t)round_up((int64_t)g.v_bytes, 256);
+  return DEINFER_OK;
+}
+
+int deinfer_pack_factors(const deinfer_factors_t *raw, void *dst, size_t dst_bytes,
+                         deinfer_factors_t *packed, void *stream) {
+  if (int rc = validate_pair(raw, "raw")) return rc;
+  if (!packed) return fail(DEINFER_ERR_INVALID_ARG, "packed descriptor is NULL");
+  if (raw->layout != DEINFER_LAYOUT_RAW) return fail(DEINFER_ERR_INVALID_ARG, "source pair is not in RAW layout");
+  if (raw->dtype != DEINFER_BF16) return fail(DEINFER_ERR_UNSUPPORTED, "only bf16 pairs can be packed");
+  size_t need = 0;
+  deinfer_packed_bytes(raw, &need);
+  if (need > 0 && !dst) return fail(DEINFER_ERR_INVALID_ARG, "dst is NULL");
+  if (!aligned(dst, 256)) return fail(DEINFER_ERR_MISALIGNED, "dst must be 256-byte aligned");
+  if (dst_bytes < need) return fail(DEINFER_ERR_WORKSPACE, "dst too small: %zu bytes given, %zu needed", dst_bytes, need);
+  const Geometry g = geometry(raw);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char *d = static_cast<char *>(dst);
+  uint4 *du = reinterpret_cast<uint4 *>(d);
+  uint4 *dv = reinterpret_cast<uint4 *>(d + round_up((int64_t)g.u_bytes, 256));
+  if (raw->r > 0) {
+    // U: source [d_in x r], k = d_in, features = r (zero-padded to r_pad)
+    int64_t n = g.n_rtiles * g.KB1 * 64;
+    hipLaunchKernelGGL(pack_fragments_kernel, dim3((unsigned)(ceil_div(n, 256) < 65535 ? ceil_div(n, 256) : 65535)), dim3(256), 0, s,
+                       static_cast<const uint16_t *>(raw->U), raw->ldu, (int)raw->d_in, (int)raw->r,
+                       (int)g.n_rtiles, (int)g.KB1, du);
+    if (int rc = check_launch("pack U")) return rc;
+    // V: source [r x d_out], k = r (zero-padded), features = d_out
+    n = g.n_otiles * g.KB2 * 64;
+    hipLaunchKernelGGL(pack_fragments_kernel, dim3((unsigned)(ceil_div(n, 256) < 65535 ? ceil_div(n, 256) : 65535)), dim3(256), 0, s,
+                       static_cast<const uint16_t *>(raw->V), raw->ldv, (int)raw->r, (int)raw->d_out,
+                       (int)g.n_otiles, (int)g.KB2, dv);
+    if (int rc = check_launch("pack V")) return rc;
+  }
+  *packed = *raw;
+  packed->U = du;
+  packed->V = dv;
+  packed->ldu = 0;
+  packed->ldv = 0;
+  packed->layout = DEINFER_LAYOUT_PACKED;
+  return DEINFER_OK;
+}
+
+int deinfer_workspace_bytes(int64_t T, const deinfer_factors_t *const *pairs, int n_pairs, size_t *bytes) {
+  if (!bytes) return fail(DEINFER_ERR_INVALID_ARG, "bytes is NULL");
+  if (T < 0) return fail(DEINFER_ERR_INVALID_ARG, "T is negative");
+  if (!pairs || n_pairs < 1 || n_pairs > 3) return fail(DEINFER_ERR_INVALID_ARG, "need 1..3 pairs");
+  for (int i = 0; i < n_pairs; ++i) {
+    if (!pairs[i]) return fail(DEINFER_ERR_INVALID_ARG, "pair %d is NULL", i);
+    if (pairs[i]->r < 0 || pairs[i]->d_in <= 0 || pairs[i]->d_out <= 0) return fail(DEINFER_ERR_INVALID_ARG, "pair %d: bad sizes", i);
+  }
+  *bytes = workspace_need(T, pairs, n_pairs);
+  return DEINFER_OK;
+}
+
+int deinfer_workspace_init(void *ws, size_t ws_bytes, void *stream) {
+  if (!ws) return fail(DEINFER_ERR_WORKSPACE, "workspace pointer is NULL");
+  if (!aligned(ws, 256)) return fail(DEINFER_ERR_MISALIGNED, "workspace must be 256-byte aligned");
+  if (ws_bytes < WS_HEADER) return fail(DEINFER_ERR_WORKSPACE, "workspace smaller than its header (%zu bytes)", WS_HEADER);
+  const size_t words = WS_HEADER / 4;
+  hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)ceil_div((int64_t)words, 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<uint32_t *>(ws), words, 0u);
+  return check_launch("workspace init");
+}
+
+int deinfer_workspace_check(void *ws, size_t ws_bytes, void *stream) {
+  if (!ws) return fail(DEINFER_ERR_WORKSPACE, "workspace pointer is NULL");
+  if (ws_bytes < WS_HEADER) return fail(DEINFER_ERR_WORKSPACE, "workspace smaller than its header");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (hipStreamSynchronize(s) != hipSuccess) return fail(DEINFER_ERR_DEVICE, "stream synchronise failed");
+  unsigned words[4] = {0, 0, 0, 0};
+  if (hipMemcpy(words, ws, sizeof(words), hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(DEINFER_ERR_DEVICE, "reading the workspace status failed");
+  if (words[2] != 0) return fail(DEINFER_ERR_DEVICE, "a kernel abandoned its cross-workgroup wait; re-run deinfer_workspace_init");
+  return DEINFER_OK;
+}
+
+int deinfer_lowrank_linear(const void *x, int64_t T, int64_t ldx, const deinfer_factors_t *f,
+                           void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream) {
+  Group g;
+  memset(&g, 0, sizeof(g));
+  g.x = x; g.T = T; g.ldx = ldx; g.n = 1; g.f[0] = f; g.out[0] = y; g.ldo[0] = ldy;
+  g.glu = false; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
+  return run_group(g);
+}
+
+int deinfer_lowrank_down(const void *h, int64_t T, int64_t ldh, const deinfer_factors_t *fdown,
+                         void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream) {
+  return deinfer_lowrank_linear(h, T, ldh, fdown, y, ldy, ws, ws_bytes, stream);
+}
+
+int deinfer_lowrank_qkv(const void *x, int64_t T, int64_t ldx,
+                        const deinfer_factors_t *fq, const deinfer_factors_t *fk, const deinfer_factors_t *fv,
+                        void *q, int64_t ldq, void *k, int64_t ldk, void *v, int64_t ldv,
+                        void *t_k, int64_t ldtk, void *t_v, int64_t ldtv,
+                        void *ws, size_t ws_bytes, void *stream) {
+  Group g;
+  memset(&g, 0, sizeof(g));
+  g.x = x; g.T = T; g.ldx = ldx; g.n = 3;
+  g.f[0] = fq; g.f[1] = fk; g.f[2] = fv;
+  g.out[0] = q; g.out[1] = k; g.out[2] = v;
+  g.ldo[0] = ldq; g.ldo[1] = ldk; g.ldo[2] = ldv;
+  g.t_out[1] = t_k; g.ldt[1] = ldtk; g.t_out[2] = t_v; g.ldt[2] = ldtv;
+  g.glu = false; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
+  return run_group(g);
+}
+
+int deinfer_lowrank_gateup_silu(const void *x, int64_t T, int64_t ldx,
+                                const deinfer_factors_t *fgate, const deinfer_factors_t *fup,
+                                void *h, int64_t ldh, void *ws, size_t ws_bytes, void *stream) {
+  Group g;
+  memset(&g, 0, sizeof(g));
+  g.x = x; g.T = T; g.ldx = ldx; g.n = 2;
+  g.f[0] = fgate; g.f[1] = fup;
+  g.out[0] = h; g.ldo[0] = ldh;
+  g.glu = true; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
+  return run_group(g);
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Generic (any size, any alignment) kernels for RAW-layout factor pairs, fp32 or bf16
+// storage with fp32 accumulation.  Plain LDS-tiled FMA GEMM on row-major operands:
+//   C[M x N] = A[M x K] . B[K x N]            (one stage of y = (x U) V, Sec. 4.1)
+// and, for the GLU sub-layer, C = silu(A1 . B1) * (A2 . B2) in one pass.
+// These kernels are the correctness baseline of the library (small fp32 case, odd
+// shapes); the packed MFMA kernels are the fast path.
+#pragma once
+#include "common.h"
+
+namespace deinfer {
+
+constexpr int GT = 64;   // output tile edge
+constexpr int GK = 16;   // k step
+constexpr int GTHREADS = 256;
+
+// Accumulate a 64x64 tile of A.B into acc (4x4 per thread).
+template <typename TA, typename TB>
+__device__ __forceinline__ void tile_gemm_rr(const TA *__restrict__ A, int64_t lda,
+                                             const TB *__restrict__ B, int64_t ldb,
+                                             int M, int N, int K, int m0, int n0,
+                                             float (&acc)[4][4], float (*sA)[GT + 1], float (*sB)[GT]) {
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;
+  for (int k0 = 0; k0 < K; k0 += GK) {
+    // A tile: 64 rows x 16 k  -> sA[k][row]
+#pragma unroll
+    for (int i = 0; i < (GT * GK) / GTHREADS; ++i) {
+      int idx = tid + i * GTHREADS;
+      int r = idx / GK, c = idx % GK;
+      int gr = m0 + r, gc = k0 + c;
+      sA[c][r] = (gr < M && gc < K) ? Elem<TA>::load(A + (int64_t)gr * lda + gc) : 0.0f;
+    }
+    // B tile: 16 k x 64 cols -> sB[k][col]
+#pragma unroll
+    for (int i = 0; i < (GT * GK) / GTHREADS; ++i) {
+      int idx = tid + i * GTHREADS;
+      int r = idx / GT, c = idx % GT;
+      int gr = k0 + r, gc = n0 + c;
+      sB[r][c] = (gr < K && gc < N) ? Elem<TB>::load(B + (int64_t)gr * ldb + gc) : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < GK; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = sA[kk][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = sB[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+}
+
+// C = A.B, or (DUAL) C = silu(A.B) * (A2.B2).  Grid: (ceil(N/64), ceil(M/64)).
+template <typename TA, typename TB, typename TC, bool DUAL>
+__global__ __launch_bounds__(GTHREADS) void gemm_generic_kernel(
+    const TA *__restrict__ A, int64_t lda, const TB *__restrict__ B, int64_t ldb, int K,
+    const TA *__restrict__ A2, int64_t lda2, const TB *__restrict__ B2, int64_t ldb2, int K2,
+    TC *__restrict__ C, int64_t ldc, int M, int N) {
+  __shared__ float sA[GK][GT + 1];
+  __shared__ float sB[GK][GT];
+  const int m0 = blockIdx.y * GT, n0 = blockIdx.x * GT;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float acc[4][4] = {};
+  tile_gemm_rr<TA, TB>(A, lda, B, ldb, M, N, K, m0, n0, acc, sA, sB);
+  float acc2[4][4] = {};
+  if (DUAL) tile_gemm_rr<TA, TB>(A2, lda2, B2, ldb2, M, N, K2, m0, n0, acc2, sA, sB);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int r = m0 + ty * 4 + i;
+    if (r >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int c = n0 + tx * 4 + j;
+      if (c >= N) continue;
+      float v = acc[i][j];
+      if (DUAL) v = (v / (1.0f + expf(-v))) * acc2[i][j];
+      Elem<TC>::store(C + (int64_t)r * ldc + c, v);
+    }
+  }
+}
+
+// Zero-fill of a strided 2-D region (r == 0 outputs) and of raw words (workspace init).
+template <typename TC>
+__global__ void zero2d_kernel(TC *C, int64_t ldc, int M, int N) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < (int64_t)M * N) C[(i / N) * ldc + (i % N)] = TC(0);
+}
+__global__ void fill_words_kernel(uint32_t *p, size_t n, uint32_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// Copy a column block of a row-major matrix (used to hand out the rank-space
+// intermediates of k and v, the low-rank KV cache of Sec. 2.1).
+template <typename TS, typename TD>
+__global__ void copy2d_kernel(const TS *S, int64_t lds, TD *D, int64_t ldd, int M, int N) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < (int64_t)M * N) {
+    int64_t r = i / N, c = i % N;
+    Elem<TD>::store(D + r * ldd + c, Elem<TS>::load(S + r * lds + c));
+  }
+}
+
+}  // namespace deinfer

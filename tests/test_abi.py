@@ -1,0 +1,140 @@
+"""Host-side tests of the C-ABI library: it loads, exports every declared symbol, and
+rejects bad arguments on the host before touching a device (no GPU needed, and no call
+here ever reaches a kernel launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2604_17709_amd as dn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000000        # 256-byte aligned, never dereferenced: every call below fails validation first
+
+
+def make(d_in=64, d_out=48, r=16, dtype=dn.BF16, layout=dn.LAYOUT_RAW, U=FAKE, V=FAKE + 0x100000, ldu=None, ldv=None):
+    f = dn.Factors()
+    f.U, f.V = U, V
+    f.d_in, f.d_out, f.r = d_in, d_out, r
+    f.ldu = r if ldu is None else ldu
+    f.ldv = d_out if ldv is None else ldv
+    f.dtype, f.layout = dtype, layout
+    return f
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "deinfer.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(deinfer_[a-z_]+)\s*\(", header))
+    assert {"deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
+            "deinfer_lowrank_down"} <= declared
+    L = ctypes.CDLL(dn.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(L, name), name
+    assert declared == set(dn.EXPORTS)
+    assert dn.lib().deinfer_version() >= 1000
+
+
+def test_rank_for_ratio_matches_golden_table():
+    path = os.path.join(ROOT, "tests", "golden", "benchmark_ranks.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        m, n, a, b, r = map(int, line.split())
+        assert dn.deinfer_rank_for_ratio(m, n, 1.0 - a / b) == r
+    assert dn.deinfer_rank_for_ratio(64, 64, 0.0) == 32
+    assert dn.deinfer_rank_for_ratio(64, 64, 1.0) == 0
+    for bad in [(0, 4, 0.5), (4, -1, 0.5), (4, 4, 1.5), (4, 4, -0.1), (4, 4, float("nan"))]:
+        with pytest.raises(dn.DeinferError) as e:
+            dn.deinfer_rank_for_ratio(*bad)
+        assert e.value.code == dn.ERR_INVALID_ARG
+    assert dn.lib().deinfer_rank_for_ratio(4, 4, 0.5, None) == dn.ERR_INVALID_ARG
+
+
+def _linear(f, x=FAKE + 0x200000, T=4, ldx=None, y=FAKE + 0x300000, ldy=None, ws=FAKE + 0x400000, ws_bytes=1 << 26):
+    return dn.lib().deinfer_lowrank_linear(x, T, f.d_in if ldx is None else ldx, ctypes.byref(f),
+                                           y, f.d_out if ldy is None else ldy, ws, ws_bytes, None)
+
+
+def test_linear_argument_validation():
+    L = dn.lib()
+    assert L.deinfer_lowrank_linear(FAKE, 4, 64, None, FAKE, 48, FAKE, 1 << 20, None) == dn.ERR_INVALID_ARG
+    assert "NULL" in dn.last_error()
+    assert _linear(make(d_in=0)) == dn.ERR_INVALID_ARG
+    assert _linear(make(r=-1)) == dn.ERR_INVALID_ARG
+    assert _linear(make(dtype=7)) == dn.ERR_UNSUPPORTED
+    assert _linear(make(layout=9)) == dn.ERR_UNSUPPORTED
+    assert _linear(make(U=None)) == dn.ERR_INVALID_ARG
+    assert _linear(make(ldu=8)) == dn.ERR_INVALID_ARG           # ldu < r
+    assert _linear(make(ldv=8)) == dn.ERR_INVALID_ARG           # ldv < d_out
+    assert _linear(make(), T=-1) == dn.ERR_INVALID_ARG
+    assert _linear(make(), x=None) == dn.ERR_INVALID_ARG
+    assert _linear(make(), y=None) == dn.ERR_INVALID_ARG
+    assert _linear(make(), ldx=10) == dn.ERR_INVALID_ARG
+    assert _linear(make(), ldy=10) == dn.ERR_INVALID_ARG
+    assert _linear(make(), ws=None) == dn.ERR_WORKSPACE
+    assert _linear(make(), ws_bytes=64) == dn.ERR_WORKSPACE
+    assert "needed" in dn.last_error()
+    assert _linear(make(), ws=FAKE + 0x400010) == dn.ERR_MISALIGNED
+    assert _linear(make(U=FAKE + 1)) == dn.ERR_MISALIGNED
+    assert _linear(make(dtype=dn.F32, layout=dn.LAYOUT_PACKED)) == dn.ERR_UNSUPPORTED   # packed is bf16 only
+    assert _linear(make(layout=dn.LAYOUT_PACKED), x=FAKE + 0x200002) == dn.ERR_MISALIGNED
+    assert _linear(make(layout=dn.LAYOUT_PACKED, d_in=60), ldx=60) == dn.ERR_MISALIGNED   # d_in % 8
+    assert _linear(make(layout=dn.LAYOUT_PACKED), ldx=68) == dn.ERR_MISALIGNED           # ldx % 8
+    # T == 0 is a successful no-op (checked after the descriptor, before any pointer use)
+    assert _linear(make(), T=0, x=None, y=None, ws=None, ws_bytes=0) == dn.OK
+
+
+def test_group_calls_validate_shared_properties():
+    L = dn.lib()
+    fq, fk, fv = make(), make(d_out=16, r=8), make(d_out=16, r=8)
+    args = lambda a, b, c: (FAKE, 4, 64, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                            FAKE, 48, FAKE, 16, FAKE, 16, None, 0, None, 0, FAKE, 1 << 26, None)
+    assert L.deinfer_lowrank_qkv(*args(fq, fk, make(d_in=32, d_out=16, r=8))) == dn.ERR_INVALID_ARG
+    assert "share" in dn.last_error()
+    assert L.deinfer_lowrank_qkv(*args(fq, fk, make(d_out=16, r=8, dtype=dn.F32))) == dn.ERR_INVALID_ARG
+    bad_t = (FAKE, 4, 64, ctypes.byref(fq), ctypes.byref(fk), ctypes.byref(fv),
+             FAKE, 48, FAKE, 16, FAKE, 16, FAKE, 4, None, 0, FAKE, 1 << 26, None)     # ldtk < r_k
+    assert L.deinfer_lowrank_qkv(*bad_t) == dn.ERR_INVALID_ARG
+    g, u = make(d_out=96), make(d_out=80)
+    assert L.deinfer_lowrank_gateup_silu(FAKE, 4, 64, ctypes.byref(g), ctypes.byref(u),
+                                         FAKE, 96, FAKE, 1 << 26, None) == dn.ERR_INVALID_ARG
+    assert "same output width" in dn.last_error()
+    assert L.deinfer_lowrank_down(FAKE, 4, 64, None, FAKE, 48, FAKE, 1 << 26, None) == dn.ERR_INVALID_ARG
+
+
+def test_pack_and_workspace_queries_are_host_only():
+    L = dn.lib()
+    n = ctypes.c_size_t(0)
+    f = make(d_in=4096, d_out=4096, r=1638)
+    assert L.deinfer_packed_bytes(ctypes.byref(f), ctypes.byref(n)) == dn.OK
+    # r padded to 1664: U image 104 tiles x 128 k-blocks KiB, V image 256 tiles x 52 k-blocks KiB
+    assert n.value == (104 * 128 + 256 * 52) * 1024
+    assert L.deinfer_packed_bytes(ctypes.byref(f), None) == dn.ERR_INVALID_ARG
+    assert L.deinfer_packed_bytes(None, ctypes.byref(n)) == dn.ERR_INVALID_ARG
+    out = dn.Factors()
+    assert L.deinfer_pack_factors(ctypes.byref(f), FAKE, 16, ctypes.byref(out), None) == dn.ERR_WORKSPACE
+    assert L.deinfer_pack_factors(ctypes.byref(f), FAKE + 8, 1 << 30, ctypes.byref(out), None) == dn.ERR_MISALIGNED
+    assert L.deinfer_pack_factors(ctypes.byref(make(dtype=dn.F32)), FAKE, 1 << 30, ctypes.byref(out), None) == dn.ERR_UNSUPPORTED
+    assert L.deinfer_pack_factors(ctypes.byref(f), FAKE, 1 << 30, None, None) == dn.ERR_INVALID_ARG
+
+    FP = ctypes.POINTER(dn.Factors)
+    arr = (FP * 1)(ctypes.pointer(f))
+    assert L.deinfer_workspace_bytes(8, arr, 1, ctypes.byref(n)) == dn.OK and n.value > 8192
+    small = n.value
+    assert L.deinfer_workspace_bytes(4096, arr, 1, ctypes.byref(n)) == dn.OK and n.value >= small
+    assert L.deinfer_workspace_bytes(8, arr, 0, ctypes.byref(n)) == dn.ERR_INVALID_ARG
+    assert L.deinfer_workspace_bytes(-1, arr, 1, ctypes.byref(n)) == dn.ERR_INVALID_ARG
+    assert L.deinfer_workspace_bytes(8, None, 1, ctypes.byref(n)) == dn.ERR_INVALID_ARG
+    assert L.deinfer_workspace_init(None, 1 << 20, None) == dn.ERR_WORKSPACE
+    assert L.deinfer_workspace_init(FAKE, 16, None) == dn.ERR_WORKSPACE
+    assert L.deinfer_workspace_init(FAKE + 4, 1 << 20, None) == dn.ERR_MISALIGNED
+    assert L.deinfer_workspace_check(None, 1 << 20, None) == dn.ERR_WORKSPACE
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(dn, "_lib", None)
+    monkeypatch.setattr(dn, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        dn.lib()

@@ -1,0 +1,191 @@
+"""GPU parity: every entry point of the C ABI against the fp64 oracle, element by element,
+on seeded inputs.  Gate: max|y - ref| / max|ref| <= 1e-2 for bf16 storage (fp32 accumulate,
+bf16 rank-space intermediate on the packed path) and <= 1e-5 for fp32."""
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+from gpu_util import TOL, max_err, pair, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dn():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2604_17709_amd as dn
+    dn.lib()
+    return dn
+
+
+def ws_for(dn, T, pairs):
+    return dn.Workspace(dn.deinfer_workspace_bytes(T, pairs))
+
+
+def gen(seed, T, d_in, r, d_out, dtype, stream0=1):
+    x = si.make(seed, stream0, (T, d_in), 1.0, dtype)
+    U = si.make(seed, stream0 + 1, (d_in, r), 1.0 / np.sqrt(d_in), dtype)
+    V = si.make(seed, stream0 + 2, (r, d_out), 1.0 / np.sqrt(max(r, 1)), dtype)
+    return x, U, V
+
+
+# ------------------------------------------------------------------ the small fp32 case
+def test_single_linear_fp32(dn):
+    x, U, V = si.single_linear_f32(seed=0)            # 16 x 512, r = 64, 512 outputs
+    p, keep = pair(dn, U, V, packed=False)
+    ws = ws_for(dn, 16, [p])
+    y = dn.deinfer_lowrank_linear(to_dev(x), p, ws)
+    ref = oracle.lowrank_linear(x.values, U.values, V.values)
+    assert max_err(to_host(y), ref) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T,d_in,r,d_out", [(1, 7, 3, 5), (5, 33, 9, 17), (70, 130, 65, 129), (64, 64, 1, 64)])
+def test_linear_raw_odd_shapes(dn, dtype, T, d_in, r, d_out):
+    x, U, V = gen(3, T, d_in, r, d_out, dtype)
+    p, keep = pair(dn, U, V, packed=False)
+    ws = ws_for(dn, T, [p])
+    y = dn.deinfer_lowrank_linear(to_dev(x), p, ws)
+    ref = oracle.lowrank_linear(x.values, U.values, V.values)
+    assert max_err(to_host(y), ref) <= TOL[dtype]
+    y2 = dn.deinfer_lowrank_down(to_dev(x), p, ws)
+    assert np.array_equal(to_host(y2), to_host(y))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_group_calls_raw(dn, dtype):
+    import torch
+    T, d_in = 37, 72
+    x = si.make(5, 1, (T, d_in), 1.0, dtype)
+    shapes = {"q": (24, 72), "k": (10, 40), "v": (13, 40), "g": (20, 100), "u": (28, 100)}
+    F, host = {}, {}
+    for i, (n, (r, d_out)) in enumerate(shapes.items()):
+        U = si.make(5, 10 + 2 * i, (d_in, r), 1.0 / np.sqrt(d_in), dtype)
+        V = si.make(5, 11 + 2 * i, (r, d_out), 1.0 / np.sqrt(r), dtype)
+        F[n], _k = pair(dn, U, V, packed=False)
+        host[n] = (U.values, V.values, _k)
+    xd = to_dev(x)
+    ws = ws_for(dn, T, [F["q"], F["k"], F["v"]])
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tk = torch.zeros((T, 10), dtype=tdt, device="cuda")
+    tv = torch.zeros((T, 13), dtype=tdt, device="cuda")
+    q, k, v = dn.deinfer_lowrank_qkv(xd, F["q"], F["k"], F["v"], ws, t_k=tk, t_v=tv)
+    rq, rk, rv, rtk, rtv = oracle.lowrank_qkv(x.values, *host["q"][:2], *host["k"][:2], *host["v"][:2], return_t=True)
+    for got, ref in ((q, rq), (k, rk), (v, rv), (tk, rtk), (tv, rtv)):
+        assert max_err(to_host(got), ref) <= TOL[dtype]
+    ws2 = ws_for(dn, T, [F["g"], F["u"]])
+    h = dn.deinfer_lowrank_gateup_silu(xd, F["g"], F["u"], ws2)
+    rh = oracle.lowrank_gateup_silu(x.values, *host["g"][:2], *host["u"][:2])
+    assert max_err(to_host(h), rh) <= TOL[dtype]
+
+
+# ------------------------------------------------------------------ packed bf16, decode-sized
+DECODE_T = [1, 5, 16, 17, 33, 64, 100, 128]
+
+
+@pytest.mark.parametrize("T", DECODE_T)
+@pytest.mark.parametrize("d_in,r,d_out", [(96, 40, 72), (512, 130, 200), (2048, 96, 48)])
+def test_linear_packed_decode(dn, T, d_in, r, d_out):
+    x, U, V = gen(11, T, d_in, r, d_out, "bf16")
+    p, keep = pair(dn, U, V, packed=True)
+    ws = ws_for(dn, T, [p])
+    xd = to_dev(x)
+    y = dn.deinfer_lowrank_linear(xd, p, ws)
+    ref = oracle.lowrank_linear(x.values, U.values, V.values)
+    assert max_err(to_host(y), ref) <= TOL["bf16"]
+    # same workspace, second call: the sync words must have been left clean; result is deterministic
+    y2 = dn.deinfer_lowrank_linear(xd, p, ws)
+    ws.check()
+    assert np.array_equal(to_host(y2), to_host(y))
+
+
+@pytest.mark.parametrize("T", [1, 8, 40, 128])
+def test_group_calls_packed_decode(dn, T):
+    import torch
+    d_in = 256
+    x = si.make(6, 1, (T, d_in), 1.0, "bf16")
+    shapes = {"q": (70, 256), "k": (24, 64), "v": (40, 64), "g": (100, 600), "u": (90, 600), "d": (33, 120)}
+    F, host = {}, {}
+    for i, (n, (r, d_out)) in enumerate(shapes.items()):
+        U = si.make(6, 10 + 2 * i, (d_in, r), 1.0 / np.sqrt(d_in), "bf16")
+        V = si.make(6, 11 + 2 * i, (r, d_out), 1.0 / np.sqrt(r), "bf16")
+        F[n], _k = pair(dn, U, V, packed=True)
+        host[n] = (U.values, V.values)
+    xd = to_dev(x)
+    ws = dn.Workspace(max(dn.deinfer_workspace_bytes(T, [F["q"], F["k"], F["v"]]),
+                          dn.deinfer_workspace_bytes(T, [F["g"], F["u"]])))
+    tk = torch.zeros((T, 24), dtype=torch.bfloat16, device="cuda")
+    tv = torch.zeros((T, 40), dtype=torch.bfloat16, device="cuda")
+    q, k, v = dn.deinfer_lowrank_qkv(xd, F["q"], F["k"], F["v"], ws, t_k=tk, t_v=tv)
+    h = dn.deinfer_lowrank_gateup_silu(xd, F["g"], F["u"], ws)
+    y = dn.deinfer_lowrank_down(xd, F["d"], ws)
+    ws.check()
+    rq, rk, rv, rtk, rtv = oracle.lowrank_qkv(x.values, *host["q"], *host["k"], *host["v"], return_t=True)
+    for got, ref in ((q, rq), (k, rk), (v, rv), (tk, rtk), (tv, rtv)):
+        assert max_err(to_host(got), ref) <= TOL["bf16"]
+    assert max_err(to_host(h), oracle.lowrank_gateup_silu(x.values, *host["g"], *host["u"])) <= TOL["bf16"]
+    assert max_err(to_host(y), oracle.lowrank_down(x.values, *host["d"])) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("packed", [False, True])
+@pytest.mark.parametrize("T", [3, 50])
+def test_integer_inputs_are_bit_exact(dn, packed, T):
+    # small integers: every product and partial sum is exact in bf16-in / fp32-accumulate
+    # arithmetic (|t| <= 4*4*64 = 1024 needs 11 bits -> keep t exactly representable in bf16:
+    # |x|,|U| <= 2, d_in = 32 -> |t| <= 128; |V| <= 2, r = 24 -> |y| <= 6144 < 2^24)
+    d_in, r, d_out = 32, 24, 40
+    x = si.store(si.small_ints(9, 1, T * d_in, -2, 2).reshape(T, d_in).astype(np.float32), "bf16")
+    U = si.store(si.small_ints(9, 2, d_in * r, -2, 2).reshape(d_in, r).astype(np.float32), "bf16")
+    V = si.store(si.small_ints(9, 3, r * d_out, -2, 2).reshape(r, d_out).astype(np.float32), "bf16")
+    p, keep = pair(dn, U, V, packed=packed)
+    ws = ws_for(dn, T, [p])
+    y = to_host(dn.deinfer_lowrank_linear(to_dev(x), p, ws))
+    ref = oracle.lowrank_linear(x.values, U.values, V.values)
+    # the output is rounded once to bf16: compare against the oracle rounded the same way
+    ref_b = si.bf16_bits_to_f32(si.f32_to_bf16_bits(ref.astype(np.float32))).astype(np.float64).reshape(ref.shape)
+    assert np.array_equal(y, ref_b)
+
+
+def test_degenerate_cases(dn):
+    import torch
+    x, U, V = gen(2, 4, 64, 8, 32, "bf16")
+    xd = to_dev(x)
+    for packed in (False, True):
+        # r == 0 -> exact zeros
+        U0 = si.Tensor("bf16", np.zeros((64, 0), np.uint16), np.zeros((64, 0), np.float32))
+        V0 = si.Tensor("bf16", np.zeros((0, 32), np.uint16), np.zeros((0, 32), np.float32))
+        p0 = dn.raw_pair(torch.zeros((64, 0), dtype=torch.bfloat16, device="cuda"),
+                         torch.zeros((0, 32), dtype=torch.bfloat16, device="cuda"))
+        if packed:
+            p0 = dn.deinfer_pack_factors(p0)
+        ws = ws_for(dn, 4, [p0])
+        y = torch.full((4, 32), 7.0, dtype=torch.bfloat16, device="cuda")
+        dn.deinfer_lowrank_linear(xd, p0, ws, out=y)
+        assert float(y.abs().max()) == 0.0
+        # T == 0 -> no-op
+        p, keep = pair(dn, U, V, packed=packed)
+        out = dn.deinfer_lowrank_linear(xd[:0], p, ws_for(dn, 0, [p]))
+        assert out.shape == (0, 32)
+        # x == 0 -> 0 ; strided (ld > width) input and output views
+        big_x = torch.zeros((4, 80), dtype=torch.bfloat16, device="cuda")
+        big_x[:, :64] = xd
+        big_y = torch.full((4, 48), 3.0, dtype=torch.bfloat16, device="cuda")
+        ws = ws_for(dn, 4, [p])
+        dn.deinfer_lowrank_linear(big_x[:, :64], p, ws, out=big_y[:, :32])
+        ref = oracle.lowrank_linear(x.values, U.values, V.values)
+        assert max_err(to_host(big_y[:, :32]), ref) <= TOL["bf16"]
+        assert float((big_y[:, 32:] - 3.0).abs().max()) == 0.0      # nothing written past d_out
+        z = dn.deinfer_lowrank_linear(torch.zeros_like(xd), p, ws)
+        assert float(z.abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("T", [129, 300])
+def test_linear_packed_beyond_decode_size(dn, T):
+    x, U, V = gen(12, T, 256, 72, 136, "bf16")
+    p, keep = pair(dn, U, V, packed=True)
+    ws = ws_for(dn, T, [p])
+    y = dn.deinfer_lowrank_linear(to_dev(x), p, ws)
+    ref = oracle.lowrank_linear(x.values, U.values, V.values)
+    assert max_err(to_host(y), ref) <= TOL["bf16"]
