@@ -1,0 +1,294 @@
+#!/usr/bin/env python3
+"""Benchmark of the decomposed-layer hot path on one MI355X.
+
+A "step" is one pass of the whole hot path of one decoder block over one batch of T
+tokens: deinfer_lowrank_qkv -> deinfer_lowrank_linear (o) -> deinfer_lowrank_gateup_silu
+-> deinfer_lowrank_down, enqueued back to back on one stream (attention core, norms,
+RoPE and residual adds are not part of the path and are not run).  Inputs are seeded
+synthetic tensors of the named shape, resident in HBM before the timed region.  To keep
+the 256 MB last-level cache from serving the weights, consecutive steps rotate through
+several independent copies of the packed weights (>= 1.5 GB in total).
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+WORKLOADS = {
+    # name: (block shape, default T, bound)
+    "llama7b_keep80_decode": ("llama7b_keep80", 64, "hbm"),
+    "llama7b_keep60_prefill": ("llama7b_keep60", 8192, "mfma"),
+    "llama7b_keep40_prefill": ("llama7b_keep40", 8192, "mfma"),
+    "llama13b_keep60_mixed": ("llama13b_keep60", 8256, "mfma"),
+    "llama70b_keep40_decode": ("llama70b_keep40", 128, "hbm"),
+    "llama70b_keep40_prefill": ("llama70b_keep40", 4096, "mfma"),
+}
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama7b_keep80_decode", choices=sorted(WORKLOADS))
+    ap.add_argument("--T", type=int, default=0, help="tokens per step (0 = the workload's default)")
+    ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
+                    help="replay the step from a captured HIP graph, or launch each call directly")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="also time the other decode batch sizes")
+    ap.add_argument("--seed", type=int, default=1)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not "
+              "supported, run with --gpus 1" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    import paper_2604_17709_amd as dn
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    L = dn.lib()            # raises if the HIP library is missing: no fallback
+
+    block_name, T_default, bound = WORKLOADS[args.workload]
+    T = args.T or T_default
+    if T <= 128:
+        bound = "hbm"
+    shape = si.BLOCKS[block_name]
+    proj = shape.projections()
+    rho = 1.0 - shape.keep_num / shape.keep_den
+    ranks = {p: dn.deinfer_rank_for_ratio(m, n, rho) for p, (m, n) in proj.items()}
+
+    # ---------------------------------------------------------------- inputs (host, seeded)
+    t0 = time.time()
+    host = si.block_tensors(shape, ranks, max(T, 1), args.seed)
+
+    def dev(t):
+        return torch.from_numpy(t.bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    params = sum(ranks[p] * (m + n) for p, (m, n) in proj.items())
+    weight_bytes = 2 * params
+    n_copies = max(2, int(np.ceil(1.5e9 / weight_bytes)))
+    packed0 = {}
+    for p in proj:
+        raw = dn.raw_pair(dev(host["U_" + p]), dev(host["V_" + p]), rho)
+        packed0[p] = dn.deinfer_pack_factors(raw)
+        torch.cuda.synchronize()
+        del raw
+    copies = [packed0]
+    for _ in range(1, n_copies):
+        c = {}
+        for p, pk in packed0.items():
+            buf = pk._keep[0].clone()
+            d = dn.Factors.from_buffer_copy(pk.desc)
+            d.U = buf.data_ptr() + (pk.desc.U - pk._keep[0].data_ptr())
+            d.V = buf.data_ptr() + (pk.desc.V - pk._keep[0].data_ptr())
+            c[p] = dn.Pair(d, [buf])
+        copies.append(c)
+    x = dev(host["x"]); a = dev(host["a"]); h_in = dev(host["h_in"])
+    bf = torch.bfloat16
+    q = torch.empty((T, proj["q"][1]), dtype=bf, device="cuda")
+    k = torch.empty((T, proj["k"][1]), dtype=bf, device="cuda")
+    v = torch.empty((T, proj["v"][1]), dtype=bf, device="cuda")
+    o = torch.empty((T, proj["o"][1]), dtype=bf, device="cuda")
+    h = torch.empty((T, proj["gate"][1]), dtype=bf, device="cuda")
+    y = torch.empty((T, proj["down"][1]), dtype=bf, device="cuda")
+    ws_bytes = max(dn.deinfer_workspace_bytes(T, [packed0["q"], packed0["k"], packed0["v"]]),
+                   dn.deinfer_workspace_bytes(T, [packed0["o"]]),
+                   dn.deinfer_workspace_bytes(T, [packed0["gate"], packed0["up"]]),
+                   dn.deinfer_workspace_bytes(T, [packed0["down"]]))
+    ws = dn.Workspace(ws_bytes)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    # ---------------------------------------------------------------- the step (pre-marshalled C calls)
+    def ld(t):
+        return int(t.stride(0))
+
+    def make_calls(c, stream_handle):
+        B = ctypes.byref
+        wsp, wsn = ws.buf.data_ptr(), ws.nbytes
+        return {
+            "qkv": (L.deinfer_lowrank_qkv, (x.data_ptr(), T, ld(x), B(c["q"].desc), B(c["k"].desc), B(c["v"].desc),
+                                            q.data_ptr(), ld(q), k.data_ptr(), ld(k), v.data_ptr(), ld(v),
+                                            None, 0, None, 0, wsp, wsn, stream_handle)),
+            "o": (L.deinfer_lowrank_linear, (a.data_ptr(), T, ld(a), B(c["o"].desc), o.data_ptr(), ld(o), wsp, wsn, stream_handle)),
+            "gateup": (L.deinfer_lowrank_gateup_silu, (x.data_ptr(), T, ld(x), B(c["gate"].desc), B(c["up"].desc),
+                                                       h.data_ptr(), ld(h), wsp, wsn, stream_handle)),
+            "down": (L.deinfer_lowrank_down, (h_in.data_ptr(), T, ld(h_in), B(c["down"].desc), y.data_ptr(), ld(y), wsp, wsn, stream_handle)),
+        }
+
+    def run_calls(calls, names=("qkv", "o", "gateup", "down")):
+        for n in names:
+            fn, a_ = calls[n]
+            rc = fn(*a_)
+            if rc != 0:
+                raise RuntimeError("%s failed: %s" % (n, dn.last_error()))
+
+    stream = torch.cuda.Stream()          # default priority
+    sh = int(stream.cuda_stream)
+    calls = [make_calls(c, sh) for c in copies]
+
+    graphs = None
+    launch_mode = args.launch
+    with torch.cuda.stream(stream):
+        run_calls(calls[0])
+    stream.synchronize()
+    ws.check(stream)
+    if launch_mode == "graph":
+        try:
+            graphs = []
+            for i in range(n_copies):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    run_calls(calls[i])
+                graphs.append(g)
+        except Exception as e:  # noqa: BLE001 - report and fall back to direct launches
+            print("graph capture failed (%s); using direct launches" % e, file=sys.stderr)
+            graphs = None
+            launch_mode = "direct"
+
+    def step(i):
+        if graphs is not None:
+            graphs[i % n_copies].replay()
+        else:
+            run_calls(calls[i % n_copies])
+
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t_a = time.perf_counter()
+        with torch.cuda.stream(stream):
+            for i in range(n):
+                fn(i)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t_a) / n
+
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            step(i)
+    stream.synchronize()
+    sec_per_step = timed(step, args.steps)
+    ws.check(stream)
+
+    # ---------------------------------------------------------------- per-call timing (HIP events on the launch stream)
+    def time_call(name, n):
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            for i in range(min(10, n)):
+                run_calls(calls[i % n_copies], (name,))
+            e0.record(stream)
+            for i in range(n):
+                run_calls(calls[i % n_copies], (name,))
+            e1.record(stream)
+        stream.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / n
+
+    s = 2
+    def call_bytes(names, outs):
+        wb = s * sum(ranks[p] * (proj[p][0] + proj[p][1]) for p in names)
+        return wb + s * T * proj[names[0]][0] + s * T * sum(outs)
+    def call_flops(names):
+        return 2.0 * T * sum(ranks[p] * (proj[p][0] + proj[p][1]) for p in names)
+    call_defs = {
+        "qkv": (("q", "k", "v"), [proj["q"][1], proj["k"][1], proj["v"][1]]),
+        "o": (("o",), [proj["o"][1]]),
+        "gateup": (("gate", "up"), [proj["gate"][1]]),
+        "down": (("down",), [proj["down"][1]]),
+    }
+    n_call = max(20, min(args.steps, 200))
+    per_call = {}
+    for name, (ps, outs) in call_defs.items():
+        sec = time_call(name, n_call)
+        per_call[name] = {"us": round(sec * 1e6, 2), "bytes": call_bytes(ps, outs), "flops": call_flops(ps),
+                          "GBs": round(call_bytes(ps, outs) / sec / 1e9, 1),
+                          "TFLOPs": round(call_flops(ps) / sec / 1e12, 2)}
+    dom = max(per_call, key=lambda n: per_call[n]["us"])
+    dsec = per_call[dom]["us"] * 1e-6
+    if bound == "hbm":
+        ach = per_call[dom]["bytes"] / dsec / 1e9
+        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+    else:
+        ach = per_call[dom]["flops"] / dsec / 1e12
+        roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+    roofline["kernel"] = "deinfer_lowrank_" + {"qkv": "qkv", "o": "linear", "gateup": "gateup_silu", "down": "down"}[dom]
+    roofline["avg_launch_us"] = per_call[dom]["us"]
+
+    step_bytes = sum(c["bytes"] for c in per_call.values())
+    step_flops = sum(c["flops"] for c in per_call.values())
+    out = {
+        "metric": "decomposed-layer tokens/sec; % HBM roofline (decode) / % MFMA peak (prefill)",
+        "value": round(T / sec_per_step, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s T=%d (qkv+o+gateup_silu+down of one block)" % (args.workload, T),
+                   "ranks": ranks, "weight_MB": round(weight_bytes / 1e6, 1), "weight_copies": n_copies,
+                   "launch": launch_mode},
+        "step_GBs": round(step_bytes / sec_per_step / 1e9, 1),
+        "step_TFLOPs": round(step_flops / sec_per_step / 1e12, 2),
+        "step_frac_of_roofline": round((step_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS) if bound == "hbm"
+                                       else (step_flops / sec_per_step / 1e12 / MFMA_BF16_PEAK_TFLOPS), 4),
+        "calls": per_call,
+        "roofline": roofline,
+        "setup_s": round(setup_s, 1),
+    }
+
+    # ---------------------------------------------------------------- other decode sizes
+    if args.sweep and T <= 128:
+        sweep = {}
+        for Ts in (1, 8, 32, 64, 128):
+            if Ts == T or Ts > host["x"].shape[0]:
+                continue
+            sub = [{n: (fn, tuple(Ts if (i == 1) else v_ for i, v_ in enumerate(a_))) for n, (fn, a_) in c.items()} for c in calls]
+            with torch.cuda.stream(stream):
+                for i in range(10):
+                    run_calls(sub[i % n_copies])
+            sec = timed(lambda i: run_calls(sub[i % n_copies]), args.steps)
+            sweep["T=%d" % Ts] = {"tokens_per_s": round(Ts / sec, 1), "us_per_step": round(sec * 1e6, 2), "launch": "direct"}
+        out["sweep"] = sweep
+
+    # ---------------------------------------------------------------- CPU baseline: the oracle, as it stands
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = min(T, 16)
+        f64 = lambda t: t.values.astype(np.float64)
+        xs, as_, hs = f64(host["x"])[:rows], f64(host["a"])[:rows], f64(host["h_in"])[:rows]
+        W = {n: f64(host[n]) for n in host if n[:2] in ("U_", "V_")}
+        t_a = time.perf_counter()
+        oracle.lowrank_qkv(xs, W["U_q"], W["V_q"], W["U_k"], W["V_k"], W["U_v"], W["V_v"])
+        oracle.lowrank_linear(as_, W["U_o"], W["V_o"])
+        oracle.lowrank_gateup_silu(xs, W["U_gate"], W["V_gate"], W["U_up"], W["V_up"])
+        oracle.lowrank_down(hs, W["U_down"], W["V_down"])
+        cpu_s = time.perf_counter() - t_a
+        out["cpu_baseline"] = {"value": round(rows / cpu_s, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": "%d of %d token rows of the same block, one pass, fp64 loops (%.1f s)" % (rows, T, cpu_s)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

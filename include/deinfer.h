@@ -71,6 +71,16 @@ const char *deinfer_last_error(void);
 int deinfer_version(void);
 
 /*
+ * Diagnostic: from now on every decode-sized call writes wall-clock stamps (100 MHz) into
+ * buf (device memory, uint64): workgroup g of the downward-projection kernel uses
+ * buf[8 g .. 8 g + 7], workgroup g of the upward-projection kernel buf[8 (1024 + g) ..]:
+ * [0] kernel entry, [5] first batch multiplied, [3] kernel exit, the rest spare.  buf must
+ * hold 2 * 1024 * 8 words; NULL switches tracing off (the default).  Process-wide, not
+ * thread-safe, not meant for production runs.
+ */
+int deinfer_set_trace_buffer(void *buf, size_t bytes);
+
+/*
  * Rank that keeps a fraction (1 - param_reduction) of the m*n parameters of a weight:
  *     r = floor((1 - param_reduction) * m * n / (m + n))
  * since a pair of inner size k holds (m + n) k parameters (Sec. 2.1).  The ratio is
@@ -98,20 +108,17 @@ int deinfer_pack_factors(const deinfer_factors_t *raw, void *dst, size_t dst_byt
                          deinfer_factors_t *packed, void *stream);
 
 /*
- * Workspace.  The library never allocates: the rank-space intermediate t (Sec. 4.1)
- * and the cross-workgroup synchronisation words live in a caller-provided device
- * buffer.
- *  deinfer_workspace_bytes: bytes needed for a call with T tokens over the given
- *    pairs (all pairs of one entry-point call).  Host-only.  Take the maximum over
- *    the calls that will share the workspace.
- *  deinfer_workspace_init: must be enqueued ONCE on a fresh workspace (and after a
- *    call was aborted) before its first use; clears the synchronisation words with
- *    a fill kernel (safe under stream capture).  Calls leave them cleared again.
- *  deinfer_workspace_check: synchronises `stream`, reads the workspace status word
- *    back and returns DEINFER_ERR_DEVICE if a kernel gave up waiting on its
- *    cross-workgroup barrier (results of that call are then invalid).
- * A workspace is 256-byte aligned and serves one call at a time: calls that overlap
- * in time (different streams) need different workspaces.
+ * Workspace.  The library never allocates: the rank-space intermediate t (Sec. 4.1) and
+ * the partial sums it is built from live in a caller-provided device buffer.
+ *  deinfer_workspace_bytes: bytes needed for a call with T tokens over the given pairs
+ *    (all pairs of one entry-point call).  Host-only.  Take the maximum over the calls
+ *    that will share the workspace.
+ *  deinfer_workspace_init: enqueue once on a fresh workspace; clears its status words with
+ *    a fill kernel (safe under stream capture).
+ *  deinfer_workspace_check: synchronises `stream`, reads the status words back and returns
+ *    DEINFER_ERR_DEVICE if a kernel flagged an error there.
+ * A workspace is 256-byte aligned and serves one call at a time: calls that overlap in
+ * time (different streams) need different workspaces.
  */
 int deinfer_workspace_bytes(int64_t T, const deinfer_factors_t *const *pairs, int n_pairs,
                             size_t *bytes);

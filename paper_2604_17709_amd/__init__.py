@@ -48,7 +48,7 @@ class DeinferError(RuntimeError):
 
 
 EXPORTS = [
-    "deinfer_last_error", "deinfer_version", "deinfer_rank_for_ratio",
+    "deinfer_last_error", "deinfer_version", "deinfer_set_trace_buffer", "deinfer_rank_for_ratio",
     "deinfer_packed_bytes", "deinfer_pack_factors",
     "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
     "deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
         FP = ctypes.POINTER(Factors)
         L.deinfer_last_error.restype = ctypes.c_char_p
         L.deinfer_version.restype = ctypes.c_int
+        L.deinfer_set_trace_buffer.argtypes = [_vp, _sz]
         L.deinfer_rank_for_ratio.argtypes = [_i64, _i64, ctypes.c_double, ctypes.POINTER(_i64)]
         L.deinfer_packed_bytes.argtypes = [FP, ctypes.POINTER(_sz)]
         L.deinfer_pack_factors.argtypes = [FP, _vp, _sz, FP, _vp]

@@ -1,33 +1,43 @@
-// Memory-bound ("decode", T <= 128 tokens) kernel for PACKED bf16 factor pairs.
+// Memory-bound ("decode", T <= 128 tokens) kernels for PACKED bf16 factor pairs.
 //
-// One persistent launch per entry-point call, one 512-thread workgroup per compute
-// unit, two phases separated by a single grid barrier:
+// A call is three launches on the caller's stream; kernel boundaries are the only
+// synchronisation (on this part a boundary costs about a microsecond, a software barrier
+// across the eight XCDs several):
 //
-//   phase 1  t = x . [U_a | U_b | U_c]   downward projections of up to three pairs as
-//            one concatenated product (Sec. 4.1).  The fragment stream of the packed
-//            U image is cut into equal contiguous ranges, one per workgroup, so every
-//            compute unit pulls the same number of bytes whatever the ranks are.  A
-//            16-wide rank tile that straddles a range boundary is completed by the
-//            workgroup where the tile starts: the others leave their partial sums in
-//            a slot and raise a flag (fixed summation order -> deterministic).
-//            t is kept as bf16 (one nearest-even rounding) in the workspace, which is
-//            small enough (<= 1.3 MB) to live in L2 / Infinity Cache.
-//   phase 2  y = t . V per pair (upward projections), 16 output features per work item,
-//            the 8 wavefronts of a workgroup split the rank dimension and reduce
-//            through LDS ("split-r"); optional SiLU-GLU epilogue for the gate/up call.
+//   down    t_part = x . [U_a | U_b | U_c]   downward projections of up to three pairs as
+//           one concatenated product (Sec. 4.1).  The fragment stream of the packed U image
+//           is cut into equal contiguous ranges, one per workgroup, so every compute unit
+//           pulls the same number of bytes whatever the ranks are.  A 16-wide rank tile that
+//           straddles range boundaries is produced in parts: workgroup g writes its fp32
+//           partial sums for the tile into part buffer (g - first workgroup of the tile).
+//   reduce  t = bf16(sum of the parts, in part order)   one nearest-even rounding; also
+//           hands out the optional rank-space results (low-rank KV cache, Sec. 2.1).
+//           t (<= 1.3 MB) stays in L2 / Infinity Cache.
+//   up      y = t . V per pair (upward projections), 16 output features per work item, the
+//           4 wavefronts of a workgroup split the rank dimension and reduce through LDS
+//           ("split-r"); optional SiLU-GLU epilogue for the gate/up call.
 //
 // Operands: weights are the MFMA A operand (16 features x 32 k fragments, one coalesced
 // 1 KiB load per wavefront), activations the B operand (16 tokens x 32 k), so the
 // accumulator holds [feature][token]; T is padded to a multiple of 16 tokens.
+//
+// Streaming: the work of a workgroup is a short list of "batches" (a run of up to
+// 4 * FM k-blocks of one tile; wavefront w takes k-blocks w, w + 4, ...): request all
+// fragments of the batch, multiply, next batch.  Memory latency is hidden the GPU way, by
+// occupancy: 256-thread workgroups (the wave dispatcher is a measurable part of a short
+// kernel: about 8 ns per wavefront and XCD) with at least two resident per compute unit, so
+// that one streams while another reduces.  The up
+// kernel runs one work item per workgroup and leaves load balancing to the hardware
+// dispatcher.  (A register-level software pipeline across batches was tried first: the
+// compiler kept placing waited register copies on the loop back-edge, which serialised it.)
 #pragma once
 #include "common.h"
 
 namespace deinfer {
 
-constexpr int DEC_THREADS = 512;
+constexpr int DEC_THREADS = 256;
 constexpr int DEC_WAVES = DEC_THREADS / kWave;
-constexpr int DEC_MAX_GRID = 1024;          // flag words reserved in the workspace header
-constexpr unsigned long long DEC_SPIN_LIMIT = 200000000ull;  // 2 s of the 100 MHz wall clock
+constexpr int DEC_MAX_PARTS = 8;            // part buffers: a rank tile spans at most this many workgroups
 
 struct DecPair {
   const uint4 *Up;      // packed U fragments [r_pad/16][KB1][64]
@@ -50,266 +60,349 @@ struct DecParams {
   int n_pairs;
   DecPair p[3];
   int n_rtiles;         // total rank tiles = Rtot_pad / 16
-  int Rtot_pad;         // pitch of t in elements
-  uint16_t *t;          // [T16][Rtot_pad]
-  float4 *slots;        // [grid][NT][64] partial sums of straddling tiles
-  unsigned *flags;      // [grid]
-  unsigned *bar;        // [0] arrivals, [1] generation, [2] error
-  int n_items2;         // phase-2 work items
-  int G1;               // workgroups that take a phase-1 range: min(grid, n_rtiles * KB1)
+  int Rtot_pad;         // pitch of t and of the part buffers, in elements
+  uint16_t *t;          // [T16][Rtot_pad] bf16
+  float *part;          // [DEC_MAX_PARTS][T16][Rtot_pad] fp32 partial sums
+  long long part_stride;  // elements between part buffers = T16 * Rtot_pad
+  int n_items2;         // work items of the up kernel
+  int G1;               // workgroups of the down kernel: every one takes a non-empty range
+  unsigned long long *trace;  // optional [2][1024][8] wall-clock stamps (diagnostic), may be null
 };
 
-__device__ __forceinline__ bool spin_until_set(unsigned *flag, unsigned *err) {
-  const unsigned long long t0 = wall_clock64();
-  while (__hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-    __builtin_amdgcn_s_sleep(1);
-    if (wall_clock64() - t0 > DEC_SPIN_LIMIT) {
-      __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      return false;
-    }
-  }
-  return true;
+// Values that are the same in every lane are moved to scalar registers explicitly (the
+// parameter block is read from LDS, so the compiler would otherwise keep them per lane).
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T>
+__device__ __forceinline__ T *uni_ptr(T *p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
+  return reinterpret_cast<T *>((unsigned long long)lo | ((unsigned long long)hi << 32));
 }
 
-// Self-resetting barrier over all workgroups of the (co-resident) grid.  Returns false
-// if the wait was abandoned (error word set); callers then skip their remaining work.
-__device__ __forceinline__ bool grid_barrier(unsigned *bar, unsigned nwg) {
-  __shared__ int ok_s;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int ok = 1;
-    const unsigned gen = __hip_atomic_load(bar + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned prev = __hip_atomic_fetch_add(bar, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    if (prev == nwg - 1) {
-      __hip_atomic_store(bar, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_fetch_add(bar + 1, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+// Pointers that were read from LDS have lost their address space; these casts put them back
+// into the global one so that plain global (not flat) memory instructions are used.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define DEINFER_GLOBAL __attribute__((address_space(1)))
+#else
+#define DEINFER_GLOBAL
+#endif
+typedef const DEINFER_GLOBAL u32x4_t *gc_u32x4_p;
+typedef DEINFER_GLOBAL float4 *g_float4_p;
+typedef DEINFER_GLOBAL uint2 *g_uint2_p;
+typedef DEINFER_GLOBAL uint16_t *g_u16_p;
+typedef DEINFER_GLOBAL unsigned long long *g_u64_p;
+
+// fragments per wavefront and batch
+template <int NT>
+struct DecFM { static constexpr int value = NT == 1 ? 16 : NT == 2 ? 10 : NT == 4 ? 6 : 3; };
+
+struct Batch {
+  const u32x4_t *a;     // fragment of k-block 0 of this tile (lane offset not included)
+  const uint16_t *b;    // activation element (row 0, k 0) of this pair
+  int kb0, kb1;         // k-blocks [kb0, kb1) of the tile, kb1 - kb0 <= 4 * FM
+  int k_lim;            // number of valid activation columns
+  bool valid;
+  bool end_seg;         // last batch of its segment
+  int tile, pi;         // down: the rank tile and its pair
+  int part;             // down: part buffer this workgroup writes for the tile
+  int otile, sub;       // up: output tile and, for the GLU call, which pair (0 gate, 1 up)
+};
+
+__device__ __forceinline__ void scalarize(Batch &d) {
+  d.a = uni_ptr(d.a); d.b = uni_ptr(d.b);
+  d.kb0 = uni(d.kb0); d.kb1 = uni(d.kb1); d.k_lim = uni(d.k_lim);
+  d.end_seg = uni(d.end_seg) != 0; d.tile = uni(d.tile); d.pi = uni(d.pi); d.part = uni(d.part);
+  d.otile = uni(d.otile); d.sub = uni(d.sub);
+}
+
+// Walks the batches of one workgroup, either of the down kernel (PHASE 1) or of the up
+// kernel (PHASE 2).  All members are wave-uniform.
+template <int NT, bool DUAL, int PHASE>
+struct Cursor {
+  static constexpr int SPAN = DEC_WAVES * DecFM<NT>::value;
+  int tile, kbp;        // down: position (rank tile, k-block inside it)
+  int tile_e, kb_e;     // down: end of the range (tile index, exclusive k-block inside it)
+  int g, G1;
+  unsigned total;
+  int it, sub, kb, G;   // up: position
+
+  __device__ __forceinline__ void init(const DecParams &P, int g_, int G_) {
+    g = g_; G = G_; G1 = P.G1;
+    if (PHASE == 1) {
+      // host guarantees n_rtiles * KB1 * (G1 + 1) < 2^31
+      total = (unsigned)P.n_rtiles * (unsigned)P.KB1;
+      const unsigned ua = (unsigned)g * total / (unsigned)G1;
+      const unsigned ub = (unsigned)(g + 1) * total / (unsigned)G1;     // > ua since G1 <= total
+      tile = (int)(ua / (unsigned)P.KB1);
+      kbp = (int)(ua - (unsigned)tile * (unsigned)P.KB1);
+      tile_e = (int)((ub - 1) / (unsigned)P.KB1);
+      kb_e = (int)(ub - (unsigned)tile_e * (unsigned)P.KB1);
     } else {
-      const unsigned long long t0 = wall_clock64();
-      while (__hip_atomic_load(bar + 1, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == gen) {
-        __builtin_amdgcn_s_sleep(1);
-        if (wall_clock64() - t0 > DEC_SPIN_LIMIT) {
-          __hip_atomic_store(bar + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          ok = 0;
-          break;
-        }
-      }
+      it = g; sub = 0; kb = 0;
     }
-    ok_s = ok;
   }
-  __syncthreads();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-  return ok_s != 0;
-}
 
-template <int NT>
-struct DecUnroll { static constexpr int value = NT == 1 ? 8 : NT == 2 ? 4 : 2; };
-
-// One split-k sweep: acc[nt] += W_frag(kb) x act(kb) for kb = kb_begin + wave, +8, ... < kb_end.
-// wfrag points at fragment 0 of the tile (+ lane); act[nt] at the lane's 8 bf16 of k-block 0
-// for token tile nt.  k_lim masks activation reads beyond the true reduction length.
-template <int NT>
-__device__ __forceinline__ void sweep(const uint4 *__restrict__ wfrag, const uint16_t *const (&act)[NT],
-                                      int kb_begin, int kb_end, int wave, int k_lane, int k_lim,
-                                      const uint16_t *__restrict__ safe, f32x4_t (&acc)[NT]) {
-  constexpr int UN = DecUnroll<NT>::value;
-  for (int kb0 = kb_begin + wave; kb0 < kb_end; kb0 += DEC_WAVES * UN) {
-    u32x4_t a[UN];
-    u32x4_t b[UN][NT];
-#pragma unroll
-    for (int i = 0; i < UN; ++i) {
-      const int kb = kb0 + i * DEC_WAVES;
-      const bool ok = kb < kb_end;
-      const int kbc = ok ? kb : kb0;
-      a[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(wfrag + (long long)kbc * 64));
-      const bool kok = ok && (kbc * 32 + k_lane < k_lim);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        // lanes beyond the reduction length read a valid dummy address and contribute zero
-        const uint16_t *src = kok ? act[nt] + (long long)kbc * 32 : safe;
-        const u32x4_t v = *reinterpret_cast<const u32x4_t *>(src);
-        b[i][nt] = kok ? v : u32x4_t{0u, 0u, 0u, 0u};
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < UN; ++i)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[i]), as_bf16x8(b[i][nt]), acc[nt], 0, 0, 0);
-  }
-}
-
-template <int NT, bool DUAL>
-__global__ __launch_bounds__(DEC_THREADS) void decode_kernel(const DecParams P) {
-  __shared__ float4 red[DUAL ? 2 : 1][DEC_WAVES][NT][kWave];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lrow = lane & 15, lkg = lane >> 4;
-  const int G = gridDim.x, g = blockIdx.x;
-
-  // ------------------------------------------------------------------ phase 1: t = x . U
-  {
-    const uint16_t *xact[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      int tok = nt * 16 + lrow;
-      tok = tok < P.T ? tok : P.T - 1;
-      xact[nt] = P.x + (long long)tok * P.ldx + lkg * 8;
-    }
-    const long long total = (long long)P.n_rtiles * P.KB1;
-    // only the first G1 = min(G, total) workgroups take a (non-empty) range
-    const int G1 = P.G1;
-    const long long ua = g < G1 ? (long long)g * total / G1 : total;
-    const long long ub = g < G1 ? (long long)(g + 1) * total / G1 : total;
-    long long u = ua;
-    while (u < ub) {
-      const int tile = (int)(u / P.KB1);
-      const long long tbeg = (long long)tile * P.KB1, tend = tbeg + P.KB1;
-      const long long se = ub < tend ? ub : tend;
-      const bool starts = (u == tbeg), ends = (se == tend);
+  __device__ __forceinline__ bool next(const DecParams &P, Batch &d) {
+    d.valid = false;
+    if (PHASE == 1) {
+      if (tile > tile_e) return false;
+      const int seg_end = tile < tile_e ? P.KB1 : kb_e;
       int pi = 0;
       if (P.n_pairs > 1 && tile >= P.p[1].tile0) pi = 1;
       if (P.n_pairs > 2 && tile >= P.p[2].tile0) pi = 2;
-      const DecPair &pr = P.p[pi];
-      const uint4 *wfrag = pr.Up + (long long)(tile - pr.tile0) * P.KB1 * 64 + lane;
+      d.valid = true;
+      d.tile = tile; d.pi = pi;
+      d.a = reinterpret_cast<const u32x4_t *>(P.p[pi].Up) + (long long)(tile - P.p[pi].tile0) * P.KB1 * 64;
+      d.b = P.x;
+      d.kb0 = kbp;
+      d.kb1 = kbp + SPAN < seg_end ? kbp + SPAN : seg_end;
+      d.k_lim = P.d_in;
+      d.end_seg = d.kb1 == seg_end;
+      // first workgroup whose range reaches into this tile
+      const unsigned tbeg = (unsigned)tile * (unsigned)P.KB1;
+      const int g_first = (int)(((tbeg + 1u) * (unsigned)G1 + total - 1u) / total) - 1;
+      d.part = g - g_first;
+      d.otile = 0; d.sub = 0;
+      if (d.end_seg) { ++tile; kbp = 0; } else { kbp = d.kb1; }
+      scalarize(d);
+      return true;
+    } else {
+      if (it >= P.n_items2) return false;
+      int pi = 0, otile = it;
+      if (DUAL) {
+        pi = sub;
+      } else {
+        if (P.n_pairs > 1 && otile >= P.p[0].n_otiles) { otile -= P.p[0].n_otiles; pi = 1; }
+        if (P.n_pairs > 2 && pi == 1 && otile >= P.p[1].n_otiles) { otile -= P.p[1].n_otiles; pi = 2; }
+      }
+      const int KB2 = P.p[pi].r_pad >> 5;
+      d.valid = true;
+      d.pi = pi; d.otile = otile; d.sub = sub; d.tile = 0; d.part = 0;
+      d.a = reinterpret_cast<const u32x4_t *>(P.p[pi].Vp) + (long long)otile * KB2 * 64;
+      d.b = P.t + P.p[pi].tile0 * 16;
+      d.kb0 = kb;
+      d.kb1 = kb + SPAN < KB2 ? kb + SPAN : KB2;
+      d.k_lim = P.p[pi].r_pad;
+      d.end_seg = d.kb1 == KB2;
+      if (d.end_seg) {
+        kb = 0;
+        if (DUAL && sub == 0) sub = 1;
+        else { sub = 0; it += G; }     // G = grid size: with one item per workgroup this ends the walk
+      } else {
+        kb = d.kb1;
+      }
+      scalarize(d);
+      return true;
+    }
+  }
+};
 
-      f32x4_t acc[NT];
+template <int NT>
+struct Frags {
+  u32x4_t a[DecFM<NT>::value];
+  u32x4_t b[DecFM<NT>::value][NT];
+};
+
+// Request the fragments of batch d (k-blocks kb0 + wave, + 4, ... below kb1; the predicate is
+// wave-uniform).  A lane whose 8 activation columns lie beyond the reduction length re-reads
+// the last 8 valid columns of its row, which meet zero-padded weights.  Addresses are a
+// scalar base plus a 32-bit per-lane offset.
+template <int NT>
+__device__ __forceinline__ void load_frags(const Batch &d, int wave, int lane, int k_lane,
+                                           const int (&rowoff)[NT], Frags<NT> &F) {
+  constexpr int FM = DecFM<NT>::value;
+  const gc_u32x4_p a = (gc_u32x4_p)d.a;
+  const DEINFER_GLOBAL char *b = (const DEINFER_GLOBAL char *)d.b;
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-      sweep<NT>(wfrag, xact, (int)(u - tbeg), (int)(se - tbeg), wave, lkg * 8, P.d_in, P.x, acc);
-
+  for (int f = 0; f < FM; ++f) {
+    const int kb = d.kb0 + wave + f * DEC_WAVES;
+    if (kb < d.kb1) {
+      F.a[f] = __builtin_nontemporal_load(a + (kb * 64 + lane));
+      int k = kb * 32 + k_lane;
+      k = k < d.k_lim - 8 ? k : d.k_lim - 8;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
-        red[0][wave][nt][lane] = make_float4(acc[nt][0], acc[nt][1], acc[nt][2], acc[nt][3]);
-      __syncthreads();
+        F.b[f][nt] = *(gc_u32x4_p)(b + (unsigned)((rowoff[nt] + k) * 2));
+    }
+  }
+}
+template <int NT>
+__device__ __forceinline__ void multiply(const Batch &d, int wave, const Frags<NT> &F, f32x4_t (&acc)[NT]) {
+  constexpr int FM = DecFM<NT>::value;
+#pragma unroll
+  for (int f = 0; f < FM; ++f) {
+    if (d.kb0 + wave + f * DEC_WAVES < d.kb1) {     // wave-uniform
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(F.a[f]), as_bf16x8(F.b[f][nt]), acc[nt], 0, 0, 0);
+    }
+  }
+}
 
-      const bool owner_wait = starts && !ends;
-      int g_last = g;
-      if (owner_wait) {
-        // workgroup that holds the last k-block of this tile
-        g_last = (int)((tend * G1 + total - 1) / total) - 1;
-        if (tid == 0)
-          for (int gg = g + 1; gg <= g_last; ++gg) spin_until_set(P.flags + gg, P.bar + 2);
-        __syncthreads();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-      }
-      if (tid < NT * kWave) {
-        const int nt = wave;
-        float4 s = red[0][0][nt][lane];
+// PHASE 1: down kernel (grid = P.G1).  PHASE 2: up kernel (grid = any, items round-robin).
+template <int NT, bool DUAL, int PHASE>
+__global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams Pk) {
+  __shared__ float4 red[(DUAL && PHASE == 2) ? 2 : 1][DEC_WAVES][NT][kWave];
+  // The parameter block is fetched once, by one vector load per thread, and read from LDS
+  // afterwards: lazily scheduled scalar loads from the kernel-argument segment would put
+  // several dependent memory round trips in front of the first weight request.
+  constexpr int PW = (int)((sizeof(DecParams) + 3) / 4);
+  static_assert(PW <= DEC_THREADS, "parameter block too large");
+  __shared__ __attribute__((aligned(16))) unsigned p_words[PW + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+#if defined(__HIP_DEVICE_COMPILE__)
+  {
+    typedef const __attribute__((address_space(4))) unsigned *kernarg_words_t;
+    kernarg_words_t ka = (kernarg_words_t)__builtin_amdgcn_kernarg_segment_ptr();
+    if (tid < PW) p_words[tid] = ka[tid];
+  }
+#endif
+  __syncthreads();
+  (void)Pk;
+  const DecParams &P = *reinterpret_cast<const DecParams *>(p_words);
+  const int lrow = lane & 15, lkg = lane >> 4;
+  const int G = gridDim.x, g = blockIdx.x;
+  const g_u64_p trace = (g_u64_p)((P.trace && g < 1024 && tid == 0) ? uni_ptr(P.trace) + ((PHASE - 1) * 1024 + g) * 8 : nullptr);
+  if (trace) {
+    trace[0] = wall_clock64();
+    for (int i = 1; i < 8; ++i) trace[i] = 0;
+  }
+
+  // per-lane activation row offsets (elements): x rows are clamped to the last token, t rows are padded
+  // (host guarantees that T * ldx and T16 * Rtot_pad fit 30 bits)
+  int rowoff[NT];
 #pragma unroll
-        for (int w = 1; w < DEC_WAVES; ++w) {
-          const float4 v = red[0][w][nt][lane];
-          s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-        }
-        if (!starts) {
-          P.slots[((long long)g * NT + nt) * kWave + lane] = s;
-        } else {
-          for (int gg = g + 1; gg <= g_last; ++gg) {
-            const float4 v = P.slots[((long long)gg * NT + nt) * kWave + lane];
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-          }
-          const int tok = nt * 16 + lrow;
-          const int col = tile * 16 + lkg * 4;
-          uint2 pk;
-          pk.x = pack_bf16x2(s.x, s.y);
-          pk.y = pack_bf16x2(s.z, s.w);
-          *reinterpret_cast<uint2 *>(P.t + (long long)tok * P.Rtot_pad + col) = pk;
-          if (pr.t_out != nullptr && tok < P.T) {
-            const int c0 = (tile - pr.tile0) * 16 + lkg * 4;
-            const float sv[4] = {s.x, s.y, s.z, s.w};
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-              if (c0 + v < pr.r) pr.t_out[(long long)tok * pr.ldt_out + c0 + v] = f32_to_bf16(sv[v]);
-          }
-        }
-      }
-      if (!starts) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        __syncthreads();
-        if (tid == 0) __hip_atomic_store(P.flags + g, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-      } else if (owner_wait) {
-        __syncthreads();
-        if (tid == 0)
-          for (int gg = g + 1; gg <= g_last; ++gg)
-            __hip_atomic_store(P.flags + gg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      __syncthreads();
-      u = se;
+  for (int nt = 0; nt < NT; ++nt) {
+    int tok = nt * 16 + lrow;
+    if (PHASE == 1) {
+      tok = tok < P.T ? tok : P.T - 1;
+      rowoff[nt] = tok * (int)P.ldx;
+    } else {
+      rowoff[nt] = tok * P.Rtot_pad;
     }
   }
 
-  if (!grid_barrier(P.bar, (unsigned)G)) return;
+  if (trace) trace[1] = wall_clock64();
+  Cursor<NT, DUAL, PHASE> cur;
+  cur.init(P, g, G);
+  if (trace && cur.G1 >= 0) trace[2] = wall_clock64();
+  Frags<NT> F;
+  f32x4_t acc[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  int n_steps = 0, n_fin = 0;
 
-  // ------------------------------------------------------------------ phase 2: y = t . V
-  for (int it = g; it < P.n_items2; it += G) {
-    int pi = 0, otile = it;
-    if (!DUAL) {
-      if (P.n_pairs > 1 && otile >= P.p[0].n_otiles) { otile -= P.p[0].n_otiles; pi = 1; }
-      if (P.n_pairs > 2 && pi == 1 && otile >= P.p[1].n_otiles) { otile -= P.p[1].n_otiles; pi = 2; }
-    }
-    f32x4_t acc[NT], acc2[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) { acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f}; acc2[nt] = acc[nt]; }
-    {
-      const DecPair &pr = P.p[pi];
-      const int KB2 = pr.r_pad >> 5;
-      const uint16_t *tact[NT];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        tact[nt] = P.t + (long long)(nt * 16 + lrow) * P.Rtot_pad + pr.tile0 * 16 + lkg * 8;
-      sweep<NT>(pr.Vp + (long long)otile * KB2 * 64 + lane, tact, 0, KB2, wave, lkg * 8, pr.r_pad, P.t, acc);
-    }
-    if (DUAL) {
-      const DecPair &pr = P.p[1];
-      const int KB2 = pr.r_pad >> 5;
-      const uint16_t *tact[NT];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        tact[nt] = P.t + (long long)(nt * 16 + lrow) * P.Rtot_pad + pr.tile0 * 16 + lkg * 8;
-      sweep<NT>(pr.Vp + (long long)otile * KB2 * 64 + lane, tact, 0, KB2, wave, lkg * 8, pr.r_pad, P.t, acc2);
-    }
+  // One batch: request its fragments, multiply, and close the segment if it ends here.
+  auto step = [&](const Batch &dc) {
+    load_frags<NT>(dc, wave, lane, lkg * 8, rowoff, F);
+    if (trace && n_steps == 0) trace[4] = wall_clock64();
+    multiply<NT>(dc, wave, F, acc);
+    if (trace && n_steps == 0 && acc[0][0] != 12345.678f) trace[5] = wall_clock64();
+    ++n_steps;
+    if (!dc.end_seg) return;
+
+    // ---- segment end: reduce the partial accumulators of the wavefronts through LDS and hand the result on
+    const int rb = (DUAL && PHASE == 2) ? dc.sub : 0;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      red[0][wave][nt][lane] = make_float4(acc[nt][0], acc[nt][1], acc[nt][2], acc[nt][3]);
-      if (DUAL) red[DUAL ? 1 : 0][wave][nt][lane] = make_float4(acc2[nt][0], acc2[nt][1], acc2[nt][2], acc2[nt][3]);
+      red[rb][wave][nt][lane] = make_float4(acc[nt][0], acc[nt][1], acc[nt][2], acc[nt][3]);
+      acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
+    if (DUAL && PHASE == 2 && dc.sub == 0) return;    // gate done, up follows: reduce both at once
     __syncthreads();
-    if (tid < NT * kWave) {
-      const int nt = wave;
+    for (int nt = wave; nt < NT; nt += DEC_WAVES) {    // token tiles are shared out among the wavefronts
       float4 s = red[0][0][nt][lane];
 #pragma unroll
       for (int w = 1; w < DEC_WAVES; ++w) {
         const float4 v = red[0][w][nt][lane];
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
       }
-      if (DUAL) {
-        float4 s2 = red[DUAL ? 1 : 0][0][nt][lane];
-#pragma unroll
-        for (int w = 1; w < DEC_WAVES; ++w) {
-          const float4 v = red[DUAL ? 1 : 0][w][nt][lane];
-          s2.x += v.x; s2.y += v.y; s2.z += v.z; s2.w += v.w;
-        }
-        s.x = silu_f32(s.x) * s2.x; s.y = silu_f32(s.y) * s2.y;
-        s.z = silu_f32(s.z) * s2.z; s.w = silu_f32(s.w) * s2.w;
-      }
-      const DecPair &pr = P.p[pi];
       const int tok = nt * 16 + lrow;
-      const int f0 = otile * 16 + lkg * 4;
-      if (tok < P.T) {
-        uint16_t *dst = pr.y + (long long)tok * pr.ldy + f0;
-        if (f0 + 3 < pr.d_out && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
-          uint2 pk;
-          pk.x = pack_bf16x2(s.x, s.y);
-          pk.y = pack_bf16x2(s.z, s.w);
-          *reinterpret_cast<uint2 *>(dst) = pk;
-        } else {
-          const float sv[4] = {s.x, s.y, s.z, s.w};
+      if (PHASE == 1) {
+        // fp32 partial sums of this workgroup's share of the tile: 4 consecutive rank columns
+        if (tok < P.T) {
+          const DEINFER_GLOBAL float *base = (const DEINFER_GLOBAL float *)uni_ptr(P.part) + (long long)dc.part * P.part_stride;
+          *(g_float4_p)(base + (tok * P.Rtot_pad + dc.tile * 16 + lkg * 4)) = s;
+        }
+      } else {
+        if (DUAL) {
+          float4 s2 = red[(DUAL && PHASE == 2) ? 1 : 0][0][nt][lane];
 #pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (f0 + v < pr.d_out) dst[v] = f32_to_bf16(sv[v]);
+          for (int w = 1; w < DEC_WAVES; ++w) {
+            const float4 v = red[(DUAL && PHASE == 2) ? 1 : 0][w][nt][lane];
+            s2.x += v.x; s2.y += v.y; s2.z += v.z; s2.w += v.w;
+          }
+          s.x = silu_f32(s.x) * s2.x; s.y = silu_f32(s.y) * s2.y;
+          s.z = silu_f32(s.z) * s2.z; s.w = silu_f32(s.w) * s2.w;
+        }
+        const DecPair &pr = P.p[DUAL ? 0 : dc.pi];
+        const int f0 = dc.otile * 16 + lkg * 4;
+        if (tok < P.T) {
+          uint16_t *dst = pr.y + (long long)tok * pr.ldy + f0;
+          if (f0 + 3 < pr.d_out && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
+            uint2 pk;
+            pk.x = pack_bf16x2(s.x, s.y);
+            pk.y = pack_bf16x2(s.z, s.w);
+            *(g_uint2_p)(dst) = pk;
+          } else {
+            const float sv[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (f0 + v < pr.d_out) ((g_u16_p)dst)[v] = f32_to_bf16(sv[v]);
+          }
         }
       }
     }
     __syncthreads();
+    if (trace && n_fin++ == 0) trace[6] = wall_clock64();
+  };
+
+  Batch d;
+  while (cur.next(P, d)) {
+    if (trace && n_steps == 0 && d.kb0 >= 0) trace[7] = wall_clock64();
+    step(d);
   }
+  if (trace) trace[3] = wall_clock64();
+}
+
+// t[tok][c] = bf16(sum over the parts of rank tile c / 16, in part order); rows T..T16-1 of t
+// are zero.  One thread per token row and group of 4 rank columns.  Also writes the optional
+// rank-space outputs.  Grid: ceil(T16 * Rtot_pad / 4 / 256) x 256 threads.
+__global__ __launch_bounds__(256) void decode_reduce_kernel(const DecParams P, int T16) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int groups = P.Rtot_pad >> 2;
+  if (i >= (long long)T16 * groups) return;
+  const int tok = (int)(i / groups);
+  const int col = (int)(i - (long long)tok * groups) * 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (tok < P.T) {
+    const int tile = col >> 4;
+    const unsigned total = (unsigned)P.n_rtiles * (unsigned)P.KB1;
+    const unsigned tbeg = (unsigned)tile * (unsigned)P.KB1, tend = tbeg + (unsigned)P.KB1;
+    const int g_first = (int)(((tbeg + 1u) * (unsigned)P.G1 + total - 1u) / total) - 1;
+    const int g_last = (int)((tend * (unsigned)P.G1 + total - 1u) / total) - 1;
+    const float *src = P.part + (long long)tok * P.Rtot_pad + col;
+    for (int k = 0; k <= g_last - g_first; ++k) {
+      const float4 v = *reinterpret_cast<const float4 *>(src + (long long)k * P.part_stride);
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    int pi = 0;
+    if (P.n_pairs > 1 && tile >= P.p[1].tile0) pi = 1;
+    if (P.n_pairs > 2 && tile >= P.p[2].tile0) pi = 2;
+    const DecPair &pr = P.p[pi];
+    if (pr.t_out != nullptr) {
+      const int c0 = col - pr.tile0 * 16;
+      const float sv[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (c0 + v < pr.r) pr.t_out[(long long)tok * pr.ldt_out + c0 + v] = f32_to_bf16(sv[v]);
+    }
+  }
+  uint2 pk;
+  pk.x = pack_bf16x2(s.x, s.y);
+  pk.y = pack_bf16x2(s.z, s.w);
+  *reinterpret_cast<uint2 *>(P.t + (long long)tok * P.Rtot_pad + col) = pk;
 }
 
 }  // namespace deinfer

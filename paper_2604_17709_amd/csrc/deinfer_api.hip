@@ -20,6 +20,8 @@ using namespace deinfer;
 namespace {
 
 thread_local char g_err[512] = "no error";
+unsigned long long *g_trace = nullptr;   // diagnostic stamp buffer (deinfer_set_trace_buffer)
+size_t g_trace_bytes = 0;
 
 int fail(int code, const char *fmt, ...) {
   va_list ap;
@@ -35,11 +37,12 @@ inline size_t elem_size(int dtype) { return dtype == DEINFER_BF16 ? 2 : 4; }
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 // ---- workspace layout -------------------------------------------------------------
-// [0, 256)       barrier words: arrivals, generation, error
-// [256, 4352)    one flag word per workgroup (DEC_MAX_GRID)
-// [8192, ...)    scratch: decode slots + t (bf16), or prefill t (bf16), or generic t (fp32)
-constexpr size_t WS_HEADER = 8192;
-constexpr size_t WS_FLAGS_OFF = 256;
+// [0, 256)   status words (reserved; cleared by deinfer_workspace_init)
+// [256, ...) scratch without invariants:
+//            decode:  t [T16 x Rtot_pad] bf16, then DEC_MAX_PARTS part buffers [T16 x Rtot_pad] fp32
+//            prefill: t [T x Rtot_pad] bf16
+//            generic: t [T x Rtot] fp32
+constexpr size_t WS_HEADER = 256;
 
 struct Geometry {          // derived sizes of one pair
   int64_t r_pad, KB1, KB2, n_rtiles, n_otiles;
@@ -98,10 +101,10 @@ size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
   } else {
     const int64_t Tc = T <= 128 ? T : 128;                       // decode-sized chunk
     const int nt = token_tiles(Tc);
-    const size_t slots = (size_t)DEC_MAX_GRID * nt * kWave * sizeof(float4);
-    const size_t tdec = (size_t)nt * 16 * (size_t)(rtot_pad > 0 ? rtot_pad : 32) * 2;
-    const size_t tpre = T > 128 ? (size_t)round_up(T, 256) * (size_t)(rtot_pad > 0 ? rtot_pad : 32) * 2 : 0;
-    scratch = round_up((int64_t)slots, 256) + round_up((int64_t)tdec, 256) + round_up((int64_t)tpre, 256);
+    const size_t rp = (size_t)(rtot_pad > 0 ? rtot_pad : 32);
+    const size_t tdec = (size_t)round_up((int64_t)nt * 16 * rp * 2, 256) + (size_t)DEC_MAX_PARTS * nt * 16 * rp * 4;
+    const size_t tpre = T > 128 ? (size_t)round_up(T, 256) * rp * 2 : 0;
+    scratch = round_up((int64_t)tdec, 256) + round_up((int64_t)tpre, 256);
   }
   return WS_HEADER + (size_t)round_up((int64_t)scratch, 256);
 }
@@ -145,17 +148,36 @@ struct Group {
 };
 
 template <int NT>
-int launch_decode_nt(const DecParams &P, bool glu, int grid, hipStream_t s) {
-  if (glu) hipLaunchKernelGGL((decode_kernel<NT, true>), dim3(grid), dim3(DEC_THREADS), 0, s, P);
-  else     hipLaunchKernelGGL((decode_kernel<NT, false>), dim3(grid), dim3(DEC_THREADS), 0, s, P);
-  return check_launch("decode kernel");
+int launch_decode_nt(const DecParams &P, bool glu, int grid2, hipStream_t s) {
+  hipLaunchKernelGGL((decode_kernel<NT, false, 1>), dim3(P.G1), dim3(DEC_THREADS), 0, s, P);
+  if (int rc = check_launch("decode down kernel")) return rc;
+  const int T16 = NT * 16;
+  const long long n = (long long)T16 * (P.Rtot_pad / 4);
+  hipLaunchKernelGGL(decode_reduce_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, P, T16);
+  if (int rc = check_launch("decode reduce kernel")) return rc;
+  if (glu) hipLaunchKernelGGL((decode_kernel<NT, true, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
+  else     hipLaunchKernelGGL((decode_kernel<NT, false, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
+  return check_launch("decode up kernel");
+}
+
+// Largest number of workgroups a single rank tile is spread over when `total` fragments
+// (tiles of KB1) are cut into G1 equal ranges.
+int max_parts(long long total, int KB1, int G1) {
+  int worst = 1;
+  const long long n_tiles = total / KB1;
+  for (long long tile = 0; tile < n_tiles; ++tile) {
+    const long long tbeg = tile * KB1, tend = tbeg + KB1;
+    const int g_first = (int)(((tbeg + 1) * G1 + total - 1) / total) - 1;
+    const int g_last = (int)((tend * G1 + total - 1) / total) - 1;
+    if (g_last - g_first + 1 > worst) worst = g_last - g_first + 1;
+  }
+  return worst;
 }
 
 // Decode-sized call (T <= 128) on packed pairs; rows [row0, row0 + T) of the group's tensors.
 int run_decode(const Group &gq, int64_t row0, int64_t T) {
   const int cus = device_cus();
   if (cus <= 0) return fail(DEINFER_ERR_DEVICE, "no usable HIP device");
-  const int grid = cus < DEC_MAX_GRID ? cus : DEC_MAX_GRID;
   const int nt = token_tiles(T);
   char *ws = static_cast<char *>(gq.ws);
   DecParams P;
@@ -182,17 +204,23 @@ int run_decode(const Group &gq, int64_t row0, int64_t T) {
   P.Rtot_pad = tile0 * 16;
   P.n_items2 = gq.glu ? P.p[0].n_otiles : items;
   const long long total = (long long)P.n_rtiles * P.KB1;
-  P.G1 = (int)(total < grid ? total : grid);
-  P.bar = reinterpret_cast<unsigned *>(ws);
-  P.flags = reinterpret_cast<unsigned *>(ws + WS_FLAGS_OFF);
-  P.slots = reinterpret_cast<float4 *>(ws + WS_HEADER);
-  const size_t slots_bytes = (size_t)round_up((int64_t)DEC_MAX_GRID * nt * kWave * sizeof(float4), 256);
-  P.t = reinterpret_cast<uint16_t *>(ws + WS_HEADER + slots_bytes);
+  if (total * (long long)(2 * cus + 1) >= (1ll << 31) || T * gq.ldx >= (1ll << 30) || (long long)nt * 16 * P.Rtot_pad >= (1ll << 30))
+    return fail(DEINFER_ERR_UNSUPPORTED, "problem too large for the decode schedule (%lld fragments)", total);
+  // two workgroups per compute unit for the down kernel (one streams while the other reduces)
+  int G1 = (int)(total < 2 * cus ? total : 2 * cus);
+  while (G1 > 1 && max_parts(total, P.KB1, G1) > DEC_MAX_PARTS) G1 = G1 * 7 / 8;
+  P.G1 = G1;
+  P.trace = (g_trace && g_trace_bytes >= (size_t)2 * 1024 * 8 * sizeof(unsigned long long)) ? g_trace : nullptr;
+  const size_t t_bytes = (size_t)round_up((int64_t)nt * 16 * P.Rtot_pad * 2, 256);
+  P.t = reinterpret_cast<uint16_t *>(ws + WS_HEADER);
+  P.part = reinterpret_cast<float *>(ws + WS_HEADER + t_bytes);
+  P.part_stride = (long long)nt * 16 * P.Rtot_pad;
+  const int grid2 = P.n_items2;     // one work item per workgroup
   switch (nt) {
-    case 1: return launch_decode_nt<1>(P, gq.glu, grid, gq.stream);
-    case 2: return launch_decode_nt<2>(P, gq.glu, grid, gq.stream);
-    case 4: return launch_decode_nt<4>(P, gq.glu, grid, gq.stream);
-    default: return launch_decode_nt<8>(P, gq.glu, grid, gq.stream);
+    case 1: return launch_decode_nt<1>(P, gq.glu, grid2, gq.stream);
+    case 2: return launch_decode_nt<2>(P, gq.glu, grid2, gq.stream);
+    case 4: return launch_decode_nt<4>(P, gq.glu, grid2, gq.stream);
+    default: return launch_decode_nt<8>(P, gq.glu, grid2, gq.stream);
   }
 }
 
@@ -327,6 +355,12 @@ const char *deinfer_last_error(void) { return g_err; }
 
 int deinfer_version(void) { return 1000; }
 
+int deinfer_set_trace_buffer(void *buf, size_t bytes) {
+  g_trace = static_cast<unsigned long long *>(buf);
+  g_trace_bytes = buf ? bytes : 0;
+  return DEINFER_OK;
+}
+
 int deinfer_rank_for_ratio(int64_t m, int64_t n, double param_reduction, int64_t *r_out) {
   if (!r_out) return fail(DEINFER_ERR_INVALID_ARG, "r_out is NULL");
   if (m <= 0 || n <= 0) return fail(DEINFER_ERR_INVALID_ARG, "m and n must be positive");
@@ -403,9 +437,10 @@ int deinfer_workspace_init(void *ws, size_t ws_bytes, void *stream) {
   if (!ws) return fail(DEINFER_ERR_WORKSPACE, "workspace pointer is NULL");
   if (!aligned(ws, 256)) return fail(DEINFER_ERR_MISALIGNED, "workspace must be 256-byte aligned");
   if (ws_bytes < WS_HEADER) return fail(DEINFER_ERR_WORKSPACE, "workspace smaller than its header (%zu bytes)", WS_HEADER);
-  const size_t words = WS_HEADER / 4;
-  hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)ceil_div((int64_t)words, 256)), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), static_cast<uint32_t *>(ws), words, 0u);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t hw = WS_HEADER / 4;
+  hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)ceil_div((int64_t)hw, 256)), dim3(256), 0, s,
+                     static_cast<uint32_t *>(ws), hw, 0u);
   return check_launch("workspace init");
 }
 
@@ -414,10 +449,10 @@ int deinfer_workspace_check(void *ws, size_t ws_bytes, void *stream) {
   if (ws_bytes < WS_HEADER) return fail(DEINFER_ERR_WORKSPACE, "workspace smaller than its header");
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (hipStreamSynchronize(s) != hipSuccess) return fail(DEINFER_ERR_DEVICE, "stream synchronise failed");
-  unsigned words[4] = {0, 0, 0, 0};
+  unsigned words[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (hipMemcpy(words, ws, sizeof(words), hipMemcpyDeviceToHost) != hipSuccess)
     return fail(DEINFER_ERR_DEVICE, "reading the workspace status failed");
-  if (words[2] != 0) return fail(DEINFER_ERR_DEVICE, "a kernel abandoned its cross-workgroup wait; re-run deinfer_workspace_init");
+  if (words[4] != 0) return fail(DEINFER_ERR_DEVICE, "a kernel reported an error in the workspace status words");
   return DEINFER_OK;
 }
 

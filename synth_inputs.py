@@ -17,6 +17,7 @@ for the bf16 configurations, N(0, std 1/sqrt(fan_in)) for the fp32 one.
 """
 from __future__ import annotations
 
+import os
 from dataclasses import dataclass
 from typing import Dict, List, Tuple
 
@@ -34,26 +35,39 @@ def _splitmix64(z: np.ndarray) -> np.ndarray:
         return z ^ (z >> np.uint64(31))
 
 
-def normal(seed: int, stream: int, n: int, std: float = 1.0) -> np.ndarray:
-    """n standard normals * std as float64; element i depends only on (seed, stream, i)."""
+def _normal_chunk(base: np.uint64, s: int, e: int, out: np.ndarray) -> None:
+    idx = np.arange(s, e, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        c0 = base + idx * np.uint64(2)
+    a = _splitmix64(c0)
+    b = _splitmix64(c0 + np.uint64(1))
+    # 53-bit uniforms; u1 in (0, 1], u2 in [0, 1)
+    u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
+    u2 = (b >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+    rad = np.sqrt(-2.0 * np.log(u1))
+    ang = (2.0 * np.pi) * u2
+    out[2 * s:2 * e:2] = rad * np.cos(ang)
+    out[2 * s + 1:2 * e:2] = rad * np.sin(ang)
+
+
+def normal(seed: int, stream: int, n: int, std: float = 1.0, start: int = 0) -> np.ndarray:
+    """n standard normals * std as float64: elements [start, start + n) of the stream
+    (seed, stream); element i depends only on (seed, stream, i).  start must be even."""
+    if start % 2:
+        raise ValueError("start must be even (values are drawn in pairs)")
     n_pairs = (n + 1) // 2
     out = np.empty(2 * n_pairs, dtype=np.float64)
-    chunk = 1 << 22
-    base = (np.uint64(seed & 0xFFFF) << np.uint64(48)) | (np.uint64(stream & 0xFFFF) << np.uint64(32))
-    for s in range(0, n_pairs, chunk):
-        e = min(n_pairs, s + chunk)
-        idx = np.arange(s, e, dtype=np.uint64)
-        with np.errstate(over="ignore"):
-            c0 = base + idx * np.uint64(2)
-        a = _splitmix64(c0)
-        b = _splitmix64(c0 + np.uint64(1))
-        # 53-bit uniforms; u1 in (0, 1], u2 in [0, 1)
-        u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
-        u2 = (b >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
-        rad = np.sqrt(-2.0 * np.log(u1))
-        ang = (2.0 * np.pi) * u2
-        out[2 * s:2 * e:2] = rad * np.cos(ang)
-        out[2 * s + 1:2 * e:2] = rad * np.sin(ang)
+    chunk = 1 << 20
+    base = ((np.uint64(seed & 0xFFFF) << np.uint64(48)) | (np.uint64(stream & 0xFFFF) << np.uint64(32))) \
+        + np.uint64(start)
+    spans = [(s, min(n_pairs, s + chunk)) for s in range(0, n_pairs, chunk)]
+    if len(spans) > 2:      # numpy releases the GIL inside the ufuncs: chunks run in parallel
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+            list(ex.map(lambda se: _normal_chunk(base, se[0], se[1], out), spans))
+    else:
+        for s, e in spans:
+            _normal_chunk(base, s, e, out)
     return out[:n] * std
 
 
@@ -92,6 +106,13 @@ class Tensor:
 
 def make(seed: int, stream: int, shape: Tuple[int, int], std: float, dtype: str) -> Tensor:
     v = normal(seed, stream, shape[0] * shape[1], std).astype(np.float32).reshape(shape)
+    return store(v, dtype)
+
+
+def make_rows(seed: int, stream: int, rows, width: int, std: float, dtype: str) -> Tensor:
+    """Selected rows of the (n_rows x width) tensor that make(seed, stream, ...) would draw
+    (width must be even), without generating the other rows."""
+    v = np.stack([normal(seed, stream, width, std, start=int(r) * width) for r in rows]).astype(np.float32)
     return store(v, dtype)
 
 
