@@ -101,8 +101,8 @@ def test_linear_packed_decode(dn, T, d_in, r, d_out):
     assert np.array_equal(to_host(y2), to_host(y))
 
 
-@pytest.mark.parametrize("T", [1, 8, 40, 128])
-def test_group_calls_packed_decode(dn, T):
+@pytest.mark.parametrize("T", [1, 8, 40, 128, 129, 300, 515])
+def test_group_calls_packed(dn, T):
     import torch
     d_in = 256
     x = si.make(6, 1, (T, d_in), 1.0, "bf16")
@@ -181,9 +181,10 @@ def test_degenerate_cases(dn):
         assert float(z.abs().max()) == 0.0
 
 
-@pytest.mark.parametrize("T", [129, 300])
-def test_linear_packed_beyond_decode_size(dn, T):
-    x, U, V = gen(12, T, 256, 72, 136, "bf16")
+@pytest.mark.parametrize("T", [129, 300, 1000])
+@pytest.mark.parametrize("d_in,r,d_out", [(256, 72, 136), (1096, 300, 520)])
+def test_linear_packed_beyond_decode_size(dn, T, d_in, r, d_out):
+    x, U, V = gen(12, T, d_in, r, d_out, "bf16")
     p, keep = pair(dn, U, V, packed=True)
     ws = ws_for(dn, T, [p])
     y = dn.deinfer_lowrank_linear(to_dev(x), p, ws)

@@ -56,11 +56,14 @@ def dn():
 
 
 def sample_rows(T, limit):
+    """First and last row plus rows on either side of the kernels' token-tile borders (16 for the
+    decode kernels, 128 / 256 for the prefill kernel), thinned to about `limit` rows."""
+    step = 16 if T <= 128 else 128
     rows = {0, T - 1}
-    for b in range(16, T, 16):
+    for b in range(step, T, step):
         rows.update((b - 1, b))
     rows = sorted(r for r in rows if 0 <= r < T)
-    if len(rows) > limit:                        # keep first/last and an even spread of boundaries
+    if len(rows) > limit:                        # keep first/last and an even spread of borders
         idx = np.unique(np.round(np.linspace(0, len(rows) - 1, limit)).astype(int))
         rows = [rows[i] for i in idx]
     return rows
