@@ -82,10 +82,12 @@ __device__ __forceinline__ T *uni_ptr(T *p) {
 
 // Pointers that were read from LDS have lost their address space; these casts put them back
 // into the global one so that plain global (not flat) memory instructions are used.
+#ifndef DEINFER_GLOBAL
 #if defined(__HIP_DEVICE_COMPILE__)
 #define DEINFER_GLOBAL __attribute__((address_space(1)))
 #else
 #define DEINFER_GLOBAL
+#endif
 #endif
 typedef const DEINFER_GLOBAL u32x4_t *gc_u32x4_p;
 typedef DEINFER_GLOBAL float4 *g_float4_p;

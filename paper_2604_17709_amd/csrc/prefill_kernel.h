@@ -14,20 +14,31 @@
 // MF x 8 accumulator fragments of the 16x16x32 bf16 MFMA (features = MFMA rows, tokens =
 // MFMA columns, so a lane ends up with 4 consecutive features of one token).  MF = 8 for a
 // single product (256 accumulator registers), MF = 4 for the GLU pair (2 x 128).
-// Weight fragments go global -> registers -> LDS as contiguous 1 KiB pieces (conflict free);
-// activations are read as coalesced 128-byte row pieces and kept in LDS with a 144-byte row
-// pitch, which makes the operand reads (16 rows x 16 bytes per quarter-wave) conflict free.
-// LDS is double buffered: global loads of k-step s + 1 are in flight while step s is
-// multiplied; one barrier per k-step.
+// Both operands go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
+// 1 KiB contiguous in LDS per wavefront instruction, no staging registers): weight fragments
+// are already contiguous 1 KiB pieces; an activation tile is kept as 128-byte token rows whose
+// eight 16-byte slots are XOR-swizzled with (row >> 1) & 7, applied on the global side of the
+// load (lane -> slot is fixed, lane -> k-chunk is permuted), which makes the operand reads
+// (16 rows x 16 bytes per quarter-wave) conflict free without padding.
+// LDS is double buffered: the loads of k-step s + 1 are in flight while step s is multiplied;
+// one barrier per k-step.
 #pragma once
 #include "common.h"
 
 namespace deinfer {
 
+#if defined(__HIP_DEVICE_COMPILE__)
+#define DEINFER_GLOBAL __attribute__((address_space(1)))
+#define DEINFER_LOCAL __attribute__((address_space(3)))
+#else
+#define DEINFER_GLOBAL
+#define DEINFER_LOCAL
+#endif
+
 constexpr int PF_THREADS = 256;
 constexpr int PF_BT = 256;                 // tokens per workgroup tile
 constexpr int PF_BK = 64;                  // k per step (two 32-wide k-blocks)
-constexpr int PF_XPITCH = PF_BK * 2 + 16;  // bytes per token row of the activation tile in LDS
+constexpr int PF_XPITCH = PF_BK * 2;       // bytes per token row of the activation tile in LDS
 
 struct PfSeg {             // a run of 16-feature tiles that belongs to one factor
   const uint4 *frags;      // its packed fragments [tiles][KB][64]
@@ -86,9 +97,9 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #pragma unroll
   for (int p = 0; p < (DUAL ? 2 : 1); ++p) {
     const PfProblem &Q = P.prob[p];
-    // ---- per-thread load assignment
-    // weights: wavefront w fetches feature tiles [w * BF_TILES / 4, +BF_TILES / 4) x 2 k-blocks
-    constexpr int WT = BF_TILES / 4;               // feature tiles per wavefront for loading
+    // ---- per-lane load assignment (every instruction moves 1 KiB: lane l -> LDS base + 16 l)
+    // weights: wavefront w fetches feature tiles [w * WT, +WT) x 2 k-blocks
+    constexpr int WT = BF_TILES / 4;
     const uint4 *wsrc[WT];
 #pragma unroll
     for (int i = 0; i < WT; ++i) {
@@ -99,48 +110,45 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       if (Q.n_seg > 2 && gt >= Q.seg[2].tile0) s = 2;
       wsrc[i] = Q.seg[s].frags + (long long)(gt - Q.seg[s].tile0) * Q.KB * 64 + lane;
     }
-    // activations: thread reads 16-byte chunk (tid % 8) of rows tid / 8 + 32 i
-    const int xc = tid & 7, xr = tid >> 3;
+    // activations: instruction i of wavefront w covers tile rows 8 (4 i + w) .. + 7; lane l holds
+    // slot l % 8 of row l / 8 and fetches k-chunk slot ^ ((row >> 1) & 7)
     const uint16_t *xsrc[8];
+    int xchunk[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      int row = tok0 + xr + 32 * i;
+      const int r = 8 * (4 * i + wave) + (lane >> 3);
+      int row = tok0 + r;
       row = row < P.T ? row : P.T - 1;
       xsrc[i] = Q.act + (long long)row * Q.lda;
+      xchunk[i] = (lane & 7) ^ ((r >> 1) & 7);
     }
     const int n_steps = (Q.KB + 1) >> 1;
 
-    uint4 wreg[WT][2], xreg[8];
-    auto fetch = [&](int step) {
+    auto fetch = [&](int step, int buf) {
       const int kb0 = step * 2;
 #pragma unroll
       for (int i = 0; i < WT; ++i)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
           const int kb = kb0 + kk < Q.KB ? kb0 + kk : Q.KB - 1;   // odd tail: duplicate, skipped below
-          wreg[i][kk] = wsrc[i][(long long)kb * 64];
+          __builtin_amdgcn_global_load_lds((const DEINFER_GLOBAL void *)(wsrc[i] + (long long)kb * 64),
+                                           (DEINFER_LOCAL void *)&S.w[buf][wave * WT + i][kk][0], 16, 0, 0);
         }
-      int k = step * PF_BK + xc * 8;
-      k = k < Q.K - 8 ? k : Q.K - 8;       // beyond K: re-read valid columns, they meet zero weights
 #pragma unroll
-      for (int i = 0; i < 8; ++i) xreg[i] = *reinterpret_cast<const uint4 *>(xsrc[i] + k);
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-      for (int i = 0; i < WT; ++i)
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) S.w[buf][wave * WT + i][kk][lane] = wreg[i][kk];
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-        *reinterpret_cast<uint4 *>(&S.x[buf][(xr + 32 * i) * PF_XPITCH + xc * 16]) = xreg[i];
+      for (int i = 0; i < 8; ++i) {
+        int k = step * PF_BK + xchunk[i] * 8;
+        k = k < Q.K - 8 ? k : Q.K - 8;     // beyond K: re-read valid columns, they meet zero weights
+        __builtin_amdgcn_global_load_lds((const DEINFER_GLOBAL void *)(xsrc[i] + k),
+                                         (DEINFER_LOCAL void *)&S.x[buf][8 * (4 * i + wave) * PF_XPITCH], 16, 0, 0);
+      }
     };
 
-    fetch(0);
-    stash(0);
+    fetch(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     for (int step = 0; step < n_steps; ++step) {
       const int buf = step & 1;
-      if (step + 1 < n_steps) fetch(step + 1);
+      if (step + 1 < n_steps) fetch(step + 1, buf ^ 1);
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
         if (step * 2 + kk < Q.KB) {        // uniform: odd number of k-blocks
@@ -149,9 +157,11 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
           for (int i = 0; i < MF; ++i)
             a[i] = *reinterpret_cast<const u32x4_t *>(&S.w[buf][wf * MF + i][kk][lane]);
 #pragma unroll
-          for (int j = 0; j < 8; ++j)
-            b[j] = *reinterpret_cast<const u32x4_t *>(
-                &S.x[buf][(wt * 128 + j * 16 + lrow) * PF_XPITCH + kk * 64 + lkg * 16]);
+          for (int j = 0; j < 8; ++j) {
+            const int r = wt * 128 + j * 16 + lrow;
+            const int slot = (kk * 4 + lkg) ^ ((r >> 1) & 7);
+            b[j] = *reinterpret_cast<const u32x4_t *>(&S.x[buf][r * PF_XPITCH + slot * 16]);
+          }
 #pragma unroll
           for (int i = 0; i < MF; ++i)
 #pragma unroll
@@ -159,7 +169,8 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
               acc[p][i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[i]), as_bf16x8(b[j]), acc[p][i][j], 0, 0, 0);
         }
       }
-      if (step + 1 < n_steps) stash(buf ^ 1);
+      // the loads of the next step have had the whole multiply to land
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
     }
   }
