@@ -71,6 +71,24 @@ const char *deinfer_last_error(void);
 int deinfer_version(void);
 
 /*
+ * Measurement aid: an entry-point call is several kernel launches (decode sizes: downward
+ * projection, reduce, upward projection; prefill sizes: one GEMM per stage).  After this call
+ * the library records start_event before, and stop_event after, every launch of the kind
+ * `which` (both are hipEvent_t created with timing enabled, passed as void*), on the stream of
+ * the call, so that a benchmark can time that one kernel with HIP events.  NULL events or
+ * which == 0 switch it off (the default).  Process-wide, not thread-safe.
+ */
+enum {
+  DEINFER_PROF_NONE = 0,
+  DEINFER_PROF_DECODE_DOWN = 1,
+  DEINFER_PROF_DECODE_REDUCE = 2,
+  DEINFER_PROF_DECODE_UP = 3,
+  DEINFER_PROF_PREFILL_DOWN = 4,
+  DEINFER_PROF_PREFILL_UP = 5
+};
+int deinfer_set_profile_events(int which, void *start_event, void *stop_event);
+
+/*
  * Diagnostic: from now on every decode-sized call writes wall-clock stamps (100 MHz) into
  * buf (device memory, uint64): workgroup g of the downward-projection kernel uses
  * buf[8 g .. 8 g + 7], workgroup g of the upward-projection kernel buf[8 (1024 + g) ..]:

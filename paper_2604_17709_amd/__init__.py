@@ -26,6 +26,7 @@ F32 = 0
 BF16 = 1
 LAYOUT_RAW = 0
 LAYOUT_PACKED = 1
+PROF_DECODE_DOWN, PROF_DECODE_REDUCE, PROF_DECODE_UP, PROF_PREFILL_DOWN, PROF_PREFILL_UP = 1, 2, 3, 4, 5
 
 _i64 = ctypes.c_int64
 _vp = ctypes.c_void_p
@@ -48,7 +49,8 @@ class DeinferError(RuntimeError):
 
 
 EXPORTS = [
-    "deinfer_last_error", "deinfer_version", "deinfer_set_trace_buffer", "deinfer_rank_for_ratio",
+    "deinfer_last_error", "deinfer_version", "deinfer_set_profile_events", "deinfer_set_trace_buffer",
+    "deinfer_rank_for_ratio",
     "deinfer_packed_bytes", "deinfer_pack_factors",
     "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
     "deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
@@ -70,6 +72,7 @@ def lib() -> ctypes.CDLL:
         L.deinfer_last_error.restype = ctypes.c_char_p
         L.deinfer_version.restype = ctypes.c_int
         L.deinfer_set_trace_buffer.argtypes = [_vp, _sz]
+        L.deinfer_set_profile_events.argtypes = [ctypes.c_int, _vp, _vp]
         L.deinfer_rank_for_ratio.argtypes = [_i64, _i64, ctypes.c_double, ctypes.POINTER(_i64)]
         L.deinfer_packed_bytes.argtypes = [FP, ctypes.POINTER(_sz)]
         L.deinfer_pack_factors.argtypes = [FP, _vp, _sz, FP, _vp]

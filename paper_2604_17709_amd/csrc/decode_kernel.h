@@ -12,7 +12,9 @@
 //           partial sums for the tile into part buffer (g - first workgroup of the tile).
 //   reduce  t = bf16(sum of the parts, in part order)   one nearest-even rounding; also
 //           hands out the optional rank-space results (low-rank KV cache, Sec. 2.1).
-//           t (<= 1.3 MB) stays in L2 / Infinity Cache.
+//           t (<= 1.3 MB) stays in L2 / Infinity Cache and is written in MFMA-fragment
+//           order (16 tokens x 32 rank columns per 1 KiB), so that the up kernel reads its
+//           activation operand with the same fully coalesced loads as the weights.
 //   up      y = t . V per pair (upward projections), 16 output features per work item, the
 //           4 wavefronts of a workgroup split the rank dimension and reduce through LDS
 //           ("split-r"); optional SiLU-GLU epilogue for the gate/up call.
@@ -61,7 +63,7 @@ struct DecParams {
   DecPair p[3];
   int n_rtiles;         // total rank tiles = Rtot_pad / 16
   int Rtot_pad;         // pitch of t and of the part buffers, in elements
-  uint16_t *t;          // [T16][Rtot_pad] bf16
+  uint16_t *t;          // bf16, fragment order: [T16 / 16][Rtot_pad / 32][64 lanes][8]
   float *part;          // [DEC_MAX_PARTS][T16][Rtot_pad] fp32 partial sums
   long long part_stride;  // elements between part buffers = T16 * Rtot_pad
   int n_items2;         // work items of the up kernel
@@ -97,7 +99,7 @@ typedef DEINFER_GLOBAL unsigned long long *g_u64_p;
 
 // fragments per wavefront and batch
 template <int NT>
-struct DecFM { static constexpr int value = NT == 1 ? 16 : NT == 2 ? 10 : NT == 4 ? 6 : 3; };
+struct DecFM { static constexpr int value = NT == 1 ? 16 : NT == 2 ? 6 : NT == 4 ? 3 : 2; };
 
 struct Batch {
   const u32x4_t *a;     // fragment of k-block 0 of this tile (lane offset not included)
@@ -182,7 +184,7 @@ struct Cursor {
       d.valid = true;
       d.pi = pi; d.otile = otile; d.sub = sub; d.tile = 0; d.part = 0;
       d.a = reinterpret_cast<const u32x4_t *>(P.p[pi].Vp) + (long long)otile * KB2 * 64;
-      d.b = P.t + P.p[pi].tile0 * 16;
+      d.b = P.t + (long long)(P.p[pi].tile0 >> 1) * 512;   // the pair's first k-block (fragments of 512 elements)
       d.kb0 = kb;
       d.kb1 = kb + SPAN < KB2 ? kb + SPAN : KB2;
       d.k_lim = P.p[pi].r_pad;
@@ -206,14 +208,31 @@ struct Frags {
   u32x4_t b[DecFM<NT>::value][NT];
 };
 
+#ifndef DEINFER_LOCAL
+#if defined(__HIP_DEVICE_COMPILE__)
+#define DEINFER_LOCAL __attribute__((address_space(3)))
+#else
+#define DEINFER_LOCAL
+#endif
+#endif
+
 // Request the fragments of batch d (k-blocks kb0 + wave, + 4, ... below kb1; the predicate is
-// wave-uniform).  A lane whose 8 activation columns lie beyond the reduction length re-reads
-// the last 8 valid columns of its row, which meet zero-padded weights.  Addresses are a
-// scalar base plus a 32-bit per-lane offset.
-template <int NT>
+// wave-uniform).  Weights: one coalesced 1 KiB fragment per k-block.
+// Activations of the up kernel (PHASE 2) are the fragment-ordered t: one coalesced 1 KiB load
+// per token tile and k-block.
+// Activations of the down kernel (PHASE 1) come from the caller's row-major x.  With one token
+// tile each lane (token l % 16, k-group l / 16) reads its 8 columns directly.  With more token
+// tiles that pattern (every quad of lanes in four different rows) would make the address unit
+// the bottleneck, so the 16 x 32 tile is moved by one global-to-LDS load in which a quad covers
+// 64 contiguous bytes of a row (lane l: row l / 4, slot l % 4, fetching k-group
+// slot ^ ((row >> 2) & 3)), into a region private to the wavefront, and read back in operand
+// order, conflict free; no workgroup barrier is involved.  A lane whose columns lie beyond d_in
+// re-reads the last 8 valid columns of its row, which meet zero-padded weights.
+template <int NT, int PHASE>
 __device__ __forceinline__ void load_frags(const Batch &d, int wave, int lane, int k_lane,
-                                           const int (&rowoff)[NT], Frags<NT> &F) {
+                                           const int (&rowoff)[NT], Frags<NT> &F, uint4 *xlds) {
   constexpr int FM = DecFM<NT>::value;
+  constexpr bool XLDS = (PHASE == 1 && NT >= 2);
   const gc_u32x4_p a = (gc_u32x4_p)d.a;
   const DEINFER_GLOBAL char *b = (const DEINFER_GLOBAL char *)d.b;
 #pragma unroll
@@ -221,11 +240,37 @@ __device__ __forceinline__ void load_frags(const Batch &d, int wave, int lane, i
     const int kb = d.kb0 + wave + f * DEC_WAVES;
     if (kb < d.kb1) {
       F.a[f] = __builtin_nontemporal_load(a + (kb * 64 + lane));
-      int k = kb * 32 + k_lane;
-      k = k < d.k_lim - 8 ? k : d.k_lim - 8;
+      if (XLDS) {
+        int k = kb * 32 + (((lane & 3) ^ ((lane >> 4) & 3)) << 3);      // row = lane / 4: (row >> 2) & 3 = lane >> 4
+        k = k < d.k_lim - 8 ? k : d.k_lim - 8;
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        F.b[f][nt] = *(gc_u32x4_p)(b + (unsigned)((rowoff[nt] + k) * 2));
+        for (int nt = 0; nt < NT; ++nt)
+          __builtin_amdgcn_global_load_lds((const DEINFER_GLOBAL void *)(b + (unsigned)((rowoff[nt] + k) * 2)),
+                                           (DEINFER_LOCAL void *)(xlds + (f * NT + nt) * 64), 16, 0, 0);
+      } else if (PHASE == 1) {
+        int k = kb * 32 + k_lane;
+        k = k < d.k_lim - 8 ? k : d.k_lim - 8;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          F.b[f][nt] = *(gc_u32x4_p)(b + (unsigned)((rowoff[nt] + k) * 2));
+      } else {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)     // rowoff[nt] = first fragment of token tile nt
+          F.b[f][nt] = *((gc_u32x4_p)b + ((rowoff[nt] + kb) * 64 + lane));
+      }
+    }
+  }
+  if (XLDS) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the LDS tiles (and the weights) have landed
+    const int lrow = lane & 15, lkg = lane >> 4;
+    const int slot = lrow * 4 + (lkg ^ ((lrow >> 2) & 3));
+#pragma unroll
+    for (int f = 0; f < FM; ++f) {
+      if (d.kb0 + wave + f * DEC_WAVES < d.kb1) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          F.b[f][nt] = *reinterpret_cast<const u32x4_t *>(xlds + (f * NT + nt) * 64 + slot);
+      }
     }
   }
 }
@@ -246,6 +291,8 @@ __device__ __forceinline__ void multiply(const Batch &d, int wave, const Frags<N
 template <int NT, bool DUAL, int PHASE>
 __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams Pk) {
   __shared__ float4 red[(DUAL && PHASE == 2) ? 2 : 1][DEC_WAVES][NT][kWave];
+  constexpr bool XLDS = (PHASE == 1 && NT >= 2);
+  __shared__ uint4 xstage[XLDS ? DEC_WAVES * DecFM<NT>::value * NT * 64 : 1];   // per-wavefront x tiles
   // The parameter block is fetched once, by one vector load per thread, and read from LDS
   // afterwards: lazily scheduled scalar loads from the kernel-argument segment would put
   // several dependent memory round trips in front of the first weight request.
@@ -273,15 +320,16 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
 
   // per-lane activation row offsets (elements): x rows are clamped to the last token, t rows are padded
   // (host guarantees that T * ldx and T16 * Rtot_pad fit 30 bits)
+  uint4 *const xlds = xstage + (XLDS ? wave * DecFM<NT>::value * NT * 64 : 0);
   int rowoff[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    int tok = nt * 16 + lrow;
+    int tok = nt * 16 + (XLDS ? (lane >> 2) : lrow);
     if (PHASE == 1) {
       tok = tok < P.T ? tok : P.T - 1;
       rowoff[nt] = tok * (int)P.ldx;
     } else {
-      rowoff[nt] = tok * P.Rtot_pad;
+      rowoff[nt] = nt * (P.Rtot_pad >> 5);      // fragment index of (token tile nt, k-block 0)
     }
   }
 
@@ -297,7 +345,7 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
 
   // One batch: request its fragments, multiply, and close the segment if it ends here.
   auto step = [&](const Batch &dc) {
-    load_frags<NT>(dc, wave, lane, lkg * 8, rowoff, F);
+    load_frags<NT, PHASE>(dc, wave, lane, lkg * 8, rowoff, F, xlds);
     if (trace && n_steps == 0) trace[4] = wall_clock64();
     multiply<NT>(dc, wave, F, acc);
     if (trace && n_steps == 0 && acc[0][0] != 12345.678f) trace[5] = wall_clock64();
@@ -404,7 +452,10 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const DecParams P, i
   uint2 pk;
   pk.x = pack_bf16x2(s.x, s.y);
   pk.y = pack_bf16x2(s.z, s.w);
-  *reinterpret_cast<uint2 *>(P.t + (long long)tok * P.Rtot_pad + col) = pk;
+  // fragment order: (token tile, k-block) -> 1 KiB, lane = token % 16 + 16 * ((k % 32) / 8)
+  const long long frag = (long long)(tok >> 4) * (P.Rtot_pad >> 5) + (col >> 5);
+  const int lane = (tok & 15) + 16 * ((col & 31) >> 3);
+  *reinterpret_cast<uint2 *>(P.t + frag * 512 + lane * 8 + (col & 7)) = pk;
 }
 
 }  // namespace deinfer

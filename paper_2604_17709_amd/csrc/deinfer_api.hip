@@ -22,6 +22,17 @@ namespace {
 thread_local char g_err[512] = "no error";
 unsigned long long *g_trace = nullptr;   // diagnostic stamp buffer (deinfer_set_trace_buffer)
 size_t g_trace_bytes = 0;
+int g_prof_kernel = 0;                   // deinfer_set_profile_events: which internal launch to bracket
+hipEvent_t g_prof_ev[2] = {nullptr, nullptr};
+
+// Brackets one internal kernel launch with the caller's two events (measurement aid).
+struct ProfScope {
+  bool on; hipStream_t s;
+  ProfScope(int kernel_id, hipStream_t s_) : on(g_prof_kernel == kernel_id && g_prof_ev[0] && g_prof_ev[1]), s(s_) {
+    if (on) (void)hipEventRecord(g_prof_ev[0], s);
+  }
+  ~ProfScope() { if (on) (void)hipEventRecord(g_prof_ev[1], s); }
+};
 
 int fail(int code, const char *fmt, ...) {
   va_list ap;
@@ -149,14 +160,23 @@ struct Group {
 
 template <int NT>
 int launch_decode_nt(const DecParams &P, bool glu, int grid2, hipStream_t s) {
-  hipLaunchKernelGGL((decode_kernel<NT, false, 1>), dim3(P.G1), dim3(DEC_THREADS), 0, s, P);
+  {
+    ProfScope ps(DEINFER_PROF_DECODE_DOWN, s);
+    hipLaunchKernelGGL((decode_kernel<NT, false, 1>), dim3(P.G1), dim3(DEC_THREADS), 0, s, P);
+  }
   if (int rc = check_launch("decode down kernel")) return rc;
   const int T16 = NT * 16;
   const long long n = (long long)T16 * (P.Rtot_pad / 4);
-  hipLaunchKernelGGL(decode_reduce_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, P, T16);
+  {
+    ProfScope ps(DEINFER_PROF_DECODE_REDUCE, s);
+    hipLaunchKernelGGL(decode_reduce_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, P, T16);
+  }
   if (int rc = check_launch("decode reduce kernel")) return rc;
-  if (glu) hipLaunchKernelGGL((decode_kernel<NT, true, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
-  else     hipLaunchKernelGGL((decode_kernel<NT, false, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
+  {
+    ProfScope ps(DEINFER_PROF_DECODE_UP, s);
+    if (glu) hipLaunchKernelGGL((decode_kernel<NT, true, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
+    else     hipLaunchKernelGGL((decode_kernel<NT, false, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
+  }
   return check_launch("decode up kernel");
 }
 
@@ -354,6 +374,14 @@ extern "C" {
 const char *deinfer_last_error(void) { return g_err; }
 
 int deinfer_version(void) { return 1000; }
+
+int deinfer_set_profile_events(int which, void *start_event, void *stop_event) {
+  if (which < 0 || which > DEINFER_PROF_PREFILL_UP) return fail(DEINFER_ERR_INVALID_ARG, "unknown launch id %d", which);
+  g_prof_kernel = (start_event && stop_event) ? which : 0;
+  g_prof_ev[0] = static_cast<hipEvent_t>(start_event);
+  g_prof_ev[1] = static_cast<hipEvent_t>(stop_event);
+  return DEINFER_OK;
+}
 
 int deinfer_set_trace_buffer(void *buf, size_t bytes) {
   g_trace = static_cast<unsigned long long *>(buf);
