@@ -46,6 +46,12 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    # a missing host stub or symbol shows up only at load time: check before replacing the old build
+    import ctypes
+    try:
+        ctypes.CDLL(LIB + ".tmp")
+    except OSError as e:
+        raise RuntimeError("built library does not load: %s" % e)
     os.replace(LIB + ".tmp", LIB)
     return LIB
 

@@ -72,6 +72,7 @@ struct PfShared {
 
 template <int MF, bool DUAL>
 __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
+#if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   PfShared<MF> &S = *reinterpret_cast<PfShared<MF> *>(smem_raw);
   constexpr int BF_TILES = 2 * MF;                 // 16-feature tiles per workgroup
@@ -97,77 +98,119 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #pragma unroll
   for (int p = 0; p < (DUAL ? 2 : 1); ++p) {
     const PfProblem &Q = P.prob[p];
-    // ---- per-lane load assignment (every instruction moves 1 KiB: lane l -> LDS base + 16 l)
-    // weights: wavefront w fetches feature tiles [w * WT, +WT) x 2 k-blocks
-    constexpr int WT = BF_TILES / 4;
-    const uint4 *wsrc[WT];
+    // ---- load assignment (every instruction moves 1 KiB: lane l -> LDS base + 16 l).
+    // Buffer addressing: a scalar resource descriptor, a scalar byte offset for the k position
+    // and one 32-bit per-lane offset, which leaves the registers to the accumulators; reads
+    // beyond a descriptor's size (token rows >= T, feature tiles past the last one) return
+    // zeros instead of faulting.  (Host guarantees every tensor here is below 2^31 bytes.)
+    constexpr int WT = BF_TILES / 4;       // feature tiles fetched per wavefront, x 2 k-blocks
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    __amdgpu_buffer_rsrc_t wres[WT];
+    unsigned wtile_off[WT];
 #pragma unroll
     for (int i = 0; i < WT; ++i) {
-      int gt = fb * BF_TILES + wave * WT + i;
-      gt = gt < Q.n_ftiles ? gt : Q.n_ftiles - 1;
+      const int gt = fb * BF_TILES + uwave * WT + i;
       int s = 0;
       if (Q.n_seg > 1 && gt >= Q.seg[1].tile0) s = 1;
       if (Q.n_seg > 2 && gt >= Q.seg[2].tile0) s = 2;
-      wsrc[i] = Q.seg[s].frags + (long long)(gt - Q.seg[s].tile0) * Q.KB * 64 + lane;
+      const int seg_end = s + 1 < Q.n_seg ? Q.seg[s + 1].tile0 : Q.n_ftiles;
+      wres[i] = __builtin_amdgcn_make_buffer_rsrc((void *)Q.seg[s].frags, 0,
+                                                  (int)((unsigned)(seg_end - Q.seg[s].tile0) * (unsigned)Q.KB * 1024u), 0x00020000);
+      wtile_off[i] = (unsigned)(gt - Q.seg[s].tile0) * (unsigned)Q.KB * 1024u;
     }
+    const unsigned wlane = lane * 16;
     // activations: instruction i of wavefront w covers tile rows 8 (4 i + w) .. + 7; lane l holds
-    // slot l % 8 of row l / 8 and fetches k-chunk slot ^ ((row >> 1) & 7)
-    const uint16_t *xsrc[8];
-    int xchunk[8];
+    // slot l % 8 of row l / 8 and fetches k-chunk slot ^ ((row >> 1) & 7).  With row = 8 m + l / 8,
+    // (row >> 1) & 7 is ((l >> 4) & 3) | ((m & 1) << 2), and m & 1 = w & 1.
+    const __amdgpu_buffer_rsrc_t xres =
+        __builtin_amdgcn_make_buffer_rsrc((void *)Q.act, 0, (int)((unsigned)P.T * (unsigned)(Q.lda * 2)), 0x00020000);
+    const int chunk = (lane & 7) ^ ((lane >> 4) & 3) ^ ((wave & 1) << 2);
+    unsigned xoff[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = 8 * (4 * i + wave) + (lane >> 3);
-      int row = tok0 + r;
-      row = row < P.T ? row : P.T - 1;
-      xsrc[i] = Q.act + (long long)row * Q.lda;
-      xchunk[i] = (lane & 7) ^ ((r >> 1) & 7);
-    }
+    for (int i = 0; i < 8; ++i)
+      xoff[i] = (unsigned)(tok0 + 8 * (4 * i + wave) + (lane >> 3)) * (unsigned)(Q.lda * 2) + (unsigned)(chunk * 16);
     const int n_steps = (Q.KB + 1) >> 1;
 
     auto fetch = [&](int step, int buf) {
-      const int kb0 = step * 2;
 #pragma unroll
       for (int i = 0; i < WT; ++i)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-          const int kb = kb0 + kk < Q.KB ? kb0 + kk : Q.KB - 1;   // odd tail: duplicate, skipped below
-          __builtin_amdgcn_global_load_lds((const DEINFER_GLOBAL void *)(wsrc[i] + (long long)kb * 64),
-                                           (DEINFER_LOCAL void *)&S.w[buf][wave * WT + i][kk][0], 16, 0, 0);
+          // a k-block past the end (odd KB) is asked for beyond the descriptor: it arrives as zeros
+          const unsigned so = step * 2 + kk < Q.KB ? wtile_off[i] + (unsigned)(step * 2 + kk) * 1024u : 0xffffff00u;
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(wres[i], (DEINFER_LOCAL void *)&S.w[buf][uwave * WT + i][kk][0], 16,
+                                                   wlane, so, 0, 0);
         }
+      if ((step + 1) * PF_BK <= Q.K) {            // uniform: the whole 64-wide slab is inside K
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        int k = step * PF_BK + xchunk[i] * 8;
-        k = k < Q.K - 8 ? k : Q.K - 8;     // beyond K: re-read valid columns, they meet zero weights
-        __builtin_amdgcn_global_load_lds((const DEINFER_GLOBAL void *)(xsrc[i] + k),
-                                         (DEINFER_LOCAL void *)&S.x[buf][8 * (4 * i + wave) * PF_XPITCH], 16, 0, 0);
+        for (int i = 0; i < 8; ++i)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LOCAL void *)&S.x[buf][8 * (4 * i + uwave) * PF_XPITCH], 16,
+                                                   xoff[i], (unsigned)step * (PF_BK * 2), 0, 0);
+      } else {
+        // slab reaches beyond K: those chunks re-read valid columns, which meet zero weights
+        int k = step * PF_BK + chunk * 8;
+        k = k < Q.K - 8 ? k : Q.K - 8;
+        const unsigned fix = (unsigned)(k * 2) - (unsigned)(chunk * 16);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LOCAL void *)&S.x[buf][8 * (4 * i + uwave) * PF_XPITCH], 16,
+                                                   xoff[i] + fix, 0, 0, 0);
       }
     };
 
+    auto read_a = [&](int buf, int kk, int i) -> u32x4_t {
+      return *reinterpret_cast<const u32x4_t *>(&S.w[buf][wf * MF + i][kk][lane]);
+    };
+    auto read_b = [&](int buf, int kk, int j) -> u32x4_t {
+      const int r = wt * 128 + j * 16 + lrow;
+      const int slot = (kk * 4 + lkg) ^ ((r >> 1) & 7);
+      return *reinterpret_cast<const u32x4_t *>(&S.x[buf][r * PF_XPITCH + slot * 16]);
+    };
+
+    // One barrier per k-step: when it is passed, step s has landed in buffer s % 2 and nobody
+    // reads buffer (s + 1) % 2 any more, so step s + 1 is requested into it right away and has
+    // the whole step to arrive.  Inside a step the LDS operand reads run ahead of the MFMAs in
+    // registers: the token fragment one product group ahead, and the feature fragments of the
+    // second k-block during the last product groups of the first.
     fetch(0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     for (int step = 0; step < n_steps; ++step) {
       const int buf = step & 1;
       if (step + 1 < n_steps) fetch(step + 1, buf ^ 1);
+      u32x4_t a0[MF], a1[MF], bc, bn;
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        if (step * 2 + kk < Q.KB) {        // uniform: odd number of k-blocks
-          u32x4_t a[MF], b[8];
+      for (int i = 0; i < MF; ++i) a0[i] = read_a(buf, 0, i);
+      bc = read_b(buf, 0, 0);
+#ifdef PF_SCHED
+      __builtin_amdgcn_sched_barrier(0);
+#endif
 #pragma unroll
-          for (int i = 0; i < MF; ++i)
-            a[i] = *reinterpret_cast<const u32x4_t *>(&S.w[buf][wf * MF + i][kk][lane]);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const int r = wt * 128 + j * 16 + lrow;
-            const int slot = (kk * 4 + lkg) ^ ((r >> 1) & 7);
-            b[j] = *reinterpret_cast<const u32x4_t *>(&S.x[buf][r * PF_XPITCH + slot * 16]);
-          }
-#pragma unroll
-          for (int i = 0; i < MF; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-              acc[p][i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[i]), as_bf16x8(b[j]), acc[p][i][j], 0, 0, 0);
+      for (int j = 0; j < 8; ++j) {
+        bn = j < 7 ? read_b(buf, 0, j + 1) : read_b(buf, 1, 0);
+        if (j >= 8 - MF / 2) {
+          const int i0 = 2 * (j - (8 - MF / 2));
+          a1[i0] = read_a(buf, 1, i0);
+          a1[i0 + 1] = read_a(buf, 1, i0 + 1);
         }
+#pragma unroll
+        for (int i = 0; i < MF; ++i)
+          acc[p][i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a0[i]), as_bf16x8(bc), acc[p][i][j], 0, 0, 0);
+        bc = bn;
+#ifdef PF_SCHED
+        __builtin_amdgcn_sched_barrier(0);      // keep the hand-written read-ahead distance
+#endif
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (j < 7) bn = read_b(buf, 1, j + 1);
+#pragma unroll
+        for (int i = 0; i < MF; ++i)
+          acc[p][i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a1[i]), as_bf16x8(bc), acc[p][i][j], 0, 0, 0);
+        bc = bn;
+#ifdef PF_SCHED
+        __builtin_amdgcn_sched_barrier(0);
+#endif
       }
       // the loads of the next step have had the whole multiply to land
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -208,8 +251,12 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
         for (int e = 0; e < 4; ++e)
           if (col + e < sg.width) dst[e] = f32_to_bf16(v[e]);
       }
+      __builtin_amdgcn_sched_barrier(0);    // one fragment at a time: keeps the epilogue's register need small
     }
   }
+#else
+  (void)P;
+#endif
 }
 
 }  // namespace deinfer
