@@ -4,16 +4,21 @@
 // with the weights W[F x K] in packed MFMA-fragment order:
 //   stage 1  act = x,  W = [U_a | U_b | U_c]^T (concatenated feature axis), out = t (bf16, one
 //            nearest-even rounding, row-major so that it is stage 2's activation operand);
-//   stage 2  act = t,  W = V^T of one pair, out = y; for the GLU call two products (gate, up)
-//            are accumulated side by side and combined by the SiLU-GLU epilogue in fp32.
+//   stage 2  act = t,  W = V^T of one pair, out = y.  The GLU call runs the gate product first
+//            (bf16 result stored in the output buffer) and then the up product, whose epilogue
+//            reads the gate values back and stores silu(gate) * up in their place: both products
+//            keep the full 256 x 256 tile, which a side-by-side accumulation (half the tile per
+//            product, 1.5 x the LDS and L2 traffic per flop) does not.
 // t makes one round trip through HBM / Infinity Cache (<= 75 MB, a few percent of the MFMA
 // time); a 256-row t tile does not fit the 160 KB LDS at these ranks.
 //
 // Tiling: 256 threads = 4 wavefronts (2 x 2), one per SIMD, workgroup tile 256 tokens x
-// (32 * MF) features; each wavefront owns 128 tokens x (16 * MF) features: MF x 8 accumulator
-// fragments of the 16x16x32 bf16 MFMA (features = MFMA rows, tokens = MFMA columns, so a lane
-// ends up with 4 consecutive features of one token).  MF = 8 for a single product (256
-// accumulator registers), MF = 4 for the GLU pair (2 x 128).
+// (32 * MF) features; each wavefront owns 128 tokens x (16 * MF) features as (MF / 2) x 4
+// accumulator blocks of the 32x32x16 bf16 MFMA (features = MFMA rows, tokens = MFMA columns).
+// MF = 8 uses all 256 accumulator registers.  (The 16x16x32 form of the instruction issued at
+// only about 60 % of the rate of the 32x32x16 form in a bare issue-rate measurement on this
+// device, which is why the wider form is used although the packed fragments are 16 features
+// tall: a 32-feature operand is gathered from two neighbouring fragments by LDS addressing.)
 // Both operands go from global memory straight into LDS (buffer loads with the LDS modifier,
 // 16 bytes per lane, 1 KiB contiguous in LDS per wavefront instruction, no staging registers):
 // weight fragments are already contiguous 1 KiB pieces; an activation tile is kept as 64-byte
@@ -46,10 +51,7 @@ constexpr int PF_XPITCH = PF_BK * 2;       // bytes per token row of the activat
 
 struct PfSeg {             // a run of 16-feature tiles that belongs to one factor
   const uint4 *frags;      // its packed fragments [tiles][KB][64]
-  uint16_t *out;           // output rows of this segment (bf16, row-major)
-  long long ldo;
   int tile0;               // first tile of the segment on the concatenated feature axis
-  int width;               // valid output columns of the segment
 };
 
 struct PfProblem {         // one product  act[T x K] . W^T
@@ -60,12 +62,15 @@ struct PfProblem {         // one product  act[T x K] . W^T
   int n_seg;
   PfSeg seg[3];
   int n_ftiles;            // 16-feature tiles on the (concatenated) feature axis
+  uint16_t *out;           // output [T x width] bf16 row-major: feature tile g lands at columns 16 g ..
+  long long ldo;
+  int width;               // valid output columns
 };
 
 struct PfParams {
   int T;
   int n_tblocks;           // ceil(T / 256)
-  PfProblem prob[2];       // [1] only for the GLU call (same feature axis, output through prob[0])
+  PfProblem prob;
 #ifdef DEINFER_PF_TRACE
   unsigned long long *trace;   // diagnostic build only: per-workgroup cycle counts
 #endif
@@ -77,7 +82,8 @@ struct PfShared {
   unsigned char x[PF_STAGES][PF_BT * PF_XPITCH];   // [stage][token row * 64 bytes], slots swizzled
 };
 
-template <int MF, bool DUAL>
+// GLU = true: the output buffer already holds the gate values g (bf16); store silu(g) * result.
+template <int MF, bool GLU>
 __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -93,20 +99,21 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   const int fb = blockIdx.x / P.n_tblocks;
   const int tok0 = tb * PF_BT;
 
+#ifdef DEINFER_PF_TRACE
+  const unsigned long long w_start = wall_clock64(), k_start = __builtin_readcyclecounter();
+  unsigned long long e_start = 0;
+#endif
   constexpr int MB = MF / 2;                       // 32-feature blocks per wavefront
-  f32x16_t acc[DUAL ? 2 : 1][MB][4];               // [product][feature block][32-token block]
+  f32x16_t acc[MB][4];                             // [feature block][32-token block]
 #pragma unroll
-  for (int p = 0; p < (DUAL ? 2 : 1); ++p)
+  for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int i = 0; i < MB; ++i)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[p][i][j][e] = 0.f;
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-#pragma unroll
-  for (int p = 0; p < (DUAL ? 2 : 1); ++p) {
-    const PfProblem &Q = P.prob[p];
+  const PfProblem &Q = P.prob;
+  {
     // ---- load assignment (every instruction moves 1 KiB: lane l -> LDS base + 16 l).
     // Buffer addressing: a scalar resource descriptor, a scalar byte offset for the k position
     // and one 32-bit per-lane offset, which leaves the registers to the accumulators; reads
@@ -209,11 +216,15 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       for (int j = 0; j < 4; ++j) {
         bn = j < 3 ? read_b(buf, j + 1, 0) : read_b(buf, 0, 1);
         if (j < MB) a1[j] = read_a(buf, j, 1);
+        // the operand reads for the next group are issued before this group's products, not after
+        // (in-order issue: a read placed behind four products starts 100 cycles late)
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-          acc[p][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a0[i]), as_bf16x8(bc), acc[p][i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a0[i]), as_bf16x8(bc), acc[i][j], 0, 0, 0);
           if (F2 && i == 0 && H1 + j < LPS) fetch_part(st + 2, H1 + j);
         }
+        __builtin_amdgcn_sched_barrier(0);
         bc = bn;
       }
       // ---- stage st + 1 has landed (this wavefront's part), barrier: it has landed everywhere and
@@ -242,11 +253,13 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       for (int j = 0; j < 4; ++j) {
         bn = j < 3 ? read_b(buf, j + 1, 1) : read_b(nbuf, 0, 0);
         if (j < MB) a0[j] = read_a(nbuf, j, 0);              // a0 is not in use during k-step 1
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-          acc[p][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a1[i]), as_bf16x8(bc), acc[p][i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a1[i]), as_bf16x8(bc), acc[i][j], 0, 0, 0);
           if (F3 && i == 0 && j < H1) fetch_part(st + 3, j);
         }
+        __builtin_amdgcn_sched_barrier(0);
         bc = bn;
       }
     };
@@ -259,27 +272,57 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       for (; st < n_stages; ++st) stage(st, no, no);
     }
 #ifdef DEINFER_PF_TRACE
-    if (P.trace && blockIdx.x < 1024 && p == 0 && (tid & 63) == 0) {
-      unsigned long long *tr = P.trace + (blockIdx.x * 4 + wave) * 4;
-      tr[0] = __builtin_readcyclecounter() - c0; tr[1] = c_wait; tr[2] = c_bar; tr[3] = (unsigned long long)n_stages;
+    c1 = __builtin_readcyclecounter();
+    if (P.trace && blockIdx.x < 2048 && tid == 0) {
+      unsigned long long *tr = P.trace + blockIdx.x * 8;
+      tr[2] = c0 - k_start; tr[3] = c1 - c0; tr[5] = c_wait; tr[6] = c_bar;
+      tr[7] = (unsigned long long)n_stages | ((unsigned long long)__builtin_amdgcn_s_getreg(63492) << 16) |
+              ((unsigned long long)__builtin_amdgcn_s_getreg(6164) << 48);
     }
+    e_start = c1;
 #endif
-    __syncthreads();       // the next product (GLU call) reuses the LDS buffers
+    __syncthreads();       // the epilogue reuses the LDS buffers
   }
 
   // ---- epilogue: through LDS (free by now; the barrier above has passed), so that the global
-  // stores are 16 bytes per lane and whole contiguous rows per group of lanes.
+  // stores are 16 bytes per lane and whole contiguous rows per group of lanes (storing straight
+  // from the accumulator arrangement, 32 bytes per row and instruction, measured slower).
   // Accumulator element 4 g + e of block (i, j) is feature 32 i + 8 g + 4 (l / 32) + e of token
   // 32 j + l % 32.  Each wavefront keeps its tile [128 tokens][16 MF features] as bf16 in its own
   // LDS region: rows of CPR 16-byte chunks (8 features each), chunk position XORed with the row
-  // number, the two 8-byte halves of a chunk swapped in rows with bit 4 set (conflict-free
-  // writes for MF = 8).  Only the wavefront itself touches the region: no barrier.
-  const PfProblem &Q = P.prob[0];
+  // number, the two 8-byte halves of a chunk swapped in rows with bit 4 set.  Only the wavefront
+  // itself touches the region: no barrier.
   constexpr int CPR = 2 * MF;                      // chunks per row
   constexpr int PITCH = CPR * 16;
   constexpr int RPI = 64 / CPR;                    // token rows per store instruction
   static_assert(4 * 128 * PITCH <= (int)sizeof(PfShared<MF>), "epilogue tile fits the stage buffers");
   unsigned char *E = smem_raw + wave * (128 * PITCH);
+  // this lane's chunk: 8 consecutive features
+  const int c = lane & (CPR - 1), rsub = lane / CPR;
+  uint16_t *const out = Q.out;
+  const long long ldo = Q.ldo;
+  const int width = Q.width;
+  const int col = (fb * BF_TILES + wf * MF) * 16 + c * 8;
+  const bool lane_on = col < width;
+  const bool wide = col + 8 <= width && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) && (ldo & 7) == 0;
+  const int tok_base = tok0 + wt * 128 + rsub;
+  uint16_t *dst = out + (long long)tok_base * ldo + col;
+  constexpr int NQ = 128 / RPI;                    // store instructions per wavefront
+  constexpr int HQ = NQ / 2;                       // ... handled in two batches (register budget)
+  const bool lane_wide = lane_on && wide;
+  // GLU: the gate values of a batch are requested one batch ahead (the first one before the
+  // accumulators go through LDS), so their latency is covered
+  u32x4_t gate[2][GLU ? HQ : 1];
+  auto load_gate = [&](int h) {
+#pragma unroll
+    for (int qq = 0; qq < HQ; ++qq) {
+      const int q = h * HQ + qq;
+      gate[h][GLU ? qq : 0] = u32x4_t{0u, 0u, 0u, 0u};
+      if (lane_wide && tok_base + q * RPI < P.T)
+        gate[h][GLU ? qq : 0] = *reinterpret_cast<const u32x4_t *>(dst + (long long)(q * RPI) * ldo);
+    }
+  };
+  if (GLU) load_gate(0);
   {
     const int wrow = lane & 31, wswz = lane & (CPR - 1);
     const int whalf = ((lane >> 5) ^ ((lane >> 4) & 1)) * 8;
@@ -289,52 +332,63 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          float v[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            v[e] = acc[0][i][j][4 * g + e];
-            if (DUAL) v[e] = silu_f32(v[e]) * acc[DUAL ? 1 : 0][i][j][4 * g + e];
-          }
           uint2 pk;
-          pk.x = pack_bf16x2(v[0], v[1]);
-          pk.y = pack_bf16x2(v[2], v[3]);
+          pk.x = pack_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]);
+          pk.y = pack_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
           *reinterpret_cast<uint2 *>(E + (32 * j + wrow) * PITCH + (((4 * i + g) ^ wswz) * 16) + whalf) = pk;
         }
   }
-  {
-    // this lane's chunk: 8 features inside one 16-feature tile, hence inside one segment
-    const int c = lane & (CPR - 1), rsub = lane / CPR;
-    const int gt = fb * BF_TILES + wf * MF + (c >> 1);
-    int sgi = 0;
-    if (Q.n_seg > 1 && gt >= Q.seg[1].tile0) sgi = 1;
-    if (Q.n_seg > 2 && gt >= Q.seg[2].tile0) sgi = 2;
-    uint16_t *out = Q.seg[0].out;
-    long long ldo = Q.seg[0].ldo;
-    int tile0 = Q.seg[0].tile0, width = Q.seg[0].width;
-    if (sgi == 1) { out = Q.seg[1].out; ldo = Q.seg[1].ldo; tile0 = Q.seg[1].tile0; width = Q.seg[1].width; }
-    if (sgi == 2) { out = Q.seg[2].out; ldo = Q.seg[2].ldo; tile0 = Q.seg[2].tile0; width = Q.seg[2].width; }
-    const int col = (gt - tile0) * 16 + (c & 1) * 8;
-    const bool lane_on = gt < Q.n_ftiles && col < width;
-    const bool wide = col + 8 <= width && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) && (ldo & 7) == 0;
-    const int tok_base = tok0 + wt * 128 + rsub;
-    uint16_t *dst = out + (long long)tok_base * ldo + col;
+  // h = silu(g) * u on the bf16 values of both products, one rounding of the result
+  auto glu = [&](u32x4_t g, u32x4_t u) -> u32x4_t {
+    u32x4_t r;
 #pragma unroll
-    for (int q = 0; q < 128 / RPI; ++q) {
+    for (int w = 0; w < 4; ++w) {
+      const float h0 = silu_f32(__uint_as_float(g[w] << 16)) * __uint_as_float(u[w] << 16);
+      const float h1 = silu_f32(__uint_as_float(g[w] & 0xffff0000u)) * __uint_as_float(u[w] & 0xffff0000u);
+      r[w] = pack_bf16x2(h0, h1);
+    }
+    return r;
+  };
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    if (GLU && h == 0) load_gate(1);
+    u32x4_t d[HQ];
+#pragma unroll
+    for (int qq = 0; qq < HQ; ++qq) {                // all reads of the batch first, then the stores
+      const int row = (h * HQ + qq) * RPI + rsub;
+      d[qq] = *reinterpret_cast<const u32x4_t *>(E + row * PITCH + ((c ^ (row & (CPR - 1))) * 16));
+    }
+#pragma unroll
+    for (int qq = 0; qq < HQ; ++qq) {
+      const int q = h * HQ + qq;
+      if (((q * RPI) >> 4) & 1) d[qq] = u32x4_t{d[qq][2], d[qq][3], d[qq][0], d[qq][1]};
+      if (GLU) d[qq] = glu(gate[h][GLU ? qq : 0], d[qq]);
+      if (lane_wide && tok_base + q * RPI < P.T)
+        *reinterpret_cast<u32x4_t *>(dst + (long long)(q * RPI) * ldo) = d[qq];
+    }
+  }
+  // rare: output rows that are not 16-byte aligned, or the valid columns end inside this chunk
+  if (lane_on && !wide) {
+    for (int q = 0; q < NQ; ++q) {
+      if (tok_base + q * RPI >= P.T) break;
       const int row = q * RPI + rsub;
       u32x4_t d = *reinterpret_cast<const u32x4_t *>(E + row * PITCH + ((c ^ (row & (CPR - 1))) * 16));
       if (((q * RPI) >> 4) & 1) d = u32x4_t{d[2], d[3], d[0], d[1]};
-      if (lane_on && tok_base + q * RPI < P.T) {
-        uint16_t *o = dst + (long long)(q * RPI) * ldo;
-        if (wide) {
-          *reinterpret_cast<u32x4_t *>(o) = d;
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (col + e < width) o[e] = (uint16_t)(d[e >> 1] >> ((e & 1) * 16));
-        }
+      uint16_t *o = dst + (long long)(q * RPI) * ldo;
+      for (int e = 0; e < 8; ++e) {
+        if (col + e >= width) break;
+        unsigned v = (d[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+        if (GLU) v = f32_to_bf16(silu_f32(bf16_to_f32(o[e])) * __uint_as_float(v << 16));
+        o[e] = (uint16_t)v;
       }
     }
   }
+#ifdef DEINFER_PF_TRACE
+  if (P.trace && blockIdx.x < 2048 && tid == 0) {
+    unsigned long long *tr = P.trace + blockIdx.x * 8;
+    tr[0] = w_start; tr[1] = wall_clock64(); tr[4] = __builtin_readcyclecounter() - e_start;
+  }
+#endif
 #else
   (void)P;
 #endif
