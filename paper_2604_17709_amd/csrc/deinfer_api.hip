@@ -14,6 +14,7 @@
 #include "generic_kernels.h"
 #include "pack_kernels.h"
 #include "prefill_kernel.h"
+#include "skinny_kernel.h"
 
 using namespace deinfer;
 
@@ -76,6 +77,40 @@ int token_tiles(int64_t T) {   // padded 16-token tiles of a decode call: 1, 2, 
   return nt <= 1 ? 1 : nt <= 2 ? 2 : nt <= 4 ? 4 : 8;
 }
 
+// ---- split of a memory-bound call with 16 < T <= 128 tokens
+struct SkPlan {              // split of one call; a pure function of the shapes (also sizes the workspace)
+  int NB;                    // 32-token blocks: 1, 2 or 4
+  int groups[2];             // 128-feature groups of stage 1 / stage 2
+  int P[2];                  // k-ranges of stage 1 / stage 2
+  int64_t rtot_pad;
+  size_t t_bytes, part_bytes;
+};
+
+SkPlan skinny_plan(int64_t T, const deinfer_factors_t *const *f, int n) {
+  SkPlan pl;
+  pl.NB = T <= 32 ? 1 : T <= 64 ? 2 : 4;
+  pl.groups[0] = pl.groups[1] = 0;
+  pl.rtot_pad = 0;
+  for (int i = 0; i < n; ++i) {
+    const Geometry ge = geometry(f[i]);
+    pl.groups[0] += (int)ceil_div(ge.n_rtiles, 8);
+    pl.groups[1] += (int)ceil_div(ge.n_otiles, 8);
+    pl.rtot_pad += ge.r_pad;
+  }
+  // enough workgroups to keep every compute unit streaming (three per unit of a 256-unit device for the
+  // long-k first stage, two for the second), but no more k-ranges than SK_MAX_PARTS
+  for (int s = 0; s < 2; ++s) {
+    const int target = s == 0 ? 768 : 512;
+    int p = (target + pl.groups[s] / 2) / (pl.groups[s] > 0 ? pl.groups[s] : 1);
+    pl.P[s] = p < 1 ? 1 : p > SK_MAX_PARTS ? SK_MAX_PARTS : p;
+  }
+  pl.t_bytes = (size_t)round_up((int64_t)pl.NB * 32 * (pl.rtot_pad > 0 ? pl.rtot_pad : 32) * 2, 256);
+  const size_t p0 = (size_t)pl.P[0] * pl.NB * 32 * (size_t)pl.groups[0] * SK_FEAT * 4;
+  const size_t p1 = (size_t)pl.P[1] * pl.NB * 32 * (size_t)pl.groups[1] * SK_FEAT * 4;
+  pl.part_bytes = (size_t)round_up((int64_t)(p0 > p1 ? p0 : p1), 256);
+  return pl;
+}
+
 int validate_pair(const deinfer_factors_t *f, const char *name) {
   if (!f) return fail(DEINFER_ERR_INVALID_ARG, "%s: factor descriptor is NULL", name);
   if (f->d_in <= 0 || f->d_out <= 0 || f->r < 0)
@@ -116,6 +151,11 @@ size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
     const size_t tdec = (size_t)round_up((int64_t)nt * 16 * rp * 2, 256) + (size_t)DEC_MAX_PARTS * nt * 16 * rp * 4;
     const size_t tpre = T > 128 ? (size_t)round_up(T, 256) * rp * 2 : 0;
     scratch = round_up((int64_t)tdec, 256) + round_up((int64_t)tpre, 256);
+    if (T > 16 && T <= 128) {
+      const SkPlan pl = skinny_plan(T, pairs, n);
+      const size_t sk = pl.t_bytes + pl.part_bytes;
+      if (sk > scratch) scratch = sk;
+    }
   }
   return WS_HEADER + (size_t)round_up((int64_t)scratch, 256);
 }
@@ -295,6 +335,7 @@ int run_generic(const Group &gq) {
 
 // The compute-bound path (T > 128) lives in its own file; it uses Group and the helpers above.
 #include "prefill_host.inc"
+#include "skinny_host.inc"
 
 int run_group(Group gq) {
   // ---- validation (host only)
@@ -363,7 +404,8 @@ int run_group(Group gq) {
 
   // ---- dispatch
   if (!packed) return dtype == DEINFER_BF16 ? run_generic<uint16_t>(gq) : run_generic<float>(gq);
-  if (gq.T <= 128) return run_decode(gq, 0, gq.T);
+  if (gq.T <= 16) return run_decode(gq, 0, gq.T);
+  if (gq.T <= 128) return run_skinny(gq);
   return run_prefill(gq);
 }
 

@@ -1,0 +1,261 @@
+// Memory-bound ("decode", T <= 128 tokens) kernels for PACKED bf16 factor pairs.
+//
+// Both stages of y = (x U) V (Sec. 4.1) are the product  out[T x F] = act[T x K] . W^T  with few
+// token rows: every weight is used for T <= 128 tokens, so the weights must stream from HBM
+// exactly once at full rate while the activations (a few hundred KiB) come from L2.
+//
+// Work split: the feature axis is cut into groups of 128 features (4 wavefronts x one
+// 32-feature block), the k axis into P ranges; one workgroup = one (group, k-range) rectangle.
+//   * weights: every wavefront loads its own fragments straight into registers (two 16-byte
+//     loads per lane and k-block cover two packed 16-feature fragments, non-temporal: they are
+//     never needed again), one stage (4 k-blocks = 8 KiB per wavefront) ahead of the products;
+//   * activations: the [T x 128 k] slab of a stage is shared by the four wavefronts: it goes
+//     from global memory straight into LDS (16-byte slots of a 256-byte row, slot index XORed
+//     with the row number, so the operand reads are conflict free), double buffered;
+//   * products: 32x32x16 bf16 MFMA, features = rows, tokens = columns, fp32 accumulators;
+//   * the rectangle's fp32 result goes to a partial buffer; a second small kernel adds the P
+//     partial sums in a fixed order (deterministic), applies the epilogue (bf16 rounding of t,
+//     SiLU-GLU of the MLP call) and writes the outputs.  (Letting the last workgroup of a
+//     feature group do the sum inside the streaming kernel was measured slower: the partial
+//     sums cross L2 caches that are not coherent with each other, and one workgroup's serial
+//     read-back is slower than a launch that uses the whole device.)
+// Every wavefront keeps two stages of weight loads in flight (three register sets, three LDS
+// slabs) and several workgroups share a compute unit.
+#pragma once
+#include "common.h"
+
+namespace deinfer {
+
+#if defined(__HIP_DEVICE_COMPILE__)
+#define DEINFER_LDS_PTR __attribute__((address_space(3)))
+#else
+#define DEINFER_LDS_PTR
+#endif
+
+constexpr int SK_THREADS = 256;
+constexpr int SK_KB = 4;                   // k-blocks per stage
+constexpr int SK_FEAT = 128;               // features per workgroup
+constexpr int SK_MAX_PARTS = 8;            // k-ranges per product at most
+constexpr int SK_XROW = SK_KB * 64;        // bytes per token row of a stage's activation slab
+constexpr int SK_SLABS = 3;                // activation slabs in LDS = weight register sets
+
+struct SkProblem {           // one product  act[T x K] . W^T,  W packed as [tiles][KB][64] fragments
+  const uint16_t *act;       // row-major bf16
+  long long lda;
+  const uint4 *frags;
+  int K;                     // valid k (columns of act)
+  int KB;                    // 32-wide k-blocks of the packed weights (zero padded)
+  int n_ftiles;              // 16-feature tiles
+  int group0;                // first feature group of this product in the launch
+  int kb_per_part;           // k-blocks per k-range (a multiple of SK_KB)
+};
+
+struct SkParams {
+  int T;
+  int n_prob;
+  int n_groups;              // feature groups of all products; grid = n_groups * P
+  int P;
+  SkProblem prob[3];
+  float *part;               // [P][NB * 32][n_groups * 128] fp32
+  long long part_stride;     // NB * 32 * n_groups * 128
+};
+
+// NB = 32-token blocks (1, 2 or 4)
+template <int NB>
+__global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 3 : 1) void skinny_kernel(const SkParams P) {
+#if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
+  __shared__ __attribute__((aligned(16))) unsigned char xs[SK_SLABS][NB * 32 * SK_XROW];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // consecutive workgroups share the k-range (the same activation slab, kept hot in L2)
+  const int g = blockIdx.x % P.n_groups;
+  const int part = blockIdx.x / P.n_groups;
+  int pi = 0;
+  if (P.n_prob > 1 && g >= P.prob[1].group0) pi = 1;
+  if (P.n_prob > 2 && g >= P.prob[2].group0) pi = 2;
+  const SkProblem &Q = P.prob[pi];
+  const int fblk = (g - Q.group0) * 4 + wave;          // this wavefront's 32-feature block
+  const int kb_begin = part * Q.kb_per_part;
+  int kb_end = kb_begin + Q.kb_per_part;
+  kb_end = kb_end < Q.KB ? kb_end : Q.KB;
+  const int n_stages = kb_end > kb_begin ? (kb_end - kb_begin + SK_KB - 1) / SK_KB : 0;
+
+  // ---- weights: buffer addressing; a lane offset beyond the descriptor's size reads zeros, which
+  // is how feature tiles past the last one and k-blocks past the range contribute nothing
+  const unsigned wbytes = (unsigned)Q.n_ftiles * (unsigned)Q.KB * 1024u;
+  const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc((void *)Q.frags, 0, (int)wbytes, 0x00020000);
+  // lane l holds feature l % 32 (tile 2 fblk + (l / 16) % 2, row l % 16) and k-group 2 s + l / 32
+  const unsigned wtile = (unsigned)(2 * fblk + ((lane >> 4) & 1));
+  const unsigned wlane = wtile * (unsigned)Q.KB * 1024u + (unsigned)(((lane & 15) + 16 * (lane >> 5)) * 16);
+  const bool wtile_ok = (int)wtile < Q.n_ftiles;
+  constexpr unsigned OOB = 0x7ffffff0u;
+  // ---- activations
+  const unsigned xbytes = (unsigned)(((long long)(P.T - 1) * Q.lda + Q.K) * 2);
+  const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void *)Q.act, 0, (int)xbytes, 0x00020000);
+  constexpr int NX = NB * 2;                            // slab load instructions per wavefront and stage
+  unsigned xrow[NX], xchunk[NX];
+#pragma unroll
+  for (int i = 0; i < NX; ++i) {
+    const int m = i * 4 + wave;                         // instruction m covers rows 4 m .. 4 m + 3
+    const int row = 4 * m + (lane >> 4);
+    xrow[i] = row < P.T ? (unsigned)row * (unsigned)(Q.lda * 2) : OOB;
+    xchunk[i] = (unsigned)(((lane & 15) ^ (row & 15)) * 16);
+  }
+  const unsigned xklim = (unsigned)(Q.K * 2 - 16);
+
+  auto fetch_x = [&](int st, int buf) {
+    const unsigned kbyte0 = (unsigned)(kb_begin + st * SK_KB) * 64u;
+    const bool live = st < n_stages;                    // uniform
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+      // chunks beyond K re-read valid columns (k clamped to K - 8), which meet zero weights
+      unsigned kb = kbyte0 + xchunk[i];
+      kb = kb < xklim ? kb : xklim;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[buf][(i * 4 + wave) * 4 * SK_XROW], 16,
+                                               live ? xrow[i] + kb : OOB, 0, 0, 0);
+    }
+  };
+  auto fetch_w = [&](u32x4_t (&w)[SK_KB * 2], int st) {
+#pragma unroll
+    for (int kbi = 0; kbi < SK_KB; ++kbi) {
+      const int kb = kb_begin + st * SK_KB + kbi;
+      const unsigned off = (wtile_ok && kb < kb_end) ? wlane : OOB;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+        w[kbi * 2 + ks] = __builtin_amdgcn_raw_buffer_load_b128(wres, off, kb * 1024 + ks * 512, 2);
+    }
+  };
+
+  f32x16_t acc[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+
+  const int b_row = lane & 31;
+  auto compute = [&](const u32x4_t (&w)[SK_KB * 2], int buf) {
+#pragma unroll
+    for (int kbi = 0; kbi < SK_KB; ++kbi)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const int slot = (kbi * 4 + 2 * ks + (lane >> 5)) ^ (lane & 15);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const u32x4_t b = *reinterpret_cast<const u32x4_t *>(&xs[buf][(32 * j + b_row) * SK_XROW + slot * 16]);
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(w[kbi * 2 + ks]), as_bf16x8(b), acc[j], 0, 0, 0);
+        }
+      }
+  };
+
+  // Stage s uses register set / slab s % 3.  Every stage issues exactly 8 + NX loads (those past
+  // the k-range read zeros through an out-of-range offset and cost no traffic), so "all but the
+  // loads of the next stage have arrived" is one constant wait.
+  if (n_stages > 0) {
+    u32x4_t w0[SK_KB * 2], w1[SK_KB * 2], w2[SK_KB * 2];
+    fetch_w(w0, 0); fetch_x(0, 0);
+    fetch_w(w1, 1); fetch_x(1, 1);
+    auto stage = [&](const u32x4_t (&w)[SK_KB * 2], u32x4_t (&wn)[SK_KB * 2], int st, int slab) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(SK_KB * 2 + NX) : "memory");   // stage st has arrived (this wavefront's part)
+      __builtin_amdgcn_s_barrier();                     // ... everywhere; nobody reads slab (st - 1) % 3 any more
+      asm volatile("" ::: "memory");
+      fetch_w(wn, st + 2);
+      fetch_x(st + 2, slab == 0 ? 2 : slab - 1);
+      compute(w, slab);
+    };
+    for (int st = 0; st < n_stages; st += 3) {
+      stage(w0, w2, st, 0);
+      if (st + 1 >= n_stages) break;
+      stage(w1, w0, st + 1, 1);
+      if (st + 2 >= n_stages) break;
+      stage(w2, w1, st + 2, 2);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // drain the out-of-range tail loads
+  }
+
+  // ---- partial result: element 4 q + e of block j is feature 8 q + 4 (l / 32) + e, token 32 j + l % 32
+  const long long F = (long long)P.n_groups * SK_FEAT;
+  float *dst = P.part + (long long)part * P.part_stride + (long long)(lane & 31) * F +
+               (long long)g * SK_FEAT + wave * 32 + 4 * (lane >> 5);
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    if (32 * j + (lane & 31) < P.T) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x4_t v = {acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]};
+        *reinterpret_cast<f32x4_t *>(dst + (long long)(32 * j) * F + 8 * q) = v;
+      }
+    }
+  }
+#else
+  (void)P;
+#endif
+}
+
+// ---- sum of the partial results + epilogue ------------------------------------------------------
+struct SkOut {               // a run of columns of the partial buffer that belongs to one output
+  int col0;                  // first column in the partial buffer
+  int width;                 // valid columns
+  uint16_t *out;             // bf16 row-major
+  long long ldo;
+  int width2;                // optional second copy of the first width2 columns (rank-space output) ...
+  uint16_t *out2;            // ... or null
+  long long ldo2;
+};
+struct SkReduceParams {
+  const float *part;
+  long long part_stride;
+  int P, T, F;               // F = columns of the partial buffer
+  int n_out;
+  SkOut o[3];
+  int glu_delta;             // > 0: o[0] columns are the gate product, the up product sits glu_delta columns later
+};
+
+// one thread = 8 consecutive columns of one token row
+__global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkReduceParams R) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int c8 = R.F / 8;
+  const int tok = (int)(idx / c8);
+  const int col = (int)(idx % c8) * 8;
+  if (tok >= R.T) return;
+  int oi = -1;
+#pragma unroll
+  for (int i = 0; i < 3; ++i)
+    if (i < R.n_out && col >= R.o[i].col0 && col < R.o[i].col0 + R.o[i].width) oi = i;
+  if (oi < 0) return;
+  const SkOut &o = R.o[oi];
+  float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float u[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const float *src = R.part + (long long)tok * R.F + col;
+  for (int p = 0; p < R.P; ++p) {               // fixed order: deterministic sums
+    const f32x4_t a = *reinterpret_cast<const f32x4_t *>(src + p * R.part_stride);
+    const f32x4_t b = *reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] += a[e]; v[4 + e] += b[e]; }
+    if (R.glu_delta > 0) {
+      const f32x4_t c = *reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + R.glu_delta);
+      const f32x4_t d = *reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + R.glu_delta + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { u[e] += c[e]; u[4 + e] += d[e]; }
+    }
+  }
+  if (R.glu_delta > 0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = silu_f32(v[e]) * u[e];
+  }
+  const int oc = col - o.col0;
+  const u32x4_t pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+  uint16_t *dst = o.out + (long long)tok * o.ldo + oc;
+  if (oc + 8 <= o.width && ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0)) {
+    *reinterpret_cast<u32x4_t *>(dst) = pk;
+  } else {
+    for (int e = 0; e < 8; ++e)
+      if (oc + e < o.width) dst[e] = (uint16_t)(pk[e >> 1] >> ((e & 1) * 16));
+  }
+  if (o.out2 && oc < o.width2) {
+    uint16_t *d2 = o.out2 + (long long)tok * o.ldo2 + oc;
+    for (int e = 0; e < 8; ++e)
+      if (oc + e < o.width2) d2[e] = (uint16_t)(pk[e >> 1] >> ((e & 1) * 16));
+  }
+}
+
+}  // namespace deinfer
