@@ -280,7 +280,7 @@ def main():
         roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
     roofline["kernel"] = ("%s kernel (%s%s-projection launch of deinfer_lowrank_%s)"
-                          % ("decode_kernel" if decode else "prefill_kernel",
+                          % (("decode_kernel" if T <= 16 else "skinny_kernel") if decode else "prefill_kernel",
                              "last " if (not decode and kdom == "up" and len(ps) > 1) else "", kdom, entry))
     roofline["avg_launch_us"] = round(ksec * 1e6, 2)
     roofline["algorithmic_bytes_per_launch"] = kbytes[kdom]

@@ -226,18 +226,35 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkReduceParams
   float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float u[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const float *src = R.part + (long long)tok * R.F + col;
-  for (int p = 0; p < R.P; ++p) {               // fixed order: deterministic sums
-    const f32x4_t a = *reinterpret_cast<const f32x4_t *>(src + p * R.part_stride);
-    const f32x4_t b = *reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + 4);
+  // all loads first (independent, one round trip), then the sums in a fixed order: deterministic
+  f32x4_t a[SK_MAX_PARTS][2];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { v[e] += a[e]; v[4 + e] += b[e]; }
-    if (R.glu_delta > 0) {
-      const f32x4_t c = *reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + R.glu_delta);
-      const f32x4_t d = *reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + R.glu_delta + 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { u[e] += c[e]; u[4 + e] += d[e]; }
+  for (int p = 0; p < SK_MAX_PARTS; ++p) {
+    a[p][0] = a[p][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    if (p < R.P) {
+      a[p][0] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + p * R.part_stride));
+      a[p][1] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + 4));
     }
   }
+  if (R.glu_delta > 0) {
+    f32x4_t b[SK_MAX_PARTS][2];
+#pragma unroll
+    for (int p = 0; p < SK_MAX_PARTS; ++p) {
+      b[p][0] = b[p][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      if (p < R.P) {
+        b[p][0] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + R.glu_delta));
+        b[p][1] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + R.glu_delta + 4));
+      }
+    }
+#pragma unroll
+    for (int p = 0; p < SK_MAX_PARTS; ++p)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { u[e] += b[p][0][e]; u[4 + e] += b[p][1][e]; }
+  }
+#pragma unroll
+  for (int p = 0; p < SK_MAX_PARTS; ++p)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] += a[p][0][e]; v[4 + e] += a[p][1][e]; }
   if (R.glu_delta > 0) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = silu_f32(v[e]) * u[e];
