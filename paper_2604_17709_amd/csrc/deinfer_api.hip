@@ -97,10 +97,11 @@ SkPlan skinny_plan(int64_t T, const deinfer_factors_t *const *f, int n) {
     pl.groups[1] += (int)ceil_div(ge.n_otiles, 8);
     pl.rtot_pad += ge.r_pad;
   }
-  // enough workgroups to keep every compute unit streaming (three per unit of a 256-unit device for the
-  // long-k first stage, two for the second), but no more k-ranges than SK_MAX_PARTS
+  // about one long-lived workgroup per compute unit of a 256-unit device (each keeps enough loads in
+  // flight to stream at its share of the HBM rate; the kernel time barely moves between 128 and 1024
+  // workgroups): more k-ranges only add partial-sum traffic
   for (int s = 0; s < 2; ++s) {
-    const int target = s == 0 ? 768 : 512;
+    const int target = 256;
     int p = (target + pl.groups[s] / 2) / (pl.groups[s] > 0 ? pl.groups[s] : 1);
     pl.P[s] = p < 1 ? 1 : p > SK_MAX_PARTS ? SK_MAX_PARTS : p;
   }

@@ -131,9 +131,11 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       if (Q.n_seg > 1 && gt >= Q.seg[1].tile0) sgi = 1;
       if (Q.n_seg > 2 && gt >= Q.seg[2].tile0) sgi = 2;
       const int seg_end = sgi + 1 < Q.n_seg ? Q.seg[sgi + 1].tile0 : Q.n_ftiles;
+      // a feature tile past the last one gets an empty descriptor: every read of it returns zeros
+      const bool live = gt < Q.n_ftiles;
       wres[i] = __builtin_amdgcn_make_buffer_rsrc((void *)Q.seg[sgi].frags, 0,
-                                                  (int)((unsigned)(seg_end - Q.seg[sgi].tile0) * (unsigned)Q.KB * 1024u), 0x00020000);
-      wtile_off[i] = (unsigned)(gt - Q.seg[sgi].tile0) * (unsigned)Q.KB * 1024u;
+                                                  live ? (int)((unsigned)(seg_end - Q.seg[sgi].tile0) * (unsigned)Q.KB * 1024u) : 0, 0x00020000);
+      wtile_off[i] = live ? (unsigned)(gt - Q.seg[sgi].tile0) * (unsigned)Q.KB * 1024u : 0u;
     }
     const unsigned wlane = lane * 16;
     // activations: instruction i of wavefront w covers tile rows 16 (4 i + w) .. + 15; lane l holds

@@ -19,8 +19,10 @@
 //     feature group do the sum inside the streaming kernel was measured slower: the partial
 //     sums cross L2 caches that are not coherent with each other, and one workgroup's serial
 //     read-back is slower than a launch that uses the whole device.)
-// Every wavefront keeps two stages of weight loads in flight (three register sets, three LDS
-// slabs) and several workgroups share a compute unit.
+// Every wavefront keeps three stages of weight loads in flight (four register sets, four LDS
+// slabs); one or two workgroups per compute unit.  Inside the kernel the stream runs at the HBM
+// rate (a per-workgroup trace shows 32 KiB per 0.93 us and workgroup with 258 workgroups);
+// what a launch loses is the 3 us to the first data and the skew of the last workgroups.
 #pragma once
 #include "common.h"
 
@@ -37,7 +39,7 @@ constexpr int SK_KB = 4;                   // k-blocks per stage
 constexpr int SK_FEAT = 128;               // features per workgroup
 constexpr int SK_MAX_PARTS = 8;            // k-ranges per product at most
 constexpr int SK_XROW = SK_KB * 64;        // bytes per token row of a stage's activation slab
-constexpr int SK_SLABS = 3;                // activation slabs in LDS = weight register sets
+constexpr int SK_SLABS = 4;                // activation slabs in LDS = weight register sets
 
 struct SkProblem {           // one product  act[T x K] . W^T,  W packed as [tiles][KB][64] fragments
   const uint16_t *act;       // row-major bf16
@@ -62,7 +64,7 @@ struct SkParams {
 
 // NB = 32-token blocks (1, 2 or 4)
 template <int NB>
-__global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 3 : 1) void skinny_kernel(const SkParams P) {
+__global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(const SkParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   __shared__ __attribute__((aligned(16))) unsigned char xs[SK_SLABS][NB * 32 * SK_XROW];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -147,27 +149,31 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 3 : 1) void skinny_kernel(con
       }
   };
 
-  // Stage s uses register set / slab s % 3.  Every stage issues exactly 8 + NX loads (those past
+  // Stage s uses register set / slab s % 4.  Every stage issues exactly 8 + NX loads (those past
   // the k-range read zeros through an out-of-range offset and cost no traffic), so "all but the
   // loads of the next stage have arrived" is one constant wait.
   if (n_stages > 0) {
-    u32x4_t w0[SK_KB * 2], w1[SK_KB * 2], w2[SK_KB * 2];
+    u32x4_t w0[SK_KB * 2], w1[SK_KB * 2], w2[SK_KB * 2], w3[SK_KB * 2];
     fetch_w(w0, 0); fetch_x(0, 0);
     fetch_w(w1, 1); fetch_x(1, 1);
+    fetch_w(w2, 2); fetch_x(2, 2);
     auto stage = [&](const u32x4_t (&w)[SK_KB * 2], u32x4_t (&wn)[SK_KB * 2], int st, int slab) {
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(SK_KB * 2 + NX) : "memory");   // stage st has arrived (this wavefront's part)
-      __builtin_amdgcn_s_barrier();                     // ... everywhere; nobody reads slab (st - 1) % 3 any more
+      // stage st has arrived (this wavefront's part): all but the loads of the next two stages
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((SK_SLABS - 2) * (SK_KB * 2 + NX)) : "memory");
+      __builtin_amdgcn_s_barrier();                     // ... everywhere; nobody reads slab (st - 1) % 4 any more
       asm volatile("" ::: "memory");
-      fetch_w(wn, st + 2);
-      fetch_x(st + 2, slab == 0 ? 2 : slab - 1);
+      fetch_w(wn, st + SK_SLABS - 1);
+      fetch_x(st + SK_SLABS - 1, slab == 0 ? SK_SLABS - 1 : slab - 1);
       compute(w, slab);
     };
-    for (int st = 0; st < n_stages; st += 3) {
-      stage(w0, w2, st, 0);
+    for (int st = 0; st < n_stages; st += 4) {
+      stage(w0, w3, st, 0);
       if (st + 1 >= n_stages) break;
       stage(w1, w0, st + 1, 1);
       if (st + 2 >= n_stages) break;
       stage(w2, w1, st + 2, 2);
+      if (st + 3 >= n_stages) break;
+      stage(w3, w2, st + 3, 3);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // drain the out-of-range tail loads
   }
