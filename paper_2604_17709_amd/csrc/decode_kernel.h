@@ -68,6 +68,7 @@ struct DecParams {
   long long part_stride;  // elements between part buffers = T16 * Rtot_pad
   int n_items2;         // work items of the up kernel
   int G1;               // workgroups of the down kernel: every one takes a non-empty range
+  int direct1;                // 1: one workgroup per rank tile sums the whole k range and writes t itself (no reduce kernel)
   unsigned long long *trace;  // optional [2][1024][8] wall-clock stamps (diagnostic), may be null
 };
 
@@ -369,7 +370,31 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
       }
       const int tok = nt * 16 + lrow;
-      if (PHASE == 1) {
+      if (PHASE == 1 && P.direct1) {
+        // this workgroup summed the whole k range of its rank tile: the result is final.  Round once
+        // to bf16 and store it where the upward kernel expects its activation operand (fragment
+        // order: (token tile, k-block) -> 1 KiB, lane = token % 16 + 16 * ((k % 32) / 8)); rows
+        // beyond T are zero.  Also the optional rank-space output (low-rank KV cache, Sec. 2.1).
+        const int col = dc.tile * 16 + lkg * 4;
+        if (tok >= P.T) s = make_float4(0.f, 0.f, 0.f, 0.f);
+        uint2 pk;
+        pk.x = pack_bf16x2(s.x, s.y);
+        pk.y = pack_bf16x2(s.z, s.w);
+        const int frag = nt * (P.Rtot_pad >> 5) + (col >> 5);
+        const int tl = lrow + 16 * ((col & 31) >> 3);
+        *(g_uint2_p)((const DEINFER_GLOBAL uint16_t *)uni_ptr(P.t) + (frag * 512 + tl * 8 + (col & 7))) = pk;
+        int pi = 0;
+        if (P.n_pairs > 1 && dc.tile >= P.p[1].tile0) pi = 1;
+        if (P.n_pairs > 2 && dc.tile >= P.p[2].tile0) pi = 2;
+        const DecPair &pr = P.p[pi];
+        if (pr.t_out != nullptr && tok < P.T) {
+          const int c0 = col - pr.tile0 * 16;
+          const float sv[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (c0 + v < pr.r) ((g_u16_p)pr.t_out)[(long long)tok * pr.ldt_out + c0 + v] = f32_to_bf16(sv[v]);
+        }
+      } else if (PHASE == 1) {
         // fp32 partial sums of this workgroup's share of the tile: 4 consecutive rank columns
         if (tok < P.T) {
           const DEINFER_GLOBAL float *base = (const DEINFER_GLOBAL float *)uni_ptr(P.part) + (long long)dc.part * P.part_stride;

@@ -206,13 +206,15 @@ int launch_decode_nt(const DecParams &P, bool glu, int grid2, hipStream_t s) {
     hipLaunchKernelGGL((decode_kernel<NT, false, 1>), dim3(P.G1), dim3(DEC_THREADS), 0, s, P);
   }
   if (int rc = check_launch("decode down kernel")) return rc;
-  const int T16 = NT * 16;
-  const long long n = (long long)T16 * (P.Rtot_pad / 4);
-  {
-    ProfScope ps(DEINFER_PROF_DECODE_REDUCE, s);
-    hipLaunchKernelGGL(decode_reduce_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, P, T16);
+  if (!P.direct1) {
+    const int T16 = NT * 16;
+    const long long n = (long long)T16 * (P.Rtot_pad / 4);
+    {
+      ProfScope ps(DEINFER_PROF_DECODE_REDUCE, s);
+      hipLaunchKernelGGL(decode_reduce_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, P, T16);
+    }
+    if (int rc = check_launch("decode reduce kernel")) return rc;
   }
-  if (int rc = check_launch("decode reduce kernel")) return rc;
   {
     ProfScope ps(DEINFER_PROF_DECODE_UP, s);
     if (glu) hipLaunchKernelGGL((decode_kernel<NT, true, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
@@ -267,10 +269,17 @@ int run_decode(const Group &gq, int64_t row0, int64_t T) {
   const long long total = (long long)P.n_rtiles * P.KB1;
   if (total * (long long)(2 * cus + 1) >= (1ll << 31) || T * gq.ldx >= (1ll << 30) || (long long)nt * 16 * P.Rtot_pad >= (1ll << 30))
     return fail(DEINFER_ERR_UNSUPPORTED, "problem too large for the decode schedule (%lld fragments)", total);
-  // two workgroups per compute unit for the down kernel (one streams while the other reduces)
-  int G1 = (int)(total < 2 * cus ? total : 2 * cus);
-  while (G1 > 1 && max_parts(total, P.KB1, G1) > DEC_MAX_PARTS) G1 = G1 * 7 / 8;
-  P.G1 = G1;
+  if (P.n_rtiles >= cus / 4) {
+    // enough rank tiles to keep the device streaming with one workgroup per tile: each sums the whole
+    // k range of its tile and writes t itself, which saves the partial sums and the reduce launch
+    P.G1 = P.n_rtiles;
+    P.direct1 = 1;
+  } else {
+    // two workgroups per compute unit for the down kernel (one streams while the other reduces)
+    int G1 = (int)(total < 2 * cus ? total : 2 * cus);
+    while (G1 > 1 && max_parts(total, P.KB1, G1) > DEC_MAX_PARTS) G1 = G1 * 7 / 8;
+    P.G1 = G1;
+  }
   P.trace = (g_trace && g_trace_bytes >= (size_t)2 * 1024 * 8 * sizeof(unsigned long long)) ? g_trace : nullptr;
   const size_t t_bytes = (size_t)round_up((int64_t)nt * 16 * P.Rtot_pad * 2, 256);
   P.t = reinterpret_cast<uint16_t *>(ws + WS_HEADER);

@@ -277,14 +277,23 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     c1 = __builtin_readcyclecounter();
     if (P.trace && blockIdx.x < 2048 && tid == 0) {
       unsigned long long *tr = P.trace + blockIdx.x * 8;
-      tr[2] = c0 - k_start; tr[3] = c1 - c0; tr[5] = c_wait; tr[6] = c_bar;
-      tr[7] = (unsigned long long)n_stages | ((unsigned long long)__builtin_amdgcn_s_getreg(63492) << 16) |
-              ((unsigned long long)__builtin_amdgcn_s_getreg(6164) << 48);
+      tr[2] = c0 - k_start; tr[3] = c1 - c0;
     }
     e_start = c1;
 #endif
-    __syncthreads();       // the epilogue reuses the LDS buffers
   }
+  // accumulators -> bf16 pairs first (registers only): it overlaps the wait for the slowest wavefront
+  uint2 pk[MB][4][4];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        pk[i][j][g].x = pack_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]);
+        pk[i][j][g].y = pack_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      }
+  __syncthreads();         // the epilogue reuses the LDS buffers
 
   // ---- epilogue: through LDS (free by now; the barrier above has passed), so that the global
   // stores are 16 bytes per lane and whole contiguous rows per group of lanes (storing straight
@@ -292,53 +301,58 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   // Accumulator element 4 g + e of block (i, j) is feature 32 i + 8 g + 4 (l / 32) + e of token
   // 32 j + l % 32.  Each wavefront keeps its tile [128 tokens][16 MF features] as bf16 in its own
   // LDS region: rows of CPR 16-byte chunks (8 features each), chunk position XORed with the row
-  // number, the two 8-byte halves of a chunk swapped in rows with bit 4 set.  Only the wavefront
-  // itself touches the region: no barrier.
+  // number, the two 8-byte halves of a chunk swapped in rows with bit 3 set (16 consecutive rows
+  // of one 8-byte write then cover 128 bytes of distinct banks).  Only the wavefront itself
+  // touches the region: no barrier.
+  // (lane-derived values are taken afresh so that none has to live through the main loop)
+  int tid_e = threadIdx.x;
+  asm volatile("" : "+v"(tid_e));
+  const int lane_e = tid_e & 63, wave_e = tid_e >> 6, wf_e = wave_e & 1, wt_e = wave_e >> 1;
   constexpr int CPR = 2 * MF;                      // chunks per row
   constexpr int PITCH = CPR * 16;
   constexpr int RPI = 64 / CPR;                    // token rows per store instruction
   static_assert(4 * 128 * PITCH <= (int)sizeof(PfShared<MF>), "epilogue tile fits the stage buffers");
-  unsigned char *E = smem_raw + wave * (128 * PITCH);
+  unsigned char *E = smem_raw + wave_e * (128 * PITCH);
   // this lane's chunk: 8 consecutive features
-  const int c = lane & (CPR - 1), rsub = lane / CPR;
+  const int c = lane_e & (CPR - 1), rsub = lane_e / CPR;
   uint16_t *const out = Q.out;
   const long long ldo = Q.ldo;
   const int width = Q.width;
-  const int col = (fb * BF_TILES + wf * MF) * 16 + c * 8;
+  const int col = (fb * BF_TILES + wf_e * MF) * 16 + c * 8;
   const bool lane_on = col < width;
   const bool wide = col + 8 <= width && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) && (ldo & 7) == 0;
-  const int tok_base = tok0 + wt * 128 + rsub;
+  const int tok_base = tok0 + wt_e * 128 + rsub;
   uint16_t *dst = out + (long long)tok_base * ldo + col;
   constexpr int NQ = 128 / RPI;                    // store instructions per wavefront
-  constexpr int HQ = NQ / 2;                       // ... handled in two batches (register budget)
+  constexpr int NBATCH = GLU ? 8 : 4, BQ = NQ / NBATCH;   // ... handled in batches (register budget)
   const bool lane_wide = lane_on && wide;
   // GLU: the gate values of a batch are requested one batch ahead (the first one before the
   // accumulators go through LDS), so their latency is covered
-  u32x4_t gate[2][GLU ? HQ : 1];
-  auto load_gate = [&](int h) {
+  u32x4_t gate[2][GLU ? BQ : 1];
+  auto load_gate = [&](int bt) {
 #pragma unroll
-    for (int qq = 0; qq < HQ; ++qq) {
-      const int q = h * HQ + qq;
-      gate[h][GLU ? qq : 0] = u32x4_t{0u, 0u, 0u, 0u};
+    for (int qq = 0; qq < BQ; ++qq) {
+      const int q = bt * BQ + qq;
+      gate[bt & 1][GLU ? qq : 0] = u32x4_t{0u, 0u, 0u, 0u};
       if (lane_wide && tok_base + q * RPI < P.T)
-        gate[h][GLU ? qq : 0] = *reinterpret_cast<const u32x4_t *>(dst + (long long)(q * RPI) * ldo);
+        gate[bt & 1][GLU ? qq : 0] = *reinterpret_cast<const u32x4_t *>(dst + (long long)(q * RPI) * ldo);
     }
   };
   if (GLU) load_gate(0);
+#ifdef DEINFER_PF_TRACE
+  unsigned long long es[4];
+  es[0] = __builtin_readcyclecounter();
+#endif
   {
-    const int wrow = lane & 31, wswz = lane & (CPR - 1);
-    const int whalf = ((lane >> 5) ^ ((lane >> 4) & 1)) * 8;
+    const int wrow = lane_e & 31, wswz = lane_e & (CPR - 1);
+    const int whalf = ((lane_e >> 5) ^ ((lane_e >> 3) & 1)) * 8;
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          uint2 pk;
-          pk.x = pack_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]);
-          pk.y = pack_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-          *reinterpret_cast<uint2 *>(E + (32 * j + wrow) * PITCH + (((4 * i + g) ^ wswz) * 16) + whalf) = pk;
-        }
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<uint2 *>(E + (32 * j + wrow) * PITCH + (((4 * i + g) ^ wswz) * 16) + whalf) = pk[i][j][g];
   }
   // h = silu(g) * u on the bf16 values of both products, one rounding of the result
   auto glu = [&](u32x4_t g, u32x4_t u) -> u32x4_t {
@@ -351,23 +365,39 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     }
     return r;
   };
+#ifdef DEINFER_PF_TRACE
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  es[1] = __builtin_readcyclecounter();
+#endif
+  // LDS reads of the next batch are issued before the stores of this one (different units)
+  u32x4_t d[2][BQ];
+  auto read_batch = [&](int bt, u32x4_t (&dd)[BQ]) {
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    if (GLU && h == 0) load_gate(1);
-    u32x4_t d[HQ];
-#pragma unroll
-    for (int qq = 0; qq < HQ; ++qq) {                // all reads of the batch first, then the stores
-      const int row = (h * HQ + qq) * RPI + rsub;
-      d[qq] = *reinterpret_cast<const u32x4_t *>(E + row * PITCH + ((c ^ (row & (CPR - 1))) * 16));
+    for (int qq = 0; qq < BQ; ++qq) {
+      const int row = (bt * BQ + qq) * RPI + rsub;
+      dd[qq] = *reinterpret_cast<const u32x4_t *>(E + row * PITCH + ((c ^ (row & (CPR - 1))) * 16));
     }
+  };
+  auto store_batch = [&](int bt, u32x4_t (&dd)[BQ]) {
 #pragma unroll
-    for (int qq = 0; qq < HQ; ++qq) {
-      const int q = h * HQ + qq;
-      if (((q * RPI) >> 4) & 1) d[qq] = u32x4_t{d[qq][2], d[qq][3], d[qq][0], d[qq][1]};
-      if (GLU) d[qq] = glu(gate[h][GLU ? qq : 0], d[qq]);
+    for (int qq = 0; qq < BQ; ++qq) {
+      const int q = bt * BQ + qq;
+      if (((q * RPI) >> 3) & 1) dd[qq] = u32x4_t{dd[qq][2], dd[qq][3], dd[qq][0], dd[qq][1]};
+      if (GLU) dd[qq] = glu(gate[bt & 1][GLU ? qq : 0], dd[qq]);
       if (lane_wide && tok_base + q * RPI < P.T)
-        *reinterpret_cast<u32x4_t *>(dst + (long long)(q * RPI) * ldo) = d[qq];
+        *reinterpret_cast<u32x4_t *>(dst + (long long)(q * RPI) * ldo) = dd[qq];
     }
+  };
+  read_batch(0, d[0]);
+#pragma unroll
+  for (int bt = 0; bt < NBATCH; ++bt) {
+    if (GLU && bt + 1 < NBATCH) load_gate(bt + 1);
+    if (bt + 1 < NBATCH) read_batch(bt + 1, d[(bt + 1) & 1]);
+    store_batch(bt, d[bt & 1]);
+#ifdef DEINFER_PF_TRACE
+    if (bt == NBATCH / 2 - 1) es[2] = __builtin_readcyclecounter();
+    if (bt == NBATCH - 1) es[3] = __builtin_readcyclecounter();
+#endif
   }
   // rare: output rows that are not 16-byte aligned, or the valid columns end inside this chunk
   if (lane_on && !wide) {
@@ -375,7 +405,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       if (tok_base + q * RPI >= P.T) break;
       const int row = q * RPI + rsub;
       u32x4_t d = *reinterpret_cast<const u32x4_t *>(E + row * PITCH + ((c ^ (row & (CPR - 1))) * 16));
-      if (((q * RPI) >> 4) & 1) d = u32x4_t{d[2], d[3], d[0], d[1]};
+      if (((q * RPI) >> 3) & 1) d = u32x4_t{d[2], d[3], d[0], d[1]};
       uint16_t *o = dst + (long long)(q * RPI) * ldo;
       for (int e = 0; e < 8; ++e) {
         if (col + e >= width) break;
@@ -389,6 +419,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   if (P.trace && blockIdx.x < 2048 && tid == 0) {
     unsigned long long *tr = P.trace + blockIdx.x * 8;
     tr[0] = w_start; tr[1] = wall_clock64(); tr[4] = __builtin_readcyclecounter() - e_start;
+    tr[5] = es[0] - e_start; tr[6] = es[1] - es[0]; tr[7] = ((es[2] - es[1]) << 32) | (es[3] - es[2]);
   }
 #endif
 #else
