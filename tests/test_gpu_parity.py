@@ -190,3 +190,58 @@ def test_linear_packed_beyond_decode_size(dn, T, d_in, r, d_out):
     y = dn.deinfer_lowrank_linear(to_dev(x), p, ws)
     ref = oracle.lowrank_linear(x.values, U.values, V.values)
     assert max_err(to_host(y), ref) <= TOL["bf16"]
+
+
+# ------------------------------------------------------------------ graph replay and determinism
+@pytest.mark.parametrize("T", [8, 64, 300])
+def test_graph_replay_matches_eager(dn, T):
+    """The four calls of a block captured into one HIP graph: every replay (with eager work and
+    synchronisations in between) must reproduce the eager result bit for bit, and that result
+    must match the oracle."""
+    import torch
+    d_in, d_ff = 256, 520
+    xq, Uq, Vq = gen(21, T, d_in, 72, d_in, "bf16", 1)
+    _, Ug, Vg = gen(21, T, d_in, 100, d_ff, "bf16", 4)
+    _, Uu, Vu = gen(21, T, d_in, 100, d_ff, "bf16", 8)
+    pq, k1 = pair(dn, Uq, Vq, packed=True)
+    pg, k2 = pair(dn, Ug, Vg, packed=True)
+    pu, k3 = pair(dn, Uu, Vu, packed=True)
+    ws = dn.Workspace(max(dn.deinfer_workspace_bytes(T, [pq]), dn.deinfer_workspace_bytes(T, [pg, pu])))
+    x = to_dev(xq)
+    y = torch.empty((T, d_in), dtype=torch.bfloat16, device="cuda")
+    h = torch.empty((T, d_ff), dtype=torch.bfloat16, device="cuda")
+    stream = torch.cuda.Stream()
+
+    def run():
+        dn.deinfer_lowrank_linear(x, pq, ws, out=y, stream=stream)
+        dn.deinfer_lowrank_gateup_silu(x, pg, pu, ws, out=h, stream=stream)
+
+    with torch.cuda.stream(stream):
+        run()
+    stream.synchronize()
+    y0, h0 = to_host(y).copy(), to_host(h).copy()
+    assert max_err(y0, oracle.lowrank_linear(xq.values, Uq.values, Vq.values)) <= TOL["bf16"]
+    assert max_err(h0, oracle.lowrank_gateup_silu(xq.values, Ug.values, Vg.values, Uu.values, Vu.values)) <= TOL["bf16"]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        run()
+    for it in range(3):
+        y.zero_(); h.zero_()                               # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(y), y0), "replay %d: linear differs from the eager result" % it
+        assert np.array_equal(to_host(h), h0), "replay %d: gate/up differs from the eager result" % it
+    ws.check()
+
+
+@pytest.mark.parametrize("T", [1, 48, 200])
+def test_results_are_deterministic(dn, T):
+    """Partial sums are added in a fixed order on every path: repeated calls give identical bits."""
+    x, U, V = gen(23, T, 1096, 300, 520, "bf16")
+    p, keep = pair(dn, U, V, packed=True)
+    ws = ws_for(dn, T, [p])
+    xd = to_dev(x)
+    first = to_host(dn.deinfer_lowrank_linear(xd, p, ws)).copy()
+    for _ in range(3):
+        assert np.array_equal(to_host(dn.deinfer_lowrank_linear(xd, p, ws)), first)
