@@ -15,6 +15,7 @@
 #include "pack_kernels.h"
 #include "prefill_kernel.h"
 #include "skinny_kernel.h"
+#include "stream_kernel.h"
 
 using namespace deinfer;
 
