@@ -245,3 +245,36 @@ def test_results_are_deterministic(dn, T):
     first = to_host(dn.deinfer_lowrank_linear(xd, p, ws)).copy()
     for _ in range(3):
         assert np.array_equal(to_host(dn.deinfer_lowrank_linear(xd, p, ws)), first)
+
+
+# ------------------------------------------------------------------ 16 < T <= 32: one-launch stages
+@pytest.mark.parametrize("T", [17, 20, 32])
+def test_stream_stage_odd_shapes(dn, T):
+    """Stages with at least 100 blocks of 32 features run as one launch with the k split inside the
+    workgroup: a wide second stage (odd tile count, ragged last block) and a wide first stage
+    (rank not a multiple of 32), plus the GLU pairing and the rank-space copy."""
+    import torch
+    # wide second stage: d_out = 3300 -> 207 tiles of 16 -> 104 blocks; k = r_pad = 128
+    x, U, V = gen(31, T, 264, 100, 3300, "bf16")
+    p, keep = pair(dn, U, V, packed=True)
+    ws = ws_for(dn, T, [p])
+    y = dn.deinfer_lowrank_linear(to_dev(x), p, ws)
+    assert max_err(to_host(y), oracle.lowrank_linear(x.values, U.values, V.values)) <= TOL["bf16"]
+    # GLU over the same width
+    _, U2, V2 = gen(31, T, 264, 72, 3300, "bf16", 5)
+    p2, keep2 = pair(dn, U2, V2, packed=True)
+    ws2 = ws_for(dn, T, [p, p2])
+    h = dn.deinfer_lowrank_gateup_silu(to_dev(x), p, p2, ws2)
+    ref = oracle.lowrank_gateup_silu(x.values, U.values, V.values, U2.values, V2.values)
+    assert max_err(to_host(h), ref) <= TOL["bf16"]
+    # wide first stage: r = 3210 -> r_pad = 3232 -> 101 blocks; narrow second stage
+    x3, U3, V3 = gen(32, T, 136, 3210, 72, "bf16")
+    p3, keep3 = pair(dn, U3, V3, packed=True)
+    ws3 = ws_for(dn, T, [p3, p3, p3])
+    tk = torch.zeros((T, 3210), dtype=torch.bfloat16, device="cuda")
+    q, k, v = dn.deinfer_lowrank_qkv(to_dev(x3), p3, p3, p3, ws3, t_k=tk)
+    rq, rk, rv, rtk, rtv = oracle.lowrank_qkv(x3.values, U3.values, V3.values, U3.values, V3.values,
+                                              U3.values, V3.values, return_t=True)
+    assert max_err(to_host(q), rq) <= TOL["bf16"]
+    assert max_err(to_host(v), rv) <= TOL["bf16"]
+    assert max_err(to_host(tk), rtk) <= TOL["bf16"]
