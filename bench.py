@@ -9,7 +9,10 @@ synthetic tensors of the named shape, resident in HBM before the timed region.  
 the 256 MB last-level cache from serving the weights, consecutive steps rotate through
 several independent copies of the packed weights (>= 1.5 GB in total).
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (tokens/s of the step), ms_per_step, per-call timings,
+"roofline" (the dominant launch of the slowest call, timed with HIP events that the library
+records around that launch, against the HBM or bf16 MFMA peak) and "cpu_baseline" (the fp64
+oracle on the host's cores, on a bounded sample of the same workload).
 """
 from __future__ import annotations
 
