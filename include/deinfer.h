@@ -174,11 +174,27 @@ int deinfer_lowrank_qkv(const void *x, int64_t T, int64_t ldx,
  * GLU-type MLP first sub-layer (Sec. 4.1 "activation computation", Table 2 GLU-based):
  *   h = silu((x U_g) V_g) * ((x U_u) V_u),   silu(z) = z / (1 + exp(-z)),
  * element-wise product, evaluated in fp32 and rounded once.  Both pairs share d_in
- * and d_out (= FFN width); the full-width gate and up results never reach memory.
+ * and d_out (= FFN width).  For T <= 128 the full-width gate and up results never reach
+ * memory in the output type; for larger T the gate product is staged (bf16) in h itself
+ * before the final values overwrite it.
  */
 int deinfer_lowrank_gateup_silu(const void *x, int64_t T, int64_t ldx,
                                 const deinfer_factors_t *fgate, const deinfer_factors_t *fup,
                                 void *h, int64_t ldh, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Upward projection alone (Sec. 2.1 / 4.1: the low-rank KV cache stores k_low_rank = x U_k and
+ * v_low_rank = x U_v; keys and values are rebuilt as k = k_low_rank V_k when attention needs
+ * them):  y[T x d_out] = t[T x r] . V.   t: device, row-major, pitch ldt >= r, same dtype as
+ * the pair.  f must describe a whole valid pair, as for every other call, although only f->V,
+ * f->r and f->d_out enter the product.  With PACKED pairs t must be 16-byte
+ * aligned with ldt % 8 == 0 and ldt >= r rounded up to a multiple of 8, and the columns
+ * r .. (r rounded up to 8) - 1 of every row must hold finite values (they meet zero weights).
+ * The rows written by deinfer_lowrank_qkv's t_k / t_v outputs into a zero-filled buffer of
+ * such a pitch qualify.  Otherwise the contract of deinfer_lowrank_linear.
+ */
+int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_factors_t *f,
+                       void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * MLP second sub-layer (Sec. 4.1): y = (h U_d) V_d with d_in = FFN width.

@@ -54,7 +54,7 @@ EXPORTS = [
     "deinfer_packed_bytes", "deinfer_pack_factors",
     "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
     "deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
-    "deinfer_lowrank_down",
+    "deinfer_lowrank_down", "deinfer_lowrank_up",
 ]
 
 _lib = None
@@ -81,6 +81,7 @@ def lib() -> ctypes.CDLL:
         L.deinfer_workspace_check.argtypes = [_vp, _sz, _vp]
         L.deinfer_lowrank_linear.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_down.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
+        L.deinfer_lowrank_up.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_qkv.argtypes = [_vp, _i64, _i64, FP, FP, FP,
                                           _vp, _i64, _vp, _i64, _vp, _i64,
                                           _vp, _i64, _vp, _i64, _vp, _sz, _vp]
@@ -241,6 +242,17 @@ def deinfer_lowrank_down(h, pair: Pair, ws: Workspace, out=None, stream=None):
         out = torch.empty((T, pair.d_out), dtype=h.dtype, device=h.device)
     _check(lib().deinfer_lowrank_down(_ptr(h), T, _ld(h), ctypes.byref(pair.desc),
                                       _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
+    return out
+
+
+def deinfer_lowrank_up(t, pair: Pair, ws: Workspace, out=None, stream=None):
+    """y = t V: the upward projection alone (rebuilding keys / values from the low-rank cache)."""
+    import torch
+    T = _rows(t, "t")
+    if out is None:
+        out = torch.empty((T, pair.d_out), dtype=t.dtype, device=t.device)
+    _check(lib().deinfer_lowrank_up(_ptr(t), T, _ld(t), ctypes.byref(pair.desc),
+                                    _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
     return out
 
 

@@ -153,7 +153,7 @@ size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
     const size_t tdec = (size_t)round_up((int64_t)nt * 16 * rp * 2, 256) + (size_t)DEC_MAX_PARTS * nt * 16 * rp * 4;
     const size_t tpre = T > 128 ? (size_t)round_up(T, 256) * rp * 2 : 0;
     scratch = round_up((int64_t)tdec, 256) + round_up((int64_t)tpre, 256);
-    if (T > 16 && T <= 128) {
+    if (T <= 128) {          // (the upward-projection-only call uses this schedule for every T <= 128)
       const SkPlan pl = skinny_plan(T, pairs, n);
       const size_t sk = pl.t_bytes + pl.part_bytes;
       if (sk > scratch) scratch = sk;
@@ -197,6 +197,7 @@ struct Group {
   void *out[3]; int64_t ldo[3];            // per pair output (GLU: only [0])
   void *t_out[3]; int64_t ldt[3];          // optional rank-space outputs
   bool glu;
+  bool up_only;                            // x is the rank-space intermediate t: only the upward projection runs
   void *ws; size_t ws_bytes; hipStream_t stream;
 };
 
@@ -306,6 +307,16 @@ int run_generic(const Group &gq) {
   int64_t off[3] = {0, 0, 0};
   int64_t acc = 0;
   for (int i = 0; i < gq.n; ++i) { off[i] = acc; acc += gq.f[i]->r; }
+  if (gq.up_only) {
+    // the caller's rank-space rows are the activation operand of the upward projection
+    const deinfer_factors_t *f = gq.f[0];
+    dim3 grid((unsigned)ceil_div(f->d_out, GT), (unsigned)ceil_div(T, GT));
+    hipLaunchKernelGGL((gemm_generic_kernel<TE, TE, TE, false>), grid, dim3(GTHREADS), 0, gq.stream,
+                       x, gq.ldx, static_cast<const TE *>(f->V), f->ldv, (int)f->r,
+                       (const TE *)nullptr, (int64_t)0, (const TE *)nullptr, (int64_t)0, 0,
+                       static_cast<TE *>(gq.out[0]), gq.ldo[0], (int)T, (int)f->d_out);
+    return check_launch("generic upward projection");
+  }
   // stage 1: t[:, off_i : off_i + r_i] = x . U_i   (downward projections, Sec. 4.1)
   for (int i = 0; i < gq.n; ++i) {
     const deinfer_factors_t *f = gq.f[i];
@@ -363,7 +374,11 @@ int run_group(Group gq) {
   const int dtype = gq.f[0]->dtype;
   const size_t es = elem_size(dtype);
   if (!gq.x) return fail(DEINFER_ERR_INVALID_ARG, "activation pointer is NULL");
-  if (gq.ldx < gq.f[0]->d_in) return fail(DEINFER_ERR_INVALID_ARG, "ldx smaller than d_in");
+  if (gq.up_only) {
+    if (gq.ldx < gq.f[0]->r) return fail(DEINFER_ERR_INVALID_ARG, "ldt smaller than r");
+  } else if (gq.ldx < gq.f[0]->d_in) {
+    return fail(DEINFER_ERR_INVALID_ARG, "ldx smaller than d_in");
+  }
   if (!aligned(gq.x, es)) return fail(DEINFER_ERR_MISALIGNED, "activation pointer not aligned to the element size");
   const int n_out = gq.glu ? 1 : gq.n;
   for (int i = 0; i < n_out; ++i) {
@@ -382,7 +397,11 @@ int run_group(Group gq) {
   if (gq.ws_bytes < need)
     return fail(DEINFER_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", gq.ws_bytes, need);
   const bool packed = gq.f[0]->layout == DEINFER_LAYOUT_PACKED;
-  if (packed) {
+  if (packed && gq.up_only) {
+    if (!aligned(gq.x, 16) || gq.ldx % 8 != 0 || gq.ldx < round_up(gq.f[0]->r, 8))
+      return fail(DEINFER_ERR_MISALIGNED,
+                  "packed pairs need 16-byte aligned rank-space rows with ldt %% 8 == 0 and ldt >= r rounded up to 8");
+  } else if (packed) {
     if (!aligned(gq.x, 16) || gq.ldx % 8 != 0 || gq.f[0]->d_in % 8 != 0)
       return fail(DEINFER_ERR_MISALIGNED,
                   "packed pairs need 16-byte aligned activations, ldx %% 8 == 0 and d_in %% 8 == 0");
@@ -415,7 +434,7 @@ int run_group(Group gq) {
 
   // ---- dispatch
   if (!packed) return dtype == DEINFER_BF16 ? run_generic<uint16_t>(gq) : run_generic<float>(gq);
-  if (gq.T <= 16) return run_decode(gq, 0, gq.T);
+  if (gq.T <= 16 && !gq.up_only) return run_decode(gq, 0, gq.T);
   if (gq.T <= 128) return run_skinny(gq);
   return run_prefill(gq);
 }
@@ -543,6 +562,15 @@ int deinfer_lowrank_linear(const void *x, int64_t T, int64_t ldx, const deinfer_
   memset(&g, 0, sizeof(g));
   g.x = x; g.T = T; g.ldx = ldx; g.n = 1; g.f[0] = f; g.out[0] = y; g.ldo[0] = ldy;
   g.glu = false; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
+  return run_group(g);
+}
+
+int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_factors_t *f,
+                       void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream) {
+  Group g;
+  memset(&g, 0, sizeof(g));
+  g.x = t; g.T = T; g.ldx = ldt; g.n = 1; g.f[0] = f; g.out[0] = y; g.ldo[0] = ldy;
+  g.glu = false; g.up_only = true; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
   return run_group(g);
 }
 

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(deinfer_[a-z_]+)\s*\(", header))
     assert {"deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
-            "deinfer_lowrank_down"} <= declared
+            "deinfer_lowrank_down", "deinfer_lowrank_up"} <= declared
     L = ctypes.CDLL(dn.LIB_PATH)
     for name in sorted(declared):
         assert hasattr(L, name), name
@@ -84,6 +84,31 @@ def test_linear_argument_validation():
     assert _linear(make(layout=dn.LAYOUT_PACKED), ldx=68) == dn.ERR_MISALIGNED           # ldx % 8
     # T == 0 is a successful no-op (checked after the descriptor, before any pointer use)
     assert _linear(make(), T=0, x=None, y=None, ws=None, ws_bytes=0) == dn.OK
+
+
+def _up(f, t=FAKE + 0x200000, T=4, ldt=None, y=FAKE + 0x300000, ldy=None, ws=FAKE + 0x400000, ws_bytes=1 << 26):
+    return dn.lib().deinfer_lowrank_up(t, T, f.r if ldt is None else ldt, ctypes.byref(f),
+                                       y, f.d_out if ldy is None else ldy, ws, ws_bytes, None)
+
+
+def test_up_projection_argument_validation():
+    L = dn.lib()
+    assert L.deinfer_lowrank_up(FAKE, 4, 16, None, FAKE, 48, FAKE, 1 << 20, None) == dn.ERR_INVALID_ARG
+    assert _up(make(), t=None) == dn.ERR_INVALID_ARG
+    assert _up(make(), y=None) == dn.ERR_INVALID_ARG
+    assert _up(make(), ldt=8) == dn.ERR_INVALID_ARG             # ldt < r
+    assert "ldt" in dn.last_error()
+    assert _up(make(), ldy=10) == dn.ERR_INVALID_ARG
+    assert _up(make(V=None)) == dn.ERR_INVALID_ARG
+    assert _up(make(), ws=None) == dn.ERR_WORKSPACE
+    # the rank-space operand is narrower than d_in: a pitch between r and d_in is fine
+    assert _up(make(d_in=64, r=16), T=0, ldt=16) == dn.OK
+    # packed pairs: 16-byte rows, pitch a multiple of 8 and at least r rounded up to 8
+    pk = dict(layout=dn.LAYOUT_PACKED, r=12)
+    assert _up(make(**pk), ldt=12) == dn.ERR_MISALIGNED         # covers r but not whole 16-byte chunks
+    assert _up(make(**pk), ldt=20) == dn.ERR_MISALIGNED
+    assert _up(make(**pk), ldt=16, t=FAKE + 0x200002) == dn.ERR_MISALIGNED
+    assert _up(make(**pk), T=0, ldt=16, t=None, y=None, ws=None, ws_bytes=0) == dn.OK
 
 
 def test_group_calls_validate_shared_properties():

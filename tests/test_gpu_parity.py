@@ -278,3 +278,40 @@ def test_stream_stage_odd_shapes(dn, T):
     assert max_err(to_host(q), rq) <= TOL["bf16"]
     assert max_err(to_host(v), rv) <= TOL["bf16"]
     assert max_err(to_host(tk), rtk) <= TOL["bf16"]
+
+
+# ------------------------------------------------------------------ upward projection alone (low-rank KV cache)
+@pytest.mark.parametrize("packed", [False, True])
+@pytest.mark.parametrize("T", [5, 40, 128, 300, 2000])
+def test_up_projection_alone(dn, packed, T):
+    """y = t V on caller-provided rank-space rows (rank not a multiple of 8, padded pitch)."""
+    import torch
+    r, d_in, d_out = 204 + 6, 136, 520                 # r % 8 == 2
+    _, U, V = gen(41, 4, d_in, r, d_out, "bf16")
+    tt = si.make(41, 9, (T, r), 1.0, "bf16")
+    p, keep = pair(dn, U, V, packed=packed)
+    ws = ws_for(dn, T, [p])
+    ld = 216                                            # r rounded up to 8; padding columns zero
+    t_dev = torch.zeros((T, ld), dtype=torch.bfloat16, device="cuda")
+    t_dev[:, :r] = to_dev(tt)
+    y = dn.deinfer_lowrank_up(t_dev[:, :r], p, ws)
+    ref = oracle.up_projection(tt.values, V.values)
+    assert max_err(to_host(y), ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("T", [8, 64, 300])
+def test_keys_rebuilt_from_the_low_rank_cache(dn, T):
+    """t_k written by the qkv call, then the upward projection alone on it: the same keys as
+    the qkv call produced, to the bit where both run the same schedule, and within the
+    tolerance of the oracle everywhere."""
+    import torch
+    d_in, r, d_out = 264, 96, 200
+    x, U, V = gen(43, T, d_in, r, d_out, "bf16")
+    p, keep = pair(dn, U, V, packed=True)
+    ws = ws_for(dn, T, [p, p, p])
+    tk = torch.zeros((T, r), dtype=torch.bfloat16, device="cuda")
+    q, k, v = dn.deinfer_lowrank_qkv(to_dev(x), p, p, p, ws, t_k=tk)
+    k2 = dn.deinfer_lowrank_up(tk, p, ws)
+    ref = oracle.lowrank_linear(x.values, U.values, V.values)
+    assert max_err(to_host(k2), ref) <= TOL["bf16"]
+    assert max_err(to_host(k2), to_host(k).astype(np.float64)) <= 2.0 ** -7    # at most an output rounding apart
