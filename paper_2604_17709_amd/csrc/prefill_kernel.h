@@ -101,7 +101,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 
 #ifdef DEINFER_PF_TRACE
   const unsigned long long w_start = wall_clock64(), k_start = __builtin_readcyclecounter();
-  unsigned long long e_start = 0;
+  unsigned long long e_start = 0, c_wait_all = 0, c_bar_all = 0;
 #endif
   constexpr int MB = MF / 2;                       // 32-feature blocks per wavefront
   f32x16_t acc[MB][4];                             // [feature block][32-token block]
@@ -204,30 +204,37 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();          // stage 0 has landed everywhere
     asm volatile("" ::: "memory");
-    u32x4_t a0[MB], a1[MB], bc, bn;
+    // Operand reads run two groups of products ahead of their use (a group = the MB products that
+    // share one token operand, about 130 cycles): with the four wavefronts reading in step and the
+    // incoming tiles being written, one group of cover left the products waiting for LDS.
+    u32x4_t a0[MB], a1[MB], b[4];
 #pragma unroll
     for (int i = 0; i < MB; ++i) a0[i] = read_a(0, i, 0);
-    bc = read_b(0, 0, 0);
+    b[0] = read_b(0, 0, 0);
+    b[1] = read_b(0, 1, 0);
     // one stage; F2: the second half of stage st + 2 is still to be requested, F3: stage st + 3 exists
     auto stage = [&](int st, auto f2, auto f3) {
       constexpr bool F2 = decltype(f2)::value, F3 = decltype(f3)::value;
       const int buf = st & (PF_STAGES - 1);
       const int nbuf = (st + 1) & (PF_STAGES - 1);
-      // ---- k-step 0 of the stage; the feature operands of k-step 1 are read along the way
+      // token operand of group g of this stage (g = 4 * k-step + token block); 8, 9 = next stage's 0, 1
+      auto read_bg = [&](int g) -> u32x4_t { return g < 8 ? read_b(buf, g & 3, g >> 2) : read_b(nbuf, g - 8, 0); };
+      // ---- k-step 0 of the stage; the feature operands of k-step 1 are read along the way.
+      // At most one memory instruction follows each product: its issue then hides behind the
+      // product's 32 cycles in the matrix pipeline (several in a row after a group held the next
+      // product up by about 40 cycles per group).
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        bn = j < 3 ? read_b(buf, j + 1, 0) : read_b(buf, 0, 1);
-        if (j < MB) a1[j] = read_a(buf, j, 1);
-        // the operand reads for the next group are issued before this group's products, not after
-        // (in-order issue: a read placed behind four products starts 100 cycles late)
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a0[i]), as_bf16x8(bc), acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a0[i]), as_bf16x8(b[j]), acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
           if (F2 && i == 0 && H1 + j < LPS) fetch_part(st + 2, H1 + j);
+          if (i == 1 || MB == 1) b[(j + 2) & 3] = read_bg(j + 2);
+          if (i == 2 && j < 3 && (j == 0 ? 0 : j + 1) < MB) a1[j == 0 ? 0 : j + 1] = read_a(buf, j == 0 ? 0 : j + 1, 1);
+          if (i == 3 && j == 0 && MB > 1) a1[1] = read_a(buf, 1, 1);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
-        bc = bn;
       }
       // ---- stage st + 1 has landed (this wavefront's part), barrier: it has landed everywhere and
       // nobody reads the buffer of stage st - 1 any more, which is where stage st + 3 goes
@@ -253,16 +260,17 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       // (after the last stage these read a stage buffer nobody writes any more; the values are unused)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        bn = j < 3 ? read_b(buf, j + 1, 1) : read_b(nbuf, 0, 0);
-        if (j < MB) a0[j] = read_a(nbuf, j, 0);              // a0 is not in use during k-step 1
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a1[i]), as_bf16x8(bc), acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a1[i]), as_bf16x8(b[j]), acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
           if (F3 && i == 0 && j < H1) fetch_part(st + 3, j);
+          if (i == 1 || MB == 1) b[(j + 2) & 3] = read_bg(j + 6);
+          // a0 is not in use during k-step 1
+          if (i == 2 && j < 3 && (j == 0 ? 0 : j + 1) < MB) a0[j == 0 ? 0 : j + 1] = read_a(nbuf, j == 0 ? 0 : j + 1, 0);
+          if (i == 3 && j == 0 && MB > 1) a0[1] = read_a(nbuf, 1, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
-        bc = bn;
       }
     };
     {
@@ -279,7 +287,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       unsigned long long *tr = P.trace + blockIdx.x * 8;
       tr[2] = c0 - k_start; tr[3] = c1 - c0;
     }
-    e_start = c1;
+    e_start = c1; c_wait_all = c_wait; c_bar_all = c_bar;
 #endif
   }
   // accumulators -> bf16 pairs first (registers only): it overlaps the wait for the slowest wavefront
@@ -420,6 +428,9 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     unsigned long long *tr = P.trace + blockIdx.x * 8;
     tr[0] = w_start; tr[1] = wall_clock64(); tr[4] = __builtin_readcyclecounter() - e_start;
     tr[5] = es[0] - e_start; tr[6] = es[1] - es[0]; tr[7] = ((es[2] - es[1]) << 32) | (es[3] - es[2]);
+#if DEINFER_PF_TRACE == 2
+    tr[5] = c_wait_all; tr[6] = c_bar_all;     // loop split instead of the epilogue split
+#endif
   }
 #endif
 #else
