@@ -11,7 +11,9 @@ several independent copies of the packed weights (>= 1.5 GB in total).
 
 Prints ONE JSON line: metric, value (tokens/s of the step), ms_per_step, per-call timings,
 "roofline" (the dominant launch of the slowest call, timed with HIP events that the library
-records around that launch, against the HBM or bf16 MFMA peak) and "cpu_baseline" (the fp64
+records around that launch, against the HBM or bf16 MFMA peak; "measured_ceiling" inside it is
+what a plain read of the same bytes, or a loop of nothing but matrix products, reaches on the
+same device) and "cpu_baseline" (the fp64
 oracle on the host's cores, on a bounded sample of the same workload).
 """
 from __future__ import annotations
@@ -289,6 +291,66 @@ def main():
     roofline["algorithmic_bytes_per_launch"] = kbytes[kdom]
     roofline["algorithmic_flops_per_launch"] = kflops[kdom]
     roofline["launches_of_this_call_us"] = {k: round(v * 1e6, 2) for k, v in ktimes.items()}
+
+    # ---- measured ceilings of this device beside the published ones (plain kernels of the library
+    # that do nothing but read, or nothing but multiply; timed with events on the launch stream)
+    def events_us(fn, n, warm=3):
+        a0 = torch.cuda.Event(enable_timing=True); a1 = torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            for i in range(warm):
+                fn(i)
+            a0.record(stream)
+            for i in range(n):
+                fn(warm + i)
+            a1.record(stream)
+        stream.synchronize()
+        return a0.elapsed_time(a1) * 1e3 / n
+
+    sink = torch.empty(dn.PROBE_SINK_BYTES, dtype=torch.uint8, device="cuda")
+    if bound == "hbm":
+        pool = torch.empty(2 << 30, dtype=torch.uint8, device="cuda").random_(0, 256)
+        nb = (int(kbytes[kdom]) + 1023) // 1024 * 1024
+        slots = max(1, pool.numel() // nb)
+        torch.cuda.synchronize()           # the fill ran on another stream
+        p0, sk, skn = pool.data_ptr(), sink.data_ptr(), sink.numel()      # plain integers: no per-launch host work
+        def rd(off, n):
+            if L.deinfer_probe_stream_read(p0 + off, n, sk, skn, sh) != 0:
+                raise RuntimeError(dn.last_error())
+        same_us = events_us(lambda i: rd((i % slots) * nb, nb), 60)
+        long_us = events_us(lambda i: rd(0, pool.numel()), 5, warm=1)
+        roofline["measured_ceiling"] = {
+            "what": "deinfer_probe_stream_read: a plain coalesced read, rotating through a 2 GiB pool",
+            "read_of_the_same_bytes_us": round(same_us, 2), "read_of_the_same_bytes_GBs": round(nb / same_us / 1e3, 1),
+            "long_stream_GBs": round(pool.numel() / long_us / 1e3, 1),
+            "launch_time_over_plain_read_time": round(ksec * 1e6 / same_us, 3)}
+        del pool
+    else:
+        fl = [0.0]
+        def mf(i):
+            fl[0] = dn.deinfer_probe_mfma_bf16(x, 4000, sink, stream)
+        torch.cuda.synchronize()
+        mf_us = events_us(mf, 5, warm=1)
+        Kd, Nd = ((ranks[ps[-1]], proj[ps[-1]][1]) if kdom == "up" else (proj[ps[0]][0], sum(ranks[p] for p in ps)))
+        ga = torch.randn((T, Kd), device="cuda").to(bf); gb = (torch.randn((Kd, Nd), device="cuda") * 0.02).to(bf)
+        gc = torch.empty((T, Nd), dtype=bf, device="cuda")
+        torch.cuda.synchronize()
+        gemm_us = events_us(lambda i: torch.matmul(ga, gb, out=gc), 20)
+        Kp = (Kd + 31) // 32 * 32          # the k extent of the packed format (zero padded)
+        gap = torch.zeros((T, Kp), dtype=bf, device="cuda"); gap[:, :Kd] = ga
+        gbp = torch.zeros((Kp, Nd), dtype=bf, device="cuda"); gbp[:Kd] = gb
+        torch.cuda.synchronize()
+        gemm_pad_us = events_us(lambda i: torch.matmul(gap, gbp, out=gc), 20)
+        roofline["measured_ceiling"] = {
+            "what": "deinfer_probe_mfma_bf16: back-to-back 32x32x16 bf16 products on register operands (activation values), "
+                    "one wavefront per SIMD, no memory traffic",
+            "products_only_TFLOPs": round(fl[0] / mf_us / 1e6, 1),
+            "frac_of_products_only": round(ach / (fl[0] / mf_us / 1e6), 4),
+            "context_vendor_gemm": {"what": "torch.matmul (bf16, random operands) of the same T x K x N as this launch, "
+                                            "without its epilogue work; not part of the path",
+                                    "K": int(Kd), "N": int(Nd), "us": round(gemm_us, 2),
+                                    "TFLOPs": round(2.0 * T * Kd * Nd / gemm_us / 1e6, 1),
+                                    "us_with_K_zero_padded_to_%d" % Kp: round(gemm_pad_us, 2)}}
+        del ga, gb, gc, gap, gbp
 
     step_bytes = sum(c["bytes"] for c in per_call.values())
     step_flops = sum(c["flops"] for c in per_call.values())

@@ -99,6 +99,25 @@ int deinfer_set_profile_events(int which, void *start_event, void *stop_event);
 int deinfer_set_trace_buffer(void *buf, size_t bytes);
 
 /*
+ * Measurement aids: what this device delivers on the two rooflines of the path (Sec. 5 reports
+ * throughput only; the denominators are this build's), for a benchmark that prints a measured
+ * ceiling beside the published one.  Both enqueue one kernel on `stream`, allocate nothing and
+ * do not synchronise.  sink: device scratch of at least DEINFER_PROBE_SINK_BYTES, 16-byte
+ * aligned, contents undefined afterwards.
+ *   deinfer_probe_stream_read  reads buf[0 .. bytes) once (bytes a positive multiple of 1024,
+ *                              buf 16-byte aligned, device) with plain coalesced loads.
+ *   deinfer_probe_mfma_bf16    every wavefront of a one-workgroup-per-compute-unit grid issues
+ *                              8 * n_rounds bf16 32x32x16 matrix products back to back on register
+ *                              operands taken from `operands` (device, >= 8192 bytes of bf16
+ *                              values, 16-byte aligned); *flops_out (host, may be NULL) receives
+ *                              the floating-point operations of the launch.
+ */
+#define DEINFER_PROBE_SINK_BYTES ((size_t)1 << 20)
+int deinfer_probe_stream_read(const void *buf, size_t bytes, void *sink, size_t sink_bytes, void *stream);
+int deinfer_probe_mfma_bf16(const void *operands, size_t operand_bytes, int64_t n_rounds,
+                            void *sink, size_t sink_bytes, void *stream, double *flops_out);
+
+/*
  * Rank that keeps a fraction (1 - param_reduction) of the m*n parameters of a weight:
  *     r = floor((1 - param_reduction) * m * n / (m + n))
  * since a pair of inner size k holds (m + n) k parameters (Sec. 2.1).  The ratio is

@@ -50,7 +50,7 @@ class DeinferError(RuntimeError):
 
 EXPORTS = [
     "deinfer_last_error", "deinfer_version", "deinfer_set_profile_events", "deinfer_set_trace_buffer",
-    "deinfer_rank_for_ratio",
+    "deinfer_rank_for_ratio", "deinfer_probe_stream_read", "deinfer_probe_mfma_bf16",
     "deinfer_packed_bytes", "deinfer_pack_factors",
     "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
     "deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.deinfer_set_trace_buffer.argtypes = [_vp, _sz]
         L.deinfer_set_profile_events.argtypes = [ctypes.c_int, _vp, _vp]
         L.deinfer_rank_for_ratio.argtypes = [_i64, _i64, ctypes.c_double, ctypes.POINTER(_i64)]
+        L.deinfer_probe_stream_read.argtypes = [_vp, _sz, _vp, _sz, _vp]
+        L.deinfer_probe_mfma_bf16.argtypes = [_vp, _sz, _i64, _vp, _sz, _vp, ctypes.POINTER(ctypes.c_double)]
         L.deinfer_packed_bytes.argtypes = [FP, ctypes.POINTER(_sz)]
         L.deinfer_pack_factors.argtypes = [FP, _vp, _sz, FP, _vp]
         L.deinfer_workspace_bytes.argtypes = [_i64, ctypes.POINTER(FP), ctypes.c_int, ctypes.POINTER(_sz)]
@@ -243,6 +245,24 @@ def deinfer_lowrank_down(h, pair: Pair, ws: Workspace, out=None, stream=None):
     _check(lib().deinfer_lowrank_down(_ptr(h), T, _ld(h), ctypes.byref(pair.desc),
                                       _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
     return out
+
+
+PROBE_SINK_BYTES = 1 << 20
+
+
+def deinfer_probe_stream_read(buf, nbytes: int, sink, stream=None) -> None:
+    """Measurement aid: one plain read of the first ``nbytes`` of ``buf`` (a multiple of 1024)."""
+    _check(lib().deinfer_probe_stream_read(_ptr(buf), int(nbytes), _ptr(sink), sink.numel() * sink.element_size(),
+                                           _stream(stream)))
+
+
+def deinfer_probe_mfma_bf16(operands, n_rounds: int, sink, stream=None) -> float:
+    """Measurement aid: back-to-back bf16 matrix products on register operands; returns the launch's flops."""
+    fl = ctypes.c_double(0.0)
+    _check(lib().deinfer_probe_mfma_bf16(_ptr(operands), operands.numel() * operands.element_size(), int(n_rounds),
+                                         _ptr(sink), sink.numel() * sink.element_size(), _stream(stream),
+                                         ctypes.byref(fl)))
+    return float(fl.value)
 
 
 def deinfer_lowrank_up(t, pair: Pair, ws: Workspace, out=None, stream=None):

@@ -16,6 +16,7 @@
 #include "prefill_kernel.h"
 #include "skinny_kernel.h"
 #include "stream_kernel.h"
+#include "probe_kernels.h"
 
 using namespace deinfer;
 
@@ -459,6 +460,37 @@ int deinfer_set_trace_buffer(void *buf, size_t bytes) {
   g_trace = static_cast<unsigned long long *>(buf);
   g_trace_bytes = buf ? bytes : 0;
   return DEINFER_OK;
+}
+
+int deinfer_probe_stream_read(const void *buf, size_t bytes, void *sink, size_t sink_bytes, void *stream) {
+  if (!buf || !sink) return fail(DEINFER_ERR_INVALID_ARG, "probe: buffer or sink is NULL");
+  if (!aligned(buf, 16) || !aligned(sink, 16)) return fail(DEINFER_ERR_MISALIGNED, "probe: buffer and sink must be 16-byte aligned");
+  if (bytes < 1024 || bytes % 1024 != 0) return fail(DEINFER_ERR_INVALID_ARG, "probe: bytes must be a positive multiple of 1024");
+  if (sink_bytes < DEINFER_PROBE_SINK_BYTES) return fail(DEINFER_ERR_WORKSPACE, "probe: sink smaller than DEINFER_PROBE_SINK_BYTES");
+  const int cus = device_cus();
+  if (cus <= 0) return fail(DEINFER_ERR_DEVICE, "cannot query the device");
+  const size_t n_kb = bytes / 1024;
+  const unsigned grid = (unsigned)(n_kb < (size_t)cus ? n_kb : (size_t)cus);
+  hipLaunchKernelGGL(probe_stream_read_kernel, dim3(grid), dim3(PROBE_READ_THREADS), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4_t *>(buf), n_kb, static_cast<u32x4_t *>(sink));
+  return check_launch("stream-read probe");
+}
+
+int deinfer_probe_mfma_bf16(const void *operands, size_t operand_bytes, int64_t n_rounds, void *sink, size_t sink_bytes,
+                            void *stream, double *flops_out) {
+  if (!operands || !sink) return fail(DEINFER_ERR_INVALID_ARG, "probe: operands or sink is NULL");
+  if (!aligned(operands, 16) || !aligned(sink, 16)) return fail(DEINFER_ERR_MISALIGNED, "probe: operands and sink must be 16-byte aligned");
+  if (operand_bytes < (size_t)PROBE_MFMA_THREADS * 32) return fail(DEINFER_ERR_INVALID_ARG, "probe: operands must hold 8192 bytes");
+  if (n_rounds <= 0 || n_rounds > (1 << 24)) return fail(DEINFER_ERR_INVALID_ARG, "probe: n_rounds out of range");
+  const int cus = device_cus();
+  if (cus <= 0) return fail(DEINFER_ERR_DEVICE, "cannot query the device");
+  if (sink_bytes < DEINFER_PROBE_SINK_BYTES || (size_t)cus * PROBE_MFMA_THREADS * sizeof(float) > sink_bytes)
+    return fail(DEINFER_ERR_WORKSPACE, "probe: sink smaller than DEINFER_PROBE_SINK_BYTES");
+  hipLaunchKernelGGL(probe_mfma_bf16_kernel, dim3((unsigned)cus), dim3(PROBE_MFMA_THREADS), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4_t *>(operands), (int)n_rounds, static_cast<float *>(sink));
+  if (flops_out)      // 32 x 32 x 16 multiply-adds per product
+    *flops_out = 2.0 * 32 * 32 * 16 * (double)PROBE_MFMA_ACC * (double)n_rounds * (PROBE_MFMA_THREADS / 64) * (double)cus;
+  return check_launch("MFMA probe");
 }
 
 int deinfer_rank_for_ratio(int64_t m, int64_t n, double param_reduction, int64_t *r_out) {

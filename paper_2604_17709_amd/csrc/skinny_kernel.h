@@ -20,9 +20,14 @@
 //     sums cross L2 caches that are not coherent with each other, and one workgroup's serial
 //     read-back is slower than a launch that uses the whole device.)
 // Every wavefront keeps three stages of weight loads in flight (four register sets, four LDS
-// slabs); one or two workgroups per compute unit.  Inside the kernel the stream runs at the HBM
-// rate (a per-workgroup trace shows 32 KiB per 0.93 us and workgroup with 258 workgroups);
-// what a launch loses is the 3 us to the first data and the skew of the last workgroups.
+// slabs); one or two workgroups per compute unit.  A per-workgroup trace (build flag
+// DEINFER_SK_TRACE) of the largest launch of a 7B block at T = 64 (172 workgroups, 19 stages)
+// shows: all workgroups start within 0.2 us, the first stage lands 3.0 us later, the other 18
+// stages take 19 us (5.2 TB/s of weights), 1 us of stores.  The same loop without the activation
+// loads takes 15.7 us, without the products 17.7 us, without both 15.0 us (6.6 TB/s): the
+// activation slabs, which every workgroup re-reads from L2 (half the weight bytes at T = 64),
+// cost more than the products.  A layout in which a workgroup's stage is one contiguous 32 KiB
+// piece timed the same as the per-tile layout.
 #pragma once
 #include "common.h"
 
@@ -60,6 +65,9 @@ struct SkParams {
   SkProblem prob[3];
   float *part;               // [P][NB * 32][n_groups * 128] fp32
   long long part_stride;     // NB * 32 * n_groups * 128
+#ifdef DEINFER_SK_TRACE
+  unsigned long long *trace; // diagnostic build only: per-workgroup wall-clock stamps (100 MHz), 8 words each
+#endif
 };
 
 // NB = 32-token blocks (1, 2 or 4)
@@ -69,6 +77,10 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
   __shared__ __attribute__((aligned(16))) unsigned char xs[SK_SLABS][NB * 32 * SK_XROW];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#ifdef DEINFER_SK_TRACE
+  const unsigned long long tr_entry = wall_clock64();
+  unsigned long long tr_first = 0, tr_loop = 0;
+#endif
   // consecutive workgroups share the k-range (the same activation slab, kept hot in L2)
   const int g = blockIdx.x % P.n_groups;
   const int part = blockIdx.x / P.n_groups;
@@ -162,6 +174,9 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((SK_SLABS - 2) * (SK_KB * 2 + NX)) : "memory");
       __builtin_amdgcn_s_barrier();                     // ... everywhere; nobody reads slab (st - 1) % 4 any more
       asm volatile("" ::: "memory");
+#ifdef DEINFER_SK_TRACE
+      if (st == 0) tr_first = wall_clock64();
+#endif
       fetch_w(wn, st + SK_SLABS - 1);
       fetch_x(st + SK_SLABS - 1, slab == 0 ? SK_SLABS - 1 : slab - 1);
       compute(w, slab);
@@ -177,6 +192,9 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // drain the out-of-range tail loads
   }
+#ifdef DEINFER_SK_TRACE
+  tr_loop = wall_clock64();
+#endif
 
   // ---- partial result: element 4 q + e of block j is feature 8 q + 4 (l / 32) + e, token 32 j + l % 32
   const long long F = (long long)P.n_groups * SK_FEAT;
@@ -192,6 +210,16 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
       }
     }
   }
+#ifdef DEINFER_SK_TRACE
+  if (P.trace && blockIdx.x < 2048 && tid == 0) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    unsigned long long *tr = P.trace + blockIdx.x * 8;
+    tr[0] = tr_entry; tr[1] = tr_first; tr[2] = tr_loop; tr[3] = wall_clock64();
+    tr[4] = __builtin_amdgcn_s_getreg(6164);      // XCC_ID
+    tr[5] = __builtin_amdgcn_s_getreg(63492);     // HW_ID
+    tr[6] = n_stages;
+  }
+#endif
 #else
   (void)P;
 #endif

@@ -26,7 +26,7 @@ def make(d_in=64, d_out=48, r=16, dtype=dn.BF16, layout=dn.LAYOUT_RAW, U=FAKE, V
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "deinfer.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(deinfer_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(deinfer_[a-z0-9_]+)\s*\(", header))
     assert {"deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
             "deinfer_lowrank_down", "deinfer_lowrank_up"} <= declared
     L = ctypes.CDLL(dn.LIB_PATH)
@@ -109,6 +109,20 @@ def test_up_projection_argument_validation():
     assert _up(make(**pk), ldt=20) == dn.ERR_MISALIGNED
     assert _up(make(**pk), ldt=16, t=FAKE + 0x200002) == dn.ERR_MISALIGNED
     assert _up(make(**pk), T=0, ldt=16, t=None, y=None, ws=None, ws_bytes=0) == dn.OK
+
+
+def test_probe_argument_validation():
+    L = dn.lib()
+    sink, big = FAKE + 0x500000, dn.PROBE_SINK_BYTES
+    assert L.deinfer_probe_stream_read(None, 1 << 20, sink, big, None) == dn.ERR_INVALID_ARG
+    assert L.deinfer_probe_stream_read(FAKE, 1000, sink, big, None) == dn.ERR_INVALID_ARG      # not a multiple of 1024
+    assert L.deinfer_probe_stream_read(FAKE, 0, sink, big, None) == dn.ERR_INVALID_ARG
+    assert L.deinfer_probe_stream_read(FAKE + 4, 1 << 20, sink, big, None) == dn.ERR_MISALIGNED
+    assert L.deinfer_probe_stream_read(FAKE, 1 << 20, sink, 4096, None) == dn.ERR_WORKSPACE
+    assert L.deinfer_probe_mfma_bf16(None, 8192, 10, sink, big, None, None) == dn.ERR_INVALID_ARG
+    assert L.deinfer_probe_mfma_bf16(FAKE, 4096, 10, sink, big, None, None) == dn.ERR_INVALID_ARG   # too few operand bytes
+    assert L.deinfer_probe_mfma_bf16(FAKE, 8192, 0, sink, big, None, None) == dn.ERR_INVALID_ARG
+    assert L.deinfer_probe_mfma_bf16(FAKE, 8192, 10, sink + 8, big, None, None) == dn.ERR_MISALIGNED
 
 
 def test_group_calls_validate_shared_properties():
