@@ -193,3 +193,45 @@ def single_linear_f32(seed: int = 0, T: int = 16, d_in: int = 512, r: int = 64, 
     U = make(seed, 2, (d_in, r), 1.0 / np.sqrt(d_in), "f32")
     V = make(seed, 3, (r, d_out), 1.0 / np.sqrt(r), "f32")
     return x, U, V
+
+
+# ---------------------------------------------------------------------------------------------
+# Block tables of a paged cache (inputs of the contiguous-block scan; no part of the scan itself)
+def paged_block_tables(seed: int, prompt_blocks, decode_blocks, n_pool_blocks: int, recycled: int = 0):
+    """Block tables as a paged-cache allocator leaves them after prefill and interleaved decoding.
+
+    The allocator hands out physical block ids from a queue: first ``recycled`` ids in a seeded
+    random order (blocks that earlier, finished sequences gave back), then the untouched ids in
+    ascending order.  Every sequence first takes its ``prompt_blocks[s]`` blocks in one go
+    (prefill: a physically contiguous run unless it falls into the recycled part), then the
+    sequences take one block each, round after round, until sequence s holds
+    ``prompt_blocks[s] + decode_blocks[s]`` blocks (decoding: neighbours in a sequence's table
+    end up ``n_seqs`` apart or scattered).  Returns ``(table, n_blocks)``: int32
+    ``[n_seqs, max_blocks]`` padded with -1, and int32 ``[n_seqs]``.
+    """
+    prompt_blocks = [int(v) for v in prompt_blocks]
+    decode_blocks = [int(v) for v in decode_blocks]
+    n_seqs = len(prompt_blocks)
+    assert len(decode_blocks) == n_seqs
+    total = sum(prompt_blocks) + sum(decode_blocks)
+    assert 0 <= recycled <= n_pool_blocks and total <= n_pool_blocks
+    # recycled ids: a seeded shuffle of a seeded choice of ids (sort by random keys)
+    keys = _splitmix64(np.arange(n_pool_blocks, dtype=np.uint64) + (np.uint64(seed) << np.uint64(32)))
+    chosen = np.sort(np.argsort(keys, kind="stable")[:recycled])
+    keys2 = _splitmix64(chosen.astype(np.uint64) + (np.uint64(seed + 1) << np.uint64(32)))
+    first = chosen[np.argsort(keys2, kind="stable")]
+    mask = np.ones(n_pool_blocks, dtype=bool)
+    mask[chosen] = False
+    queue = np.concatenate([first, np.nonzero(mask)[0]]).astype(np.int64)
+    n_blocks = np.array([p + d for p, d in zip(prompt_blocks, decode_blocks)], dtype=np.int32)
+    table = np.full((n_seqs, max(1, int(n_blocks.max()) if n_seqs else 1)), -1, dtype=np.int32)
+    head = 0
+    fill = [0] * n_seqs
+    for s in range(n_seqs):
+        for _ in range(prompt_blocks[s]):
+            table[s, fill[s]] = queue[head]; head += 1; fill[s] += 1
+    for rnd_ in range(max(decode_blocks) if n_seqs else 0):
+        for s in range(n_seqs):
+            if rnd_ < decode_blocks[s]:
+                table[s, fill[s]] = queue[head]; head += 1; fill[s] += 1
+    return table, n_blocks
