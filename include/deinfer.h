@@ -216,6 +216,57 @@ int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_fact
                        void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Paged low-rank cache and static graphs (Sec. 4.3).  The low-rank cache (k_low_rank, v_low_rank)
+ * lives in a pool of fixed-size physical blocks; a block table names, per sequence, the blocks it
+ * owns.  Before attention the blocks are squeezed into a compact buffer at a fixed address, the
+ * buffer is multiplied by the upward matrix (deinfer_lowrank_up with T = the buffer's token
+ * capacity, so the launch never changes) and, for keys, the rotary embedding is applied in
+ * place.  The kernels take what changes between steps from device memory: the sequence
+ * "preparation stage (host) -> copy of the plan and the positions to the device -> replay of a
+ * captured graph of deinfer_kv_compact_copy, deinfer_lowrank_up, deinfer_rope_inplace" is valid.
+ *
+ * deinfer_kv_compact_plan (host only, preparation stage): walks the sequences in table order and
+ * their blocks in logical order; the d-th block of the walk goes to buffer block d.  It writes
+ *   plan   (host, DEINFER_KV_PLAN_WORDS(plan_capacity_runs) int32): [0] number of runs, [1] number
+ *          of blocks, [2..3] zero, then (source block, destination block, length) per run, a run
+ *          being a maximal stretch of the walk whose physical ids increase by one (it may pass
+ *          from one sequence into the next);
+ *   remap  (host, n_seqs x remap_pitch, may be NULL): the "remapping index list", remap[s][i] =
+ *          buffer block of logical block i of sequence s, -1 beyond the sequence's blocks;
+ *   positions (host, buffer_blocks * block_tokens, may be NULL): position inside its sequence of
+ *          every token slot of the buffer (0 for unused blocks), the input of the rotary kernel.
+ * block_table: host, n_seqs x table_pitch int32; n_blocks: host, blocks held per sequence.
+ * Errors: a block id outside [0, n_pool_blocks), more blocks than the buffer or the tables hold,
+ * more runs than plan_capacity_runs.
+ *
+ * deinfer_kv_compact_copy (device, graph replay stage): copies the runs of `plan` (DEVICE copy of
+ * the host plan) from `pool` (n_pool_blocks x block_bytes, device, 16-byte aligned, block_bytes a
+ * multiple of 16) into `buffer` (buffer_blocks x block_bytes).  Buffer blocks beyond plan[1] are
+ * left alone.  Runs that point outside the pool or the buffer are skipped.  Asynchronous on
+ * `stream`, no allocation; the launch shape depends only on buffer_blocks and block_bytes.
+ */
+#define DEINFER_KV_PLAN_WORDS(capacity_runs) (4 + 3 * (size_t)(capacity_runs))
+int deinfer_kv_compact_plan(const int32_t *block_table, int64_t n_seqs, int64_t table_pitch,
+                            const int32_t *n_blocks, int64_t n_pool_blocks, int64_t buffer_blocks,
+                            int64_t block_tokens, int32_t *plan, int64_t plan_capacity_runs,
+                            int32_t *remap, int64_t remap_pitch, int32_t *positions);
+int deinfer_kv_compact_copy(const void *pool, int64_t n_pool_blocks, int64_t block_bytes,
+                            const int32_t *plan, int64_t plan_capacity_runs,
+                            void *buffer, int64_t buffer_blocks, void *stream);
+
+/*
+ * Rotary position embedding in place (Sec. 4.3 applies it to the rebuilt keys; the paper prints
+ * no formula, this is the one of LLaMA-type models): x is T x (n_heads * head_dim), pitch ldx,
+ * device, dtype DEINFER_BF16 or DEINFER_F32; inside every head the elements i and i + head_dim/2
+ * (i < head_dim/2) are replaced by
+ *   x_i cos(a) - x_{i + D/2} sin(a),   x_{i + D/2} cos(a) + x_i sin(a),   a = pos * theta^(-2 i / D),
+ * pos = positions[token] (device, int32).  Angles in double precision, products in fp32, one
+ * rounding to the storage type.  Asynchronous on `stream`, no allocation.
+ */
+int deinfer_rope_inplace(void *x, int64_t T, int64_t ldx, int64_t n_heads, int64_t head_dim,
+                         const int32_t *positions, double theta, int dtype, void *stream);
+
+/*
  * MLP second sub-layer (Sec. 4.1): y = (h U_d) V_d with d_in = FFN width.
  * Same contract as deinfer_lowrank_linear.
  */

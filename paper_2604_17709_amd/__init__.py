@@ -55,6 +55,7 @@ EXPORTS = [
     "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
     "deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
     "deinfer_lowrank_down", "deinfer_lowrank_up",
+    "deinfer_kv_compact_plan", "deinfer_kv_compact_copy", "deinfer_rope_inplace",
 ]
 
 _lib = None
@@ -76,6 +77,10 @@ def lib() -> ctypes.CDLL:
         L.deinfer_rank_for_ratio.argtypes = [_i64, _i64, ctypes.c_double, ctypes.POINTER(_i64)]
         L.deinfer_probe_stream_read.argtypes = [_vp, _sz, _vp, _sz, _vp]
         L.deinfer_probe_mfma_bf16.argtypes = [_vp, _sz, _i64, _vp, _sz, _vp, ctypes.POINTER(ctypes.c_double)]
+        _ip = ctypes.POINTER(ctypes.c_int32)
+        L.deinfer_kv_compact_plan.argtypes = [_ip, _i64, _i64, _ip, _i64, _i64, _i64, _ip, _i64, _ip, _i64, _ip]
+        L.deinfer_kv_compact_copy.argtypes = [_vp, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
+        L.deinfer_rope_inplace.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, ctypes.c_double, ctypes.c_int, _vp]
         L.deinfer_packed_bytes.argtypes = [FP, ctypes.POINTER(_sz)]
         L.deinfer_pack_factors.argtypes = [FP, _vp, _sz, FP, _vp]
         L.deinfer_workspace_bytes.argtypes = [_i64, ctypes.POINTER(FP), ctypes.c_int, ctypes.POINTER(_sz)]
@@ -245,6 +250,49 @@ def deinfer_lowrank_down(h, pair: Pair, ws: Workspace, out=None, stream=None):
     _check(lib().deinfer_lowrank_down(_ptr(h), T, _ld(h), ctypes.byref(pair.desc),
                                       _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
     return out
+
+
+KV_PLAN_HEADER = 4
+
+
+def deinfer_kv_compact_plan(block_table, n_blocks, n_pool_blocks: int, buffer_blocks: int, block_tokens: int,
+                            capacity_runs: Optional[int] = None):
+    """Preparation stage (host): scan the block tables for physically contiguous blocks.
+
+    block_table: int32 numpy [n_seqs, pitch]; n_blocks: int32 numpy [n_seqs].  Returns numpy int32
+    arrays (plan, remap, positions): plan = [n_runs, n_blocks, 0, 0, (src, dst, len) ...] of fixed
+    size 4 + 3 * capacity_runs, remap = [n_seqs, pitch] (the new block table, -1 padded),
+    positions = [buffer_blocks * block_tokens].
+    """
+    import numpy as np
+    bt = np.ascontiguousarray(block_table, dtype=np.int32).reshape(len(n_blocks), -1)
+    nb = np.ascontiguousarray(n_blocks, dtype=np.int32)
+    n_seqs, pitch = bt.shape
+    cap = int(buffer_blocks if capacity_runs is None else capacity_runs)
+    plan = np.zeros(KV_PLAN_HEADER + 3 * cap, dtype=np.int32)
+    remap = np.full((n_seqs, pitch), -1, dtype=np.int32)
+    positions = np.zeros(int(buffer_blocks) * int(block_tokens), dtype=np.int32)
+    ip = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    _check(lib().deinfer_kv_compact_plan(ip(bt), n_seqs, pitch, ip(nb), int(n_pool_blocks), int(buffer_blocks),
+                                         int(block_tokens), ip(plan), cap, ip(remap), pitch, ip(positions)))
+    return plan, remap, positions
+
+
+def deinfer_kv_compact_copy(pool, block_bytes: int, plan_dev, buffer, stream=None) -> None:
+    """Graph-replay stage: copy the runs of the (device) plan from the block pool into the compact buffer."""
+    pool_bytes = pool.numel() * pool.element_size()
+    buf_bytes = buffer.numel() * buffer.element_size()
+    cap = (plan_dev.numel() - KV_PLAN_HEADER) // 3
+    _check(lib().deinfer_kv_compact_copy(_ptr(pool), pool_bytes // block_bytes, int(block_bytes), _ptr(plan_dev), cap,
+                                         _ptr(buffer), buf_bytes // block_bytes, _stream(stream)))
+
+
+def deinfer_rope_inplace(x, n_heads: int, head_dim: int, positions_dev, theta: float = 10000.0, stream=None) -> None:
+    """Rotary position embedding in place on x [T, n_heads * head_dim] (pairs i, i + head_dim / 2)."""
+    import torch
+    dt = {torch.bfloat16: BF16, torch.float32: F32}[x.dtype]
+    _check(lib().deinfer_rope_inplace(_ptr(x), _rows(x, "x"), _ld(x), int(n_heads), int(head_dim), _ptr(positions_dev),
+                                      float(theta), dt, _stream(stream)))
 
 
 PROBE_SINK_BYTES = 1 << 20

@@ -17,6 +17,7 @@
 #include "skinny_kernel.h"
 #include "stream_kernel.h"
 #include "probe_kernels.h"
+#include "paged_kernels.h"
 
 using namespace deinfer;
 
@@ -491,6 +492,101 @@ int deinfer_probe_mfma_bf16(const void *operands, size_t operand_bytes, int64_t 
   if (flops_out)      // 32 x 32 x 16 multiply-adds per product
     *flops_out = 2.0 * 32 * 32 * 16 * (double)PROBE_MFMA_ACC * (double)n_rounds * (PROBE_MFMA_THREADS / 64) * (double)cus;
   return check_launch("MFMA probe");
+}
+
+int deinfer_kv_compact_plan(const int32_t *block_table, int64_t n_seqs, int64_t table_pitch, const int32_t *n_blocks,
+                            int64_t n_pool_blocks, int64_t buffer_blocks, int64_t block_tokens,
+                            int32_t *plan, int64_t plan_capacity_runs, int32_t *remap, int64_t remap_pitch,
+                            int32_t *positions) {
+  if (n_seqs < 0 || table_pitch < 0 || n_pool_blocks < 0 || buffer_blocks < 0 || plan_capacity_runs < 0)
+    return fail(DEINFER_ERR_INVALID_ARG, "kv plan: negative size");
+  if (!plan) return fail(DEINFER_ERR_INVALID_ARG, "kv plan: plan is NULL");
+  if (n_seqs > 0 && (!block_table || !n_blocks)) return fail(DEINFER_ERR_INVALID_ARG, "kv plan: block table or block counts are NULL");
+  if (n_pool_blocks > INT32_MAX || buffer_blocks > INT32_MAX || plan_capacity_runs > (INT32_MAX - KV_PLAN_HEADER) / 3)
+    return fail(DEINFER_ERR_INVALID_ARG, "kv plan: sizes above 2^31 are not supported");
+  if (positions && block_tokens <= 0) return fail(DEINFER_ERR_INVALID_ARG, "kv plan: block_tokens must be positive when positions are asked for");
+  if (positions && buffer_blocks * block_tokens > INT32_MAX) return fail(DEINFER_ERR_INVALID_ARG, "kv plan: too many token slots");
+  int64_t n_runs = 0, d = 0;
+  int64_t run_src = 0, run_len = 0;          // the open run; its destination is d - run_len
+  for (int64_t s = 0; s < n_seqs; ++s) {
+    const int64_t nb = n_blocks[s];
+    if (nb < 0 || nb > table_pitch) return fail(DEINFER_ERR_INVALID_ARG, "kv plan: sequence %lld has %lld blocks, the table holds %lld per sequence", (long long)s, (long long)nb, (long long)table_pitch);
+    if (remap && nb > remap_pitch) return fail(DEINFER_ERR_INVALID_ARG, "kv plan: sequence %lld has %lld blocks, the remapping list holds %lld per sequence", (long long)s, (long long)nb, (long long)remap_pitch);
+    for (int64_t i = 0; i < nb; ++i) {
+      const int64_t p = block_table[s * table_pitch + i];
+      if (p < 0 || p >= n_pool_blocks) return fail(DEINFER_ERR_INVALID_ARG, "kv plan: sequence %lld block %lld names physical block %lld outside the pool of %lld", (long long)s, (long long)i, (long long)p, (long long)n_pool_blocks);
+      if (d >= buffer_blocks) return fail(DEINFER_ERR_WORKSPACE, "kv plan: the sequences hold more than the %lld blocks of the compact buffer", (long long)buffer_blocks);
+      if (run_len > 0 && run_src + run_len == p) {
+        ++run_len;                              // physically contiguous with the block before it in the walk
+      } else {
+        if (run_len > 0) {
+          if (n_runs >= plan_capacity_runs) return fail(DEINFER_ERR_WORKSPACE, "kv plan: more than %lld runs", (long long)plan_capacity_runs);
+          int32_t *r = plan + KV_PLAN_HEADER + 3 * n_runs++;
+          r[0] = (int32_t)run_src; r[1] = (int32_t)(d - run_len); r[2] = (int32_t)run_len;
+        }
+        run_src = p; run_len = 1;
+      }
+      if (remap) remap[s * remap_pitch + i] = (int32_t)d;
+      if (positions)
+        for (int64_t j = 0; j < block_tokens; ++j) positions[d * block_tokens + j] = (int32_t)(i * block_tokens + j);
+      ++d;
+    }
+    if (remap) for (int64_t i = nb; i < remap_pitch; ++i) remap[s * remap_pitch + i] = -1;
+  }
+  if (run_len > 0) {
+    if (n_runs >= plan_capacity_runs) return fail(DEINFER_ERR_WORKSPACE, "kv plan: more than %lld runs", (long long)plan_capacity_runs);
+    int32_t *r = plan + KV_PLAN_HEADER + 3 * n_runs++;
+    r[0] = (int32_t)run_src; r[1] = (int32_t)(d - run_len); r[2] = (int32_t)run_len;
+  }
+  if (positions)
+    for (int64_t j = d * block_tokens; j < buffer_blocks * block_tokens; ++j) positions[j] = 0;
+  plan[0] = (int32_t)n_runs; plan[1] = (int32_t)d; plan[2] = 0; plan[3] = 0;
+  return DEINFER_OK;
+}
+
+int deinfer_kv_compact_copy(const void *pool, int64_t n_pool_blocks, int64_t block_bytes, const int32_t *plan,
+                            int64_t plan_capacity_runs, void *buffer, int64_t buffer_blocks, void *stream) {
+  if (n_pool_blocks < 0 || buffer_blocks < 0 || plan_capacity_runs < 0 || block_bytes <= 0)
+    return fail(DEINFER_ERR_INVALID_ARG, "kv copy: bad size");
+  if (block_bytes % 16 != 0) return fail(DEINFER_ERR_MISALIGNED, "kv copy: block_bytes must be a multiple of 16");
+  if (n_pool_blocks > INT32_MAX || buffer_blocks > INT32_MAX || plan_capacity_runs > (INT32_MAX - KV_PLAN_HEADER) / 3)
+    return fail(DEINFER_ERR_INVALID_ARG, "kv copy: sizes above 2^31 are not supported");
+  if (buffer_blocks == 0 || plan_capacity_runs == 0) return DEINFER_OK;
+  if (!pool || !plan || !buffer) return fail(DEINFER_ERR_INVALID_ARG, "kv copy: pool, plan or buffer is NULL");
+  if (!aligned(pool, 16) || !aligned(buffer, 16) || !aligned(plan, 4))
+    return fail(DEINFER_ERR_MISALIGNED, "kv copy: pool and buffer must be 16-byte aligned");
+  // the grid depends on capacities only: a captured launch serves every later plan
+  const int64_t pieces = buffer_blocks * ceil_div(block_bytes, (int64_t)KV_PIECE);
+  const unsigned grid = (unsigned)(pieces < 4096 ? pieces : 4096);
+  hipLaunchKernelGGL(kv_compact_copy_kernel, dim3(grid), dim3(KV_COPY_THREADS), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const unsigned char *>(pool), (long long)n_pool_blocks, (long long)block_bytes, plan,
+                     (int)plan_capacity_runs, static_cast<unsigned char *>(buffer), (long long)buffer_blocks);
+  return check_launch("kv compact copy");
+}
+
+int deinfer_rope_inplace(void *x, int64_t T, int64_t ldx, int64_t n_heads, int64_t head_dim, const int32_t *positions,
+                         double theta, int dtype, void *stream) {
+  if (T < 0 || n_heads <= 0 || head_dim <= 0 || head_dim % 2 != 0)
+    return fail(DEINFER_ERR_INVALID_ARG, "rope: T >= 0, n_heads > 0 and an even head_dim > 0 are required");
+  if (dtype != DEINFER_F32 && dtype != DEINFER_BF16) return fail(DEINFER_ERR_UNSUPPORTED, "rope: unknown dtype %d", dtype);
+  if (!(theta > 0.0)) return fail(DEINFER_ERR_INVALID_ARG, "rope: theta must be positive");
+  if (n_heads > (1 << 20) || head_dim > (1 << 20) || ldx < n_heads * head_dim)
+    return fail(DEINFER_ERR_INVALID_ARG, "rope: ldx smaller than n_heads * head_dim, or sizes out of range");
+  if (T == 0) return DEINFER_OK;
+  if (!x || !positions) return fail(DEINFER_ERR_INVALID_ARG, "rope: x or positions is NULL");
+  if (!aligned(x, elem_size(dtype)) || !aligned(positions, 4)) return fail(DEINFER_ERR_MISALIGNED, "rope: x not aligned to its element size");
+  const int64_t chunks = ceil_div(head_dim / 2, (int64_t)8);
+  const int64_t n = T * chunks;
+  if (ceil_div(n, (int64_t)256) > INT32_MAX) return fail(DEINFER_ERR_UNSUPPORTED, "rope: too many tokens");
+  const dim3 grid((unsigned)ceil_div(n, (int64_t)256));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dtype == DEINFER_BF16)
+    hipLaunchKernelGGL((rope_inplace_kernel<uint16_t>), grid, dim3(256), 0, s, static_cast<uint16_t *>(x), (long long)T,
+                       (long long)ldx, (int)n_heads, (int)head_dim, positions, log2(theta));
+  else
+    hipLaunchKernelGGL((rope_inplace_kernel<float>), grid, dim3(256), 0, s, static_cast<float *>(x), (long long)T,
+                       (long long)ldx, (int)n_heads, (int)head_dim, positions, log2(theta));
+  return check_launch("rope");
 }
 
 int deinfer_rank_for_ratio(int64_t m, int64_t n, double param_reduction, int64_t *r_out) {
