@@ -550,6 +550,12 @@ def kv_rebuild(args, L, shape, T):
     kflops = 2.0 * T * r * d_kv
     ach = kflops / ksec / 1e12
     n_run_blocks = int(plan[1])
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic_%s_T%d.txt" % (args.workload, T))
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split("=")[1])
     copy_bytes = 2 * 2 * n_run_blocks * block_bytes                  # k and v, read + write
     rope_bytes = 2 * T * d_kv * 2
     out = {
@@ -565,7 +571,7 @@ def kv_rebuild(args, L, shape, T):
                   "up_k_v": {"us": round(parts["up"] * 1e6, 2), "flops": 2 * kflops, "TFLOPs": round(2 * kflops / parts["up"] / 1e12, 2)},
                   "rope_k": {"us": round(parts["rope"] * 1e6, 2), "bytes": rope_bytes, "GBs": round(rope_bytes / parts["rope"] / 1e9, 1)}},
         "roofline": {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
                      "kernel": "prefill_kernel kernel (upward projection of one of k, v: deinfer_lowrank_up)",
                      "avg_launch_us": round(ksec * 1e6, 2), "algorithmic_flops_per_launch": kflops,
                      "algorithmic_bytes_per_launch": 2 * (r * d_kv + T * r + T * d_kv)},
