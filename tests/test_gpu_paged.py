@@ -165,3 +165,43 @@ def test_rebuild_keys_from_paged_cache_under_one_graph(dn):
         ref_full = pc.rope(oracle.lowrank_linear(x.values, U.values, V.values), pos[:n_tok], H, D)
         assert max_err(got, ref_full) <= TOL["bf16"]
     assert torch.equal(results[0], results[2])                     # same state, same graph: same bits
+
+
+def test_rebuild_at_the_benchmark_size(dn):
+    """The configuration bench.py times for the rebuild step (7B block, keep 0.8: r = 1638 for k,
+    4096 key features in 32 heads of 128; 16 sequences of 32 blocks of 16 tokens; pool of 1024
+    blocks, 128 of them recycled): copy compared byte for byte in full, the keys on sampled
+    token rows (first / last rows, rows around block, tile and sequence borders)."""
+    import torch
+    r, d_kv, H, D, bt = 1638, 4096, 32, 128, 16
+    pitch = 1640
+    n_seqs, per_seq, n_pool = 16, 32, 1024
+    cap_blocks = n_seqs * per_seq
+    T = cap_blocks * bt
+    table, n_blocks = si.paged_block_tables(1, [24] * n_seqs, [8] * n_seqs, n_pool, recycled=n_pool // 8)
+    plan, remap, pos = dn.deinfer_kv_compact_plan(table, n_blocks, n_pool, cap_blocks, bt)
+    runs, _ = pc.contiguous_runs(table, n_blocks)
+    assert plan[0] == len(runs) and plan[1] == cap_blocks
+    bits = pool_bits(1, n_pool, bt, pitch)
+    bits[:, :, r:] = 0                                              # the padding columns of the cache rows are zero
+    pool = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    V = si.make(1, 21, (r, d_kv), 0.02, "bf16")
+    U = si.make(1, 20, (64, r), 0.02, "bf16")                       # not used by the upward projection
+    p, keep = pair(dn, U, V, packed=True)
+    ws = dn.Workspace(dn.deinfer_workspace_bytes(T, [p]))
+    buf = torch.zeros((T, pitch), dtype=torch.bfloat16, device="cuda")
+    keys = torch.empty((T, d_kv), dtype=torch.bfloat16, device="cuda")
+    dn.deinfer_kv_compact_copy(pool, bt * pitch * 2, torch.from_numpy(plan).cuda(), buf)
+    dn.deinfer_lowrank_up(buf, p, ws, out=keys)
+    dn.deinfer_rope_inplace(keys, H, D, torch.from_numpy(pos).cuda(), 10000.0)
+    torch.cuda.synchronize()
+    want = pc.gather_blocks(bits, table, n_blocks, cap_blocks)
+    got = buf.view(torch.int16).cpu().numpy().view(np.uint16).reshape(cap_blocks, bt, pitch)
+    assert np.array_equal(got, want)
+    rows = {0, T - 1}
+    for b in list(range(bt, T, 1024)) + list(range(128, T, 896)) + list(range(per_seq * bt, T, per_seq * bt)):
+        rows.update((b - 1, b))
+    rows = sorted(rows)
+    t_rows = si.bf16_bits_to_f32(want.reshape(T, pitch)[rows][:, :r]).astype(np.float64)
+    ref = pc.rope(oracle.up_projection(t_rows, V.values.astype(np.float64)), pos[rows], H, D)
+    assert max_err(to_host(keys[rows]), ref) <= TOL["bf16"]
