@@ -56,6 +56,13 @@ def lib() -> ctypes.CDLL:
         L.oracle_down_projection.argtypes = [_dp, _i64, _i64, _dp, _i64, _i64, _i64, _dp, _i64]
         L.oracle_up_projection.restype = None
         L.oracle_up_projection.argtypes = [_dp, _i64, _i64, _dp, _i64, _i64, _i64, _dp, _i64]
+        L.oracle_relu.restype = ctypes.c_double
+        L.oracle_relu.argtypes = [ctypes.c_double]
+        L.oracle_gelu.restype = ctypes.c_double
+        L.oracle_gelu.argtypes = [ctypes.c_double]
+        L.oracle_lowrank_linear_act.restype = ctypes.c_int
+        L.oracle_lowrank_linear_act.argtypes = [_dp, _i64, _i64, _dp, _i64, _dp, _i64, _i64, _i64, _i64,
+                                                _dp, ctypes.c_int, _dp, _i64]
         L.oracle_lowrank_linear.restype = ctypes.c_int
         L.oracle_lowrank_linear.argtypes = [_dp, _i64, _i64, _dp, _i64, _dp, _i64,
                                             _i64, _i64, _i64, _dp, _i64, _dp]
@@ -153,6 +160,33 @@ def lowrank_linear(x, U, V, return_t: bool = False):
         if rc:
             raise MemoryError("oracle_lowrank_linear")
     return (y, t) if return_t else y
+
+
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
+
+
+def relu(z: float) -> float:
+    return float(lib().oracle_relu(float(z)))
+
+
+def gelu(z: float) -> float:
+    return float(lib().oracle_gelu(float(z)))
+
+
+def lowrank_linear_act(x, U, V, bias=None, act: int = ACT_NONE):
+    """y = act((x U) V + bias) in fp64 (non-GLU MLP first sub-layer)."""
+    x, U, V = _f64(x), _f64(U), _f64(V)
+    _check_pair(x, U, V)
+    T, d_in = x.shape
+    r, d_out = V.shape
+    b = None if bias is None else np.ascontiguousarray(np.asarray(bias, dtype=np.float64).reshape(d_out))
+    y = np.zeros((T, d_out), dtype=np.float64)
+    if T and d_out:
+        rc = lib().oracle_lowrank_linear_act(_p(x), T, d_in, _p(U), max(r, 1), _p(V), d_out, d_in, r, d_out,
+                                             _p(b) if b is not None else None, int(act), _p(y), d_out)
+        if rc:
+            raise RuntimeError("oracle_lowrank_linear_act: %d" % rc)
+    return y
 
 
 def lowrank_qkv(x, Uq, Vq, Uk, Vk, Uv, Vv, return_t: bool = False):

@@ -189,6 +189,32 @@ int oracle_lowrank_gateup_silu(const double *x, int64_t T, int64_t ldx, int64_t 
   return rc;
 }
 
+/* ------------------------------------------------------------------------
+ * Non-GLU MLP first sub-layer (Table 2 lists GLU-based and non-GLU models; Sec. 4.1
+ * "activation computation" after the upward projection):
+ *   y = act((x U) V + b),  b broadcast over the token rows (NULL = no bias),
+ *   act 0: identity, 1: ReLU max(z, 0), 2: GELU z * Phi(z) with Phi the standard
+ *   normal distribution function, written with erf.
+ * The paper prints neither activation; these are the textbook definitions.
+ * ---------------------------------------------------------------------- */
+double oracle_relu(double z) { return z > 0.0 ? z : 0.0; }
+double oracle_gelu(double z) { return 0.5 * z * (1.0 + erf(z / sqrt(2.0))); }
+
+int oracle_lowrank_linear_act(const double *x, int64_t T, int64_t ldx,
+                              const double *U, int64_t ldu, const double *V, int64_t ldv,
+                              int64_t d_in, int64_t r, int64_t d_out,
+                              const double *bias, int act, double *y, int64_t ldy) {
+  if (act < 0 || act > 2) return -3;
+  int rc = oracle_lowrank_linear(x, T, ldx, U, ldu, V, ldv, d_in, r, d_out, y, ldy, NULL);
+  if (rc) return rc;
+  for (int64_t i = 0; i < T; ++i)
+    for (int64_t j = 0; j < d_out; ++j) {
+      double z = y[i * ldy + j] + (bias ? bias[j] : 0.0);
+      y[i * ldy + j] = act == 1 ? oracle_relu(z) : act == 2 ? oracle_gelu(z) : z;
+    }
+  return 0;
+}
+
 /* Second sub-layer of the MLP (and the O projection): a plain factor pair. */
 int oracle_lowrank_down(const double *h, int64_t T, int64_t ldh,
                         const double *U, int64_t ldu, const double *V, int64_t ldv,

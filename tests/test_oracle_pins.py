@@ -279,3 +279,34 @@ def test_generator_is_seeded_and_counter_based():
     t = si.make(0, 1, (8, 16), 0.02, "bf16")
     assert t.bits.dtype == np.uint16 and t.values.dtype == np.float32
     assert np.array_equal(si.f32_to_bf16_bits(t.values), t.bits)      # already representable
+
+
+# --------------------------------------------------------------------- non-GLU sub-layer: bias and activation
+def test_gelu_is_z_times_the_normal_distribution_function():
+    import scipy.stats
+    for z in (-6.0, -2.5, -1.0, -0.3, 0.0, 0.3, 1.0, 2.5, 6.0):
+        assert math.isclose(oracle.gelu(z), z * scipy.stats.norm.cdf(z), rel_tol=1e-13, abs_tol=1e-16)
+    # values from a table of the normal distribution: Phi(1) = 0.8413447, Phi(2) = 0.9772499
+    assert abs(oracle.gelu(1.0) - 0.8413447) < 1e-7 and abs(oracle.gelu(-1.0) + 0.1586553) < 1e-7
+    assert abs(oracle.gelu(2.0) - 1.9544998) < 1e-7
+    assert oracle.gelu(0.0) == 0.0 and abs(oracle.gelu(40.0) - 40.0) < 1e-12 and abs(oracle.gelu(-40.0)) < 1e-12
+    assert oracle.relu(-3.0) == 0.0 and oracle.relu(2.5) == 2.5 and oracle.relu(0.0) == 0.0
+
+
+def test_linear_act_against_numpy_and_special_cases():
+    x, U, V, b = rnd(5, 21), rnd(21, 4), rnd(4, 13), rnd(13)
+    z = (x @ U) @ V
+    assert rel_err(oracle.lowrank_linear_act(x, U, V), z) < 1e-13
+    assert rel_err(oracle.lowrank_linear_act(x, U, V, b), z + b[None, :]) < 1e-13
+    assert rel_err(oracle.lowrank_linear_act(x, U, V, b, oracle.ACT_RELU), np.maximum(z + b[None, :], 0.0)) < 1e-13
+    g = oracle.lowrank_linear_act(x, U, V, b, oracle.ACT_GELU)
+    want = (z + b) * 0.5 * (1.0 + scipy.special.erf((z + b) / math.sqrt(2.0)))
+    assert rel_err(g, want) < 1e-13
+    # the bias is added before the activation and runs along the output features, not the tokens
+    only_b = oracle.lowrank_linear_act(x, U, np.zeros_like(V), b, oracle.ACT_RELU)
+    assert np.array_equal(only_b, np.tile(np.maximum(b, 0.0), (5, 1)))
+    # ReLU is positively homogeneous, GELU is not
+    r1 = oracle.lowrank_linear_act(3.0 * x, U, V, 3.0 * b, oracle.ACT_RELU)
+    assert rel_err(r1, 3.0 * oracle.lowrank_linear_act(x, U, V, b, oracle.ACT_RELU)) < 1e-13
+    with pytest.raises(RuntimeError):
+        oracle.lowrank_linear_act(x, U, V, b, 7)
