@@ -216,6 +216,21 @@ int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_fact
                        void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * First sub-layer of a non-GLU MLP (Table 2 lists GLU-based and non-GLU models; Sec. 4.1
+ * "activation computation" after the upward projection):
+ *   y = act((x U) V + bias),   bias: device, d_out values of the pair's dtype, may be NULL
+ *   (PACKED pairs: 16-byte aligned), broadcast over the token rows;
+ *   act: DEINFER_ACT_NONE, DEINFER_ACT_RELU max(z, 0), DEINFER_ACT_GELU z * Phi(z) (erf form).
+ * Sum, bias and activation are evaluated in fp32 on the accumulators and rounded once.  The
+ * paper prints neither activation nor a bias; these are the textbook definitions.  Otherwise
+ * the contract of deinfer_lowrank_linear (a pair of rank 0 gives y = act(bias)).
+ */
+enum { DEINFER_ACT_NONE = 0, DEINFER_ACT_RELU = 1, DEINFER_ACT_GELU = 2 };
+int deinfer_lowrank_linear_act(const void *x, int64_t T, int64_t ldx, const deinfer_factors_t *f,
+                               const void *bias, int act, void *y, int64_t ldy,
+                               void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Paged low-rank cache and static graphs (Sec. 4.3).  The low-rank cache (k_low_rank, v_low_rank)
  * lives in a pool of fixed-size physical blocks; a block table names, per sequence, the blocks it
  * owns.  Before attention the blocks are squeezed into a compact buffer at a fixed address, the

@@ -54,7 +54,7 @@ EXPORTS = [
     "deinfer_packed_bytes", "deinfer_pack_factors",
     "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
     "deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
-    "deinfer_lowrank_down", "deinfer_lowrank_up",
+    "deinfer_lowrank_down", "deinfer_lowrank_up", "deinfer_lowrank_linear_act",
     "deinfer_kv_compact_plan", "deinfer_kv_compact_copy", "deinfer_rope_inplace",
 ]
 
@@ -89,6 +89,7 @@ def lib() -> ctypes.CDLL:
         L.deinfer_lowrank_linear.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_down.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_up.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
+        L.deinfer_lowrank_linear_act.argtypes = [_vp, _i64, _i64, FP, _vp, ctypes.c_int, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_qkv.argtypes = [_vp, _i64, _i64, FP, FP, FP,
                                           _vp, _i64, _vp, _i64, _vp, _i64,
                                           _vp, _i64, _vp, _i64, _vp, _sz, _vp]
@@ -249,6 +250,20 @@ def deinfer_lowrank_down(h, pair: Pair, ws: Workspace, out=None, stream=None):
         out = torch.empty((T, pair.d_out), dtype=h.dtype, device=h.device)
     _check(lib().deinfer_lowrank_down(_ptr(h), T, _ld(h), ctypes.byref(pair.desc),
                                       _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
+    return out
+
+
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
+
+
+def deinfer_lowrank_linear_act(x, pair: Pair, ws: Workspace, bias=None, act: int = ACT_NONE, out=None, stream=None):
+    """y = act((x U) V + bias): first sub-layer of a non-GLU MLP."""
+    import torch
+    T = _rows(x, "x")
+    if out is None:
+        out = torch.empty((T, pair.d_out), dtype=x.dtype, device=x.device)
+    _check(lib().deinfer_lowrank_linear_act(_ptr(x), T, _ld(x), ctypes.byref(pair.desc), _ptr(bias), int(act),
+                                            _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
     return out
 
 

@@ -39,6 +39,15 @@ template <> struct Elem<uint16_t> {  // bf16
 // SiLU in fp32: z * sigmoid(z) = z / (1 + exp(-z))
 __device__ __forceinline__ float silu_f32(float z) { return z * __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 
+// Activation of the non-GLU MLP sub-layer (Table 2 lists both kinds of model), applied in fp32
+// to the sum of product and bias: 0 identity, 1 ReLU, 2 GELU z Phi(z) (erf form).
+constexpr int ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2;
+__device__ __forceinline__ float act_f32(float z, int act) {
+  if (act == ACT_RELU) return fmaxf(z, 0.0f);
+  if (act == ACT_GELU) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+  return z;
+}
+
 __device__ __forceinline__ bf16x8_t as_bf16x8(const u32x4_t &v) {
   return __builtin_bit_cast(bf16x8_t, v);
 }

@@ -69,6 +69,8 @@ struct DecParams {
   int n_items2;         // work items of the up kernel
   int G1;               // workgroups of the down kernel: every one takes a non-empty range
   int direct1;                // 1: one workgroup per rank tile sums the whole k range and writes t itself (no reduce kernel)
+  const uint16_t *bias;       // single non-GLU pair: y = act(product + bias[feature]); may be null
+  int act;                    // see act_f32
   unsigned long long *trace;  // optional [2][1024][8] wall-clock stamps (diagnostic), may be null
 };
 
@@ -413,6 +415,19 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
         }
         const DecPair &pr = P.p[DUAL ? 0 : dc.pi];
         const int f0 = dc.otile * 16 + lkg * 4;
+        if (!DUAL && (P.bias != nullptr || P.act != ACT_NONE)) {
+          // non-GLU sub-layer: bias and activation on the fp32 sums, before the one rounding
+          const g_u16_p bp = (g_u16_p)uni_ptr(P.bias);
+          const int act = uni(P.act);
+          float b[4] = {0.f, 0.f, 0.f, 0.f};
+          if (bp != nullptr) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (f0 + v < pr.d_out) b[v] = bf16_to_f32(bp[f0 + v]);
+          }
+          s.x = act_f32(s.x + b[0], act); s.y = act_f32(s.y + b[1], act);
+          s.z = act_f32(s.z + b[2], act); s.w = act_f32(s.w + b[3], act);
+        }
         if (tok < P.T) {
           uint16_t *dst = pr.y + (long long)tok * pr.ldy + f0;
           if (f0 + 3 < pr.d_out && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {

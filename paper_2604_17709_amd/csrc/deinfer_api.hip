@@ -200,6 +200,7 @@ struct Group {
   void *t_out[3]; int64_t ldt[3];          // optional rank-space outputs
   bool glu;
   bool up_only;                            // x is the rank-space intermediate t: only the upward projection runs
+  const void *bias; int act;               // single non-GLU pair only: y = act(product + bias), bias per output feature
   void *ws; size_t ws_bytes; hipStream_t stream;
 };
 
@@ -251,6 +252,7 @@ int run_decode(const Group &gq, int64_t row0, int64_t T) {
   memset(&P, 0, sizeof(P));
   P.x = static_cast<const uint16_t *>(gq.x) + row0 * gq.ldx;
   P.ldx = gq.ldx; P.T = (int)T; P.d_in = (int)gq.f[0]->d_in; P.KB1 = (int)ceil_div(gq.f[0]->d_in, 32);
+  P.bias = static_cast<const uint16_t *>(gq.bias); P.act = gq.act;
   P.n_pairs = gq.n;
   int tile0 = 0, items = 0;
   for (int i = 0; i < gq.n; ++i) {
@@ -351,7 +353,8 @@ int run_generic(const Group &gq) {
     hipLaunchKernelGGL((gemm_generic_kernel<float, TE, TE, false>), grid, dim3(GTHREADS), 0, gq.stream,
                        t32 + off[i], ldt, static_cast<const TE *>(f->V), f->ldv, (int)f->r,
                        (const float *)nullptr, (int64_t)0, (const TE *)nullptr, (int64_t)0, 0,
-                       static_cast<TE *>(gq.out[i]), gq.ldo[i], (int)T, (int)f->d_out);
+                       static_cast<TE *>(gq.out[i]), gq.ldo[i], (int)T, (int)f->d_out,
+                       static_cast<const TE *>(gq.bias), gq.act);
     if (int rc = check_launch("generic stage 2")) return rc;
   }
   return DEINFER_OK;
@@ -407,6 +410,27 @@ int run_group(Group gq) {
     if (!aligned(gq.x, 16) || gq.ldx % 8 != 0 || gq.f[0]->d_in % 8 != 0)
       return fail(DEINFER_ERR_MISALIGNED,
                   "packed pairs need 16-byte aligned activations, ldx %% 8 == 0 and d_in %% 8 == 0");
+  }
+
+  // ---- bias / activation of the non-GLU sub-layer: single pair only
+  if (gq.bias != nullptr || gq.act != ACT_NONE) {
+    if (gq.n != 1 || gq.glu || gq.up_only) return fail(DEINFER_ERR_INVALID_ARG, "bias and activation go with a single pair");
+    if (gq.act != ACT_NONE && gq.act != ACT_RELU && gq.act != ACT_GELU) return fail(DEINFER_ERR_UNSUPPORTED, "unknown activation %d", gq.act);
+    if (gq.bias && !aligned(gq.bias, packed ? 16 : es))
+      return fail(DEINFER_ERR_MISALIGNED, packed ? "packed pairs need a 16-byte aligned bias" : "bias not aligned to the element size");
+    if (gq.f[0]->r == 0) {       // empty product: y = act(bias)
+      const int64_t cnt = gq.T * gq.f[0]->d_out;
+      if (cnt == 0) return DEINFER_OK;
+      if (dtype == DEINFER_BF16)
+        hipLaunchKernelGGL((bias_act_fill_kernel<uint16_t>), dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, gq.stream,
+                           static_cast<uint16_t *>(gq.out[0]), gq.ldo[0], (int)gq.T, (int)gq.f[0]->d_out,
+                           static_cast<const uint16_t *>(gq.bias), gq.act);
+      else
+        hipLaunchKernelGGL((bias_act_fill_kernel<float>), dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, gq.stream,
+                           static_cast<float *>(gq.out[0]), gq.ldo[0], (int)gq.T, (int)gq.f[0]->d_out,
+                           static_cast<const float *>(gq.bias), gq.act);
+      return check_launch("bias / activation fill");
+    }
   }
 
   // ---- pairs of rank 0: the output is exactly zero (empty sum)
@@ -699,6 +723,18 @@ int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_fact
   memset(&g, 0, sizeof(g));
   g.x = t; g.T = T; g.ldx = ldt; g.n = 1; g.f[0] = f; g.out[0] = y; g.ldo[0] = ldy;
   g.glu = false; g.up_only = true; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
+  return run_group(g);
+}
+
+int deinfer_lowrank_linear_act(const void *x, int64_t T, int64_t ldx, const deinfer_factors_t *f, const void *bias, int act,
+                               void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream) {
+  if (!f) return fail(DEINFER_ERR_INVALID_ARG, "factor descriptor is NULL");
+  if (act != DEINFER_ACT_NONE && act != DEINFER_ACT_RELU && act != DEINFER_ACT_GELU)
+    return fail(DEINFER_ERR_UNSUPPORTED, "unknown activation %d", act);
+  Group g;
+  memset(&g, 0, sizeof(g));
+  g.x = x; g.T = T; g.ldx = ldx; g.n = 1; g.f[0] = f; g.out[0] = y; g.ldo[0] = ldy;
+  g.glu = false; g.bias = bias; g.act = act; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
   return run_group(g);
 }
 

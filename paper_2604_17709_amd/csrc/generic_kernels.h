@@ -55,12 +55,13 @@ __device__ __forceinline__ void tile_gemm_rr(const TA *__restrict__ A, int64_t l
   }
 }
 
-// C = A.B, or (DUAL) C = silu(A.B) * (A2.B2).  Grid: (ceil(N/64), ceil(M/64)).
+// C = act(A.B + bias), or (DUAL) C = silu(A.B) * (A2.B2).  Grid: (ceil(N/64), ceil(M/64)).
+// bias: one value per column of C (may be null), act: see act_f32.
 template <typename TA, typename TB, typename TC, bool DUAL>
 __global__ __launch_bounds__(GTHREADS) void gemm_generic_kernel(
     const TA *__restrict__ A, int64_t lda, const TB *__restrict__ B, int64_t ldb, int K,
     const TA *__restrict__ A2, int64_t lda2, const TB *__restrict__ B2, int64_t ldb2, int K2,
-    TC *__restrict__ C, int64_t ldc, int M, int N) {
+    TC *__restrict__ C, int64_t ldc, int M, int N, const TC *__restrict__ bias = nullptr, int act = ACT_NONE) {
   __shared__ float sA[GK][GT + 1];
   __shared__ float sB[GK][GT];
   const int m0 = blockIdx.y * GT, n0 = blockIdx.x * GT;
@@ -79,8 +80,19 @@ __global__ __launch_bounds__(GTHREADS) void gemm_generic_kernel(
       if (c >= N) continue;
       float v = acc[i][j];
       if (DUAL) v = (v / (1.0f + expf(-v))) * acc2[i][j];
+      else v = act_f32(v + (bias ? Elem<TC>::load(bias + c) : 0.0f), act);
       Elem<TC>::store(C + (int64_t)r * ldc + c, v);
     }
+  }
+}
+
+// C[r][c] = act(bias[c]): the non-GLU sub-layer of a pair of rank 0 (empty product).
+template <typename TC>
+__global__ void bias_act_fill_kernel(TC *C, int64_t ldc, int M, int N, const TC *bias, int act) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < (int64_t)M * N) {
+    const int64_t r = i / N, c = i % N;
+    Elem<TC>::store(C + r * ldc + c, act_f32(bias ? Elem<TC>::load(bias + c) : 0.0f, act));
   }
 }
 

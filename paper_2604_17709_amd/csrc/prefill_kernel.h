@@ -65,6 +65,8 @@ struct PfProblem {         // one product  act[T x K] . W^T
   uint16_t *out;           // output [T x width] bf16 row-major: feature tile g lands at columns 16 g ..
   long long ldo;
   int width;               // valid output columns
+  const uint16_t *bias;    // POST kernels only: out = act(product + bias[column]); may be null
+  int post_act;            // see act_f32
 };
 
 struct PfParams {
@@ -83,7 +85,8 @@ struct PfShared {
 };
 
 // GLU = true: the output buffer already holds the gate values g (bf16); store silu(g) * result.
-template <int MF, bool GLU>
+// POST = true: bias and activation of the non-GLU MLP sub-layer on the fp32 accumulators.
+template <int MF, bool GLU, bool POST = false>
 __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -290,17 +293,35 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     e_start = c1; c_wait_all = c_wait; c_bar_all = c_bar;
 #endif
   }
+  // (lane-derived values are taken afresh so that none has to live through the main loop)
+  int tid_e = threadIdx.x;
+  asm volatile("" : "+v"(tid_e));
+  const int lane_e = tid_e & 63, wave_e = tid_e >> 6, wf_e = wave_e & 1, wt_e = wave_e >> 1;
   // accumulators -> bf16 pairs first (registers only): it overlaps the wait for the slowest wavefront
   uint2 pk[MB][4][4];
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int g = 0; g < 4; ++g) {
+      float b[4] = {0.f, 0.f, 0.f, 0.f};
+      if (POST && Q.bias != nullptr) {
+        // element 4 g + e of block (i, j) is feature 32 i + 8 g + 4 (lane / 32) + e of this wavefront's 16 MF features
+        const int f0 = (fb * BF_TILES + wf_e * MF) * 16 + 32 * i + 8 * g + 4 * (lane_e >> 5);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        pk[i][j][g].x = pack_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]);
-        pk[i][j][g].y = pack_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+        for (int e = 0; e < 4; ++e)
+          if (f0 + e < Q.width) b[e] = bf16_to_f32(Q.bias[f0 + e]);
       }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float v[4] = {acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        if (POST) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = act_f32(v[e] + b[e], Q.post_act);
+        }
+        pk[i][j][g].x = pack_bf16x2(v[0], v[1]);
+        pk[i][j][g].y = pack_bf16x2(v[2], v[3]);
+      }
+    }
   __syncthreads();         // the epilogue reuses the LDS buffers
 
   // ---- epilogue: through LDS (free by now; the barrier above has passed), so that the global
@@ -312,10 +333,6 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   // number, the two 8-byte halves of a chunk swapped in rows with bit 3 set (16 consecutive rows
   // of one 8-byte write then cover 128 bytes of distinct banks).  Only the wavefront itself
   // touches the region: no barrier.
-  // (lane-derived values are taken afresh so that none has to live through the main loop)
-  int tid_e = threadIdx.x;
-  asm volatile("" : "+v"(tid_e));
-  const int lane_e = tid_e & 63, wave_e = tid_e >> 6, wf_e = wave_e & 1, wt_e = wave_e >> 1;
   constexpr int CPR = 2 * MF;                      // chunks per row
   constexpr int PITCH = CPR * 16;
   constexpr int RPI = 64 / CPR;                    // token rows per store instruction

@@ -242,6 +242,8 @@ struct SkReduceParams {
   int n_out;
   SkOut o[3];
   int glu_delta;             // > 0: o[0] columns are the gate product, the up product sits glu_delta columns later
+  const uint16_t *bias;      // single non-GLU product: out = act(sum + bias[column]); may be null
+  int act;                   // see act_f32
 };
 
 // one thread = 8 consecutive columns of one token row
@@ -294,6 +296,11 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkReduceParams
     for (int e = 0; e < 8; ++e) v[e] = silu_f32(v[e]) * u[e];
   }
   const int oc = col - o.col0;
+  if (R.glu_delta <= 0 && (R.bias != nullptr || R.act != ACT_NONE)) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      v[e] = act_f32(v[e] + ((R.bias != nullptr && oc + e < o.width) ? bf16_to_f32(R.bias[oc + e]) : 0.f), R.act);
+  }
   const u32x4_t pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
   uint16_t *dst = o.out + (long long)tok * o.ldo + oc;
   if (oc + 8 <= o.width && ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0)) {

@@ -49,6 +49,8 @@ struct StParams {
   int n_prob;
   int glu;                   // 1: prob[0] = gate, prob[1] = up (same shapes); output silu(gate) * up through prob[0]
   StProblem prob[3];
+  const uint16_t *bias;      // single non-GLU product: out = act(product + bias[column]); may be null
+  int act;                   // see act_f32
 };
 
 // NB = 32-token blocks (1 or 2)
@@ -197,6 +199,11 @@ __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P)
     }
     const int tok = 32 * j + (lane & 31);
     const int col = fblk * 32 + 8 * q + 4 * (lane >> 5);
+    if (!P.glu && (P.bias != nullptr || P.act != ACT_NONE)) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        v[e] = act_f32(v[e] + ((P.bias != nullptr && col + e < O.width) ? bf16_to_f32(P.bias[col + e]) : 0.f), P.act);
+    }
     if (tok < P.T && col < O.width) {
       uint2 pk;
       pk.x = pack_bf16x2(v[0], v[1]);

@@ -125,6 +125,20 @@ def test_probe_argument_validation():
     assert L.deinfer_probe_mfma_bf16(FAKE, 8192, 10, sink + 8, big, None, None) == dn.ERR_MISALIGNED
 
 
+def test_linear_act_argument_validation():
+    L = dn.lib()
+    f = make()
+    args = lambda bias=FAKE + 0x500000, act=1, ff=f: (FAKE + 0x200000, 4, 64, ctypes.byref(ff), bias, act,
+                                                      FAKE + 0x300000, 48, FAKE + 0x400000, 1 << 26, None)
+    assert L.deinfer_lowrank_linear_act(*args(act=5)) == dn.ERR_UNSUPPORTED
+    assert L.deinfer_lowrank_linear_act(*args(act=-1)) == dn.ERR_UNSUPPORTED
+    assert L.deinfer_lowrank_linear_act(*args(bias=FAKE + 1)) == dn.ERR_MISALIGNED
+    assert L.deinfer_lowrank_linear_act(*args(bias=FAKE + 8, ff=make(layout=dn.LAYOUT_PACKED))) == dn.ERR_MISALIGNED
+    assert L.deinfer_lowrank_linear_act(FAKE, 4, 64, None, None, 0, FAKE, 48, FAKE, 1 << 20, None) == dn.ERR_INVALID_ARG
+    # T == 0 stays a no-op
+    assert L.deinfer_lowrank_linear_act(None, 0, 64, ctypes.byref(f), None, 1, None, 48, None, 0, None) == dn.OK
+
+
 def test_group_calls_validate_shared_properties():
     L = dn.lib()
     fq, fk, fv = make(), make(d_out=16, r=8), make(d_out=16, r=8)

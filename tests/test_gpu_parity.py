@@ -315,3 +315,47 @@ def test_keys_rebuilt_from_the_low_rank_cache(dn, T):
     ref = oracle.lowrank_linear(x.values, U.values, V.values)
     assert max_err(to_host(k2), ref) <= TOL["bf16"]
     assert max_err(to_host(k2), to_host(k).astype(np.float64)) <= 2.0 ** -7    # at most an output rounding apart
+
+
+# ------------------------------------------------------------------ non-GLU sub-layer: bias and activation
+@pytest.mark.parametrize("act", [0, 1, 2])
+@pytest.mark.parametrize("kind,T,d_in,r,d_out", [
+    ("f32", 16, 96, 24, 70),          # generic fp32 kernel
+    ("raw", 9, 96, 24, 70),           # generic kernel, bf16 storage
+    ("packed", 3, 264, 96, 200),      # T <= 16 kernel
+    ("packed", 16, 128, 40, 3300),    # T <= 16, ragged last feature tile
+    ("packed", 24, 264, 96, 3240),    # one-launch stage (>= 100 blocks of 32 features)
+    ("packed", 24, 264, 96, 200),     # streaming kernel + reduce
+    ("packed", 64, 520, 72, 1000),
+    ("packed", 128, 264, 96, 136),
+    ("packed", 300, 264, 96, 200),    # compute-bound kernel, ragged token block
+    ("packed", 520, 128, 40, 777),    # ... output rows not 16-byte aligned (odd width)
+])
+def test_linear_with_bias_and_activation(dn, kind, T, d_in, r, d_out, act):
+    import torch
+    dtype = "f32" if kind == "f32" else "bf16"
+    x, U, V = gen(61, T, d_in, r, d_out, dtype)
+    b = si.make(61, 9, (1, d_out), 0.5, dtype)
+    p, keep = pair(dn, U, V, packed=(kind == "packed"))
+    ws = ws_for(dn, T, [p])
+    bias = to_dev(b).reshape(-1)
+    y = dn.deinfer_lowrank_linear_act(to_dev(x), p, ws, bias=bias, act=act)
+    ref = oracle.lowrank_linear_act(x.values, U.values, V.values, b.values.reshape(-1), act)
+    assert max_err(to_host(y), ref) <= TOL[dtype]
+    # without bias and activation the call is the plain linear layer, bit for bit
+    if act == 0:
+        y0 = dn.deinfer_lowrank_linear_act(to_dev(x), p, ws)
+        assert torch.equal(y0, dn.deinfer_lowrank_linear(to_dev(x), p, ws))
+
+
+def test_bias_and_activation_with_an_empty_product(dn):
+    import torch
+    for packed in (False, True):
+        x, U, V = gen(62, 5, 64, 8, 48, "bf16")
+        b = si.make(62, 9, (1, 48), 1.0, "bf16")
+        p, keep = pair(dn, U, V, packed=packed)
+        p.desc.r = 0
+        ws = ws_for(dn, 5, [p])
+        y = dn.deinfer_lowrank_linear_act(to_dev(x), p, ws, bias=to_dev(b).reshape(-1), act=dn.ACT_RELU)
+        want = np.tile(np.maximum(b.values.reshape(-1).astype(np.float64), 0.0), (5, 1))
+        assert np.array_equal(to_host(y), want)
