@@ -44,6 +44,9 @@ WORKLOADS = {
     "llama70b_keep40_prefill": ("llama70b_keep40", 4096, "mfma"),
     # keys and values of cached tokens rebuilt from the paged low-rank cache (a different step, see kv_rebuild)
     "llama7b_keep80_kv_rebuild": ("llama7b_keep80", 8192, "mfma"),
+    # non-GLU block: the MLP is act(x U1 V1 + b1) then a second pair with bias (deinfer_lowrank_linear_act)
+    "opt30b_keep60_decode": ("opt30b_keep60", 64, "hbm"),
+    "opt30b_keep60_prefill": ("opt30b_keep60", 4096, "mfma"),
 }
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
@@ -126,6 +129,8 @@ def main():
             c[p] = dn.Pair(d, [buf])
         copies.append(c)
     x = dev(host["x"]); a = dev(host["a"]); h_in = dev(host["h_in"])
+    if not shape.glu:
+        b_gate = dev(host["b_gate"]).reshape(-1); b_down = dev(host["b_down"]).reshape(-1)
     bf = torch.bfloat16
     q = torch.empty((T, proj["q"][1]), dtype=bf, device="cuda")
     k = torch.empty((T, proj["k"][1]), dtype=bf, device="cuda")
@@ -135,7 +140,7 @@ def main():
     y = torch.empty((T, proj["down"][1]), dtype=bf, device="cuda")
     ws_bytes = max(dn.deinfer_workspace_bytes(T, [packed0["q"], packed0["k"], packed0["v"]]),
                    dn.deinfer_workspace_bytes(T, [packed0["o"]]),
-                   dn.deinfer_workspace_bytes(T, [packed0["gate"], packed0["up"]]),
+                   dn.deinfer_workspace_bytes(T, [packed0["gate"], packed0["up"]] if shape.glu else [packed0["gate"]]),
                    dn.deinfer_workspace_bytes(T, [packed0["down"]]))
     ws = dn.Workspace(ws_bytes)
     torch.cuda.synchronize()
@@ -153,9 +158,14 @@ def main():
                                             q.data_ptr(), ld(q), k.data_ptr(), ld(k), v.data_ptr(), ld(v),
                                             None, 0, None, 0, wsp, wsn, stream_handle)),
             "o": (L.deinfer_lowrank_linear, (a.data_ptr(), T, ld(a), B(c["o"].desc), o.data_ptr(), ld(o), wsp, wsn, stream_handle)),
-            "gateup": (L.deinfer_lowrank_gateup_silu, (x.data_ptr(), T, ld(x), B(c["gate"].desc), B(c["up"].desc),
-                                                       h.data_ptr(), ld(h), wsp, wsn, stream_handle)),
-            "down": (L.deinfer_lowrank_down, (h_in.data_ptr(), T, ld(h_in), B(c["down"].desc), y.data_ptr(), ld(y), wsp, wsn, stream_handle)),
+            "gateup": ((L.deinfer_lowrank_gateup_silu, (x.data_ptr(), T, ld(x), B(c["gate"].desc), B(c["up"].desc),
+                                                        h.data_ptr(), ld(h), wsp, wsn, stream_handle)) if shape.glu else
+                       (L.deinfer_lowrank_linear_act, (x.data_ptr(), T, ld(x), B(c["gate"].desc), b_gate.data_ptr(), dn.ACT_RELU,
+                                                       h.data_ptr(), ld(h), wsp, wsn, stream_handle))),
+            "down": ((L.deinfer_lowrank_down, (h_in.data_ptr(), T, ld(h_in), B(c["down"].desc), y.data_ptr(), ld(y), wsp, wsn, stream_handle))
+                     if shape.glu else
+                     (L.deinfer_lowrank_linear_act, (h_in.data_ptr(), T, ld(h_in), B(c["down"].desc), b_down.data_ptr(), dn.ACT_NONE,
+                                                     y.data_ptr(), ld(y), wsp, wsn, stream_handle))),
         }
 
     def run_calls(calls, names=("qkv", "o", "gateup", "down")):
@@ -233,7 +243,7 @@ def main():
     call_defs = {
         "qkv": (("q", "k", "v"), [proj["q"][1], proj["k"][1], proj["v"][1]]),
         "o": (("o",), [proj["o"][1]]),
-        "gateup": (("gate", "up"), [proj["gate"][1]]),
+        "gateup": (("gate", "up") if shape.glu else ("gate",), [proj["gate"][1]]),
         "down": (("down",), [proj["down"][1]]),
     }
     n_call = max(20, min(args.steps, 200))
@@ -284,7 +294,8 @@ def main():
         pl = ps[-1]
         kflops["up"] = 2.0 * T * ranks[pl] * proj[pl][1]
         kbytes["up"] = s * ranks[pl] * proj[pl][1] + s * T * ranks[pl] + s * T * proj[pl][1] * (2 if dom == "gateup" else 1)
-    entry = {"qkv": "qkv", "o": "linear", "gateup": "gateup_silu", "down": "down"}[dom]
+    entry = {"qkv": "qkv", "o": "linear", "gateup": "gateup_silu" if shape.glu else "linear_act",
+             "down": "down" if shape.glu else "linear_act"}[dom]
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "hbm_traffic_%s_T%d.txt" % (args.workload, T))
     if os.path.exists(tfile):
@@ -376,7 +387,8 @@ def main():
         "ms_per_step": round(sec_per_step * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s T=%d (qkv+o+gateup_silu+down of one block)" % (args.workload, T),
+        "config": {"workload": "%s T=%d (%s of one block)" % (args.workload, T, "qkv+o+gateup_silu+down" if shape.glu else
+                                                              "qkv+o+linear_act(bias, ReLU)+linear_act(bias)"),
                    "ranks": ranks, "weight_MB": round(weight_bytes / 1e6, 1), "weight_copies": n_copies,
                    "launch": launch_mode},
         "step_GBs": round(step_bytes / sec_per_step / 1e9, 1),
@@ -431,8 +443,12 @@ def main():
             t_a = time.perf_counter()
             oracle.lowrank_qkv(xs, W["U_q"], W["V_q"], W["U_k"], W["V_k"], W["U_v"], W["V_v"])
             oracle.lowrank_linear(as_, W["U_o"], W["V_o"])
-            oracle.lowrank_gateup_silu(xs, W["U_gate"], W["V_gate"], W["U_up"], W["V_up"])
-            oracle.lowrank_down(hs, W["U_down"], W["V_down"])
+            if shape.glu:
+                oracle.lowrank_gateup_silu(xs, W["U_gate"], W["V_gate"], W["U_up"], W["V_up"])
+                oracle.lowrank_down(hs, W["U_down"], W["V_down"])
+            else:
+                oracle.lowrank_linear_act(xs, W["U_gate"], W["V_gate"], f64(host["b_gate"]).reshape(-1), oracle.ACT_RELU)
+                oracle.lowrank_linear_act(hs, W["U_down"], W["V_down"], f64(host["b_down"]).reshape(-1), oracle.ACT_NONE)
             cpu_s += time.perf_counter() - t_a
             passes += 1
         out["cpu_baseline"] = {"value": round(rows * passes / cpu_s, 2), "unit": "tokens/s", "cores": oracle.num_threads(),

@@ -142,14 +142,18 @@ class BlockShape:
     keep_den: int
     dtype: str = "bf16"
     weight_std: float = 0.02
+    glu: bool = True    # False: non-GLU MLP, "gate" is its first layer (bias, activation), there is no "up"
 
     def projections(self) -> Dict[str, Tuple[int, int]]:
-        return {
+        p = {
             "q": (self.hidden, self.hidden), "k": (self.hidden, self.kv_width),
             "v": (self.hidden, self.kv_width), "o": (self.hidden, self.hidden),
             "gate": (self.hidden, self.ffn), "up": (self.hidden, self.ffn),
             "down": (self.ffn, self.hidden),
         }
+        if not self.glu:
+            del p["up"]
+        return p
 
 
 BLOCKS: Dict[str, BlockShape] = {
@@ -162,6 +166,8 @@ BLOCKS: Dict[str, BlockShape] = {
     "llama13b_keep60": BlockShape("llama13b_keep60", 5120, 13824, 5120, 3, 5),
     # Llama-70B-shaped GQA layer (8 kv heads -> k/v width 1024), 60 % reduction
     "llama70b_keep40": BlockShape("llama70b_keep40", 8192, 28672, 1024, 2, 5),
+    # OPT-30B-shaped block (non-GLU MLP with ReLU and biases, full-width k/v), 40 % reduction
+    "opt30b_keep60": BlockShape("opt30b_keep60", 7168, 28672, 7168, 3, 5, glu=False),
 }
 
 _ORDER = ["q", "k", "v", "o", "gate", "up", "down"]
@@ -177,8 +183,11 @@ def block_tensors(shape: BlockShape, ranks: Dict[str, int], T: int, seed: int,
     out["a"] = make(seed, 2, (T, shape.hidden), 1.0, shape.dtype)
     out["h_in"] = make(seed, 3, (T, shape.ffn), 1.0, shape.dtype)
     proj = shape.projections()
+    if not shape.glu:      # biases of the two MLP layers
+        out["b_gate"] = make(seed, 4, (1, shape.ffn), shape.weight_std, shape.dtype)
+        out["b_down"] = make(seed, 5, (1, shape.hidden), shape.weight_std, shape.dtype)
     for i, p in enumerate(_ORDER):
-        if names is not None and p not in names:
+        if p not in proj or (names is not None and p not in names):
             continue
         d_in, d_out = proj[p]
         r = ranks[p]

@@ -35,6 +35,8 @@ def block(dn, name, seed):
             assert ranks[p] == oracle.rank_for_keep(m, n, shape.keep_num, shape.keep_den)
         P, H = {}, {}
         for i, p in enumerate(si._ORDER):
+            if p not in proj:
+                continue
             m, n = proj[p]
             U = si.make(seed, 16 + 2 * i, (m, ranks[p]), shape.weight_std, "bf16")
             V = si.make(seed, 17 + 2 * i, (ranks[p], n), shape.weight_std, "bf16")
@@ -91,22 +93,30 @@ def run_block(dn, name, T, seed, row_limit):
     hd, hh = activations(seed, 3, T, shape.ffn, rows)
     nbytes = max(dn.deinfer_workspace_bytes(T, [P["q"], P["k"], P["v"]]),
                  dn.deinfer_workspace_bytes(T, [P["o"]]),
-                 dn.deinfer_workspace_bytes(T, [P["gate"], P["up"]]),
+                 dn.deinfer_workspace_bytes(T, [P["gate"], P["up"]] if shape.glu else [P["gate"]]),
                  dn.deinfer_workspace_bytes(T, [P["down"]]))
     ws = dn.Workspace(nbytes)
     tk = torch.zeros((T, ranks["k"]), dtype=torch.bfloat16, device="cuda")
     tv = torch.zeros((T, ranks["v"]), dtype=torch.bfloat16, device="cuda")
     q, k, v = dn.deinfer_lowrank_qkv(xd, P["q"], P["k"], P["v"], ws, t_k=tk, t_v=tv)
     o = dn.deinfer_lowrank_linear(ad, P["o"], ws)
-    h = dn.deinfer_lowrank_gateup_silu(xd, P["gate"], P["up"], ws)
-    y = dn.deinfer_lowrank_down(hd, P["down"], ws)
+    if shape.glu:
+        h = dn.deinfer_lowrank_gateup_silu(xd, P["gate"], P["up"], ws)
+        y = dn.deinfer_lowrank_down(hd, P["down"], ws)
+    else:       # non-GLU MLP: act(x U1 V1 + b1), then the second pair with its bias
+        b1 = si.make(seed, 4, (1, shape.ffn), shape.weight_std, "bf16")
+        b2 = si.make(seed, 5, (1, shape.hidden), shape.weight_std, "bf16")
+        h = dn.deinfer_lowrank_linear_act(xd, P["gate"], ws, bias=to_dev(b1).reshape(-1), act=dn.ACT_RELU)
+        y = dn.deinfer_lowrank_linear_act(hd, P["down"], ws, bias=to_dev(b2).reshape(-1), act=dn.ACT_NONE)
     ws.check()
     sel = torch.tensor(rows, device="cuda")
     rq, rk, rv, rtk, rtv = oracle.lowrank_qkv(xh, *H["q"], *H["k"], *H["v"], return_t=True)
     refs = {"q": (q, rq), "k": (k, rk), "v": (v, rv), "t_k": (tk, rtk), "t_v": (tv, rtv),
             "o": (o, oracle.lowrank_linear(ah, *H["o"])),
-            "h": (h, oracle.lowrank_gateup_silu(xh, *H["gate"], *H["up"])),
-            "y": (y, oracle.lowrank_down(hh, *H["down"]))}
+            "h": (h, oracle.lowrank_gateup_silu(xh, *H["gate"], *H["up"]) if shape.glu else
+                  oracle.lowrank_linear_act(xh, *H["gate"], b1.values.reshape(-1), oracle.ACT_RELU)),
+            "y": (y, oracle.lowrank_down(hh, *H["down"]) if shape.glu else
+                  oracle.lowrank_linear_act(hh, *H["down"], b2.values.reshape(-1), oracle.ACT_NONE))}
     errs = {n: max_err(to_host(got[sel]), ref) for n, (got, ref) in refs.items()}
     print(name, "T=%d" % T, "rows=%d" % len(rows), {n: "%.2e" % e for n, e in errs.items()}, flush=True)
     assert max(errs.values()) <= TOL["bf16"], errs
@@ -135,3 +145,8 @@ def test_llama7b_prefill_8192(dn, name):
 
 def test_llama13b_keep60_mixed_8256(dn):
     run_block(dn, "llama13b_keep60", 8256, seed=3, row_limit=10)
+
+
+@pytest.mark.parametrize("T", [64, 4096])
+def test_opt30b_keep60_non_glu(dn, T):
+    run_block(dn, "opt30b_keep60", T, seed=5, row_limit=8)
