@@ -115,6 +115,36 @@ SkPlan skinny_plan(int64_t T, const deinfer_factors_t *const *f, int n) {
   return pl;
 }
 
+// ---- k-split of the first stage of a compute-bound call with few token blocks
+// Stage 1 has a long k (d_in) and few features (the ranks): with T of a few hundred tokens its
+// 256 x 256 tiles are far fewer than the compute units.  The k range is then cut into up to 8
+// parts (fp32 partial products, summed by the reduce kernel of the T <= 128 path).  Stage 2
+// (short k, many features) is left whole: its partial products would cost more than they save.
+struct PfSplitPlan {
+  int n_parts, kb_per_part, n_fblocks, n_tblocks;
+  size_t part_bytes;          // 0: no split
+};
+PfSplitPlan prefill_split_plan(int64_t T, const deinfer_factors_t *const *f, int n) {
+  PfSplitPlan pl;
+  memset(&pl, 0, sizeof(pl));
+  int64_t tiles = 0;
+  for (int i = 0; i < n; ++i) tiles += geometry(f[i]).n_rtiles;
+  const int64_t KB = ceil_div(f[0]->d_in, 32);
+  pl.n_tblocks = (int)ceil_div(T, 256);
+  pl.n_fblocks = (int)ceil_div(tiles, 16);
+  pl.n_parts = 1; pl.kb_per_part = (int)KB;
+  const int64_t wgs = (int64_t)pl.n_tblocks * pl.n_fblocks;
+  if (wgs <= 0 || wgs > 128 || KB < 16) return pl;
+  int64_t p = 256 / wgs;
+  if (p > SK_MAX_PARTS) p = SK_MAX_PARTS;
+  if (p > KB / 8) p = KB / 8;                       // at least 8 pipeline stages per part
+  if (p < 2) return pl;
+  pl.kb_per_part = (int)ceil_div(KB, p);
+  pl.n_parts = (int)ceil_div(KB, pl.kb_per_part);   // every part is non-empty
+  pl.part_bytes = (size_t)pl.n_parts * pl.n_tblocks * 256 * (size_t)pl.n_fblocks * 256 * sizeof(float);
+  return pl;
+}
+
 int validate_pair(const deinfer_factors_t *f, const char *name) {
   if (!f) return fail(DEINFER_ERR_INVALID_ARG, "%s: factor descriptor is NULL", name);
   if (f->d_in <= 0 || f->d_out <= 0 || f->r < 0)
@@ -153,7 +183,8 @@ size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
     const int nt = token_tiles(Tc);
     const size_t rp = (size_t)(rtot_pad > 0 ? rtot_pad : 32);
     const size_t tdec = (size_t)round_up((int64_t)nt * 16 * rp * 2, 256) + (size_t)DEC_MAX_PARTS * nt * 16 * rp * 4;
-    const size_t tpre = T > 128 ? (size_t)round_up(T, 256) * rp * 2 : 0;
+    size_t tpre = T > 128 ? (size_t)round_up(T, 256) * rp * 2 : 0;
+    if (T > 128) tpre = (size_t)round_up((int64_t)tpre, 256) + prefill_split_plan(T, pairs, n).part_bytes;
     scratch = round_up((int64_t)tdec, 256) + round_up((int64_t)tpre, 256);
     if (T <= 128) {          // (the upward-projection-only call uses this schedule for every T <= 128)
       const SkPlan pl = skinny_plan(T, pairs, n);
@@ -361,8 +392,8 @@ int run_generic(const Group &gq) {
 }
 
 // The compute-bound path (T > 128) lives in its own file; it uses Group and the helpers above.
-#include "prefill_host.inc"
 #include "skinny_host.inc"
+#include "prefill_host.inc"
 
 int run_group(Group gq) {
   // ---- validation (host only)

@@ -73,6 +73,11 @@ struct PfParams {
   int T;
   int n_tblocks;           // ceil(T / 256)
   PfProblem prob;
+  // SPLIT kernels only (few tiles, long k: the k range is cut into parts, one workgroup per part)
+  int n_fblocks;           // feature blocks of 256; grid = n_tblocks * n_fblocks * n_parts
+  int kb_per_part;         // k-blocks per part
+  float *part;             // [n_parts][n_tblocks * 256][n_fblocks * 256] fp32 partial products
+  long long part_stride;   // elements between parts
 #ifdef DEINFER_PF_TRACE
   unsigned long long *trace;   // diagnostic build only: per-workgroup cycle counts
 #endif
@@ -86,7 +91,9 @@ struct PfShared {
 
 // GLU = true: the output buffer already holds the gate values g (bf16); store silu(g) * result.
 // POST = true: bias and activation of the non-GLU MLP sub-layer on the fp32 accumulators.
-template <int MF, bool GLU, bool POST = false>
+// SPLIT = true: this workgroup multiplies only its part of the k range and stores the fp32
+// accumulators to a partial buffer (the sum and the epilogue are a second, small kernel's).
+template <int MF, bool GLU, bool POST = false, bool SPLIT = false>
 __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -99,7 +106,10 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   // blocks of one feature block run at the same time, spread over the XCDs, so each L2
   // streams those weights once
   const int tb = blockIdx.x % P.n_tblocks;
-  const int fb = blockIdx.x / P.n_tblocks;
+  const int fb_all = blockIdx.x / P.n_tblocks;
+  const int fb = SPLIT ? fb_all % P.n_fblocks : fb_all;
+  const int kpart = SPLIT ? fb_all / P.n_fblocks : 0;
+  const int kb0 = SPLIT ? kpart * P.kb_per_part : 0;          // first k-block of this workgroup
   const int tok0 = tb * PF_BT;
 
 #ifdef DEINFER_PF_TRACE
@@ -150,7 +160,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     unsigned xrow[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) xrow[i] = (unsigned)(tok0 + 16 * (4 * i + wave) + (lane >> 2)) * (unsigned)(Q.lda * 2);
-    const int n_stages = Q.KB;
+    const int n_stages = SPLIT ? (Q.KB - kb0 < P.kb_per_part ? Q.KB - kb0 : P.kb_per_part) : Q.KB;
 
     // one load instruction (index 0 .. LPS - 1) of stage st: weight tiles first, then activation rows.
     // Activation chunks beyond K re-read valid columns (k clamped to K - 8), which meet zero weights.
@@ -159,10 +169,10 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       const int buf = st & (PF_STAGES - 1);
       if (idx < WT) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(wres[idx], (DEINFER_LOCAL void *)&S.w[buf][uwave * WT + idx][0], 16,
-                                                 wlane, wtile_off[idx] + (unsigned)st * 1024u, 0, 0);
+                                                 wlane, wtile_off[idx] + (unsigned)(st + kb0) * 1024u, 0, 0);
       } else {
         const int i = idx - WT;
-        unsigned kb = (unsigned)st * (PF_BK * 2) + xchunk;
+        unsigned kb = (unsigned)(st + kb0) * (PF_BK * 2) + xchunk;
         kb = kb < xklim ? kb : xklim;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LOCAL void *)&S.x[buf][16 * (4 * i + uwave) * PF_XPITCH], 16,
                                                  xrow[i] + kb, 0, 0, 0);
@@ -298,6 +308,23 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   int tid_e = threadIdx.x;
   asm volatile("" : "+v"(tid_e));
   const int lane_e = tid_e & 63, wave_e = tid_e >> 6, wf_e = wave_e & 1, wt_e = wave_e >> 1;
+  if constexpr (SPLIT) {
+    // element 4 g + e of block (i, j) is feature 32 i + 8 g + 4 (lane / 32) + e, token 32 j + lane % 32:
+    // four consecutive features = one 16-byte store; the buffer has whole tiles, no bounds to check
+    const long long F = (long long)P.n_fblocks * (32 * MF);
+    float *dst = P.part + (long long)kpart * P.part_stride + (long long)(tok0 + wt_e * 128 + (lane_e & 31)) * F +
+                 (fb * BF_TILES + wf_e * MF) * 16 + 4 * (lane_e >> 5);
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4_t v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          *reinterpret_cast<f32x4_t *>(dst + (long long)(32 * j) * F + 32 * i + 8 * g) = v;
+        }
+    return;
+  }
   // accumulators -> bf16 pairs first (registers only): it overlaps the wait for the slowest wavefront
   uint2 pk[MB][4][4];
 #pragma unroll

@@ -359,3 +359,38 @@ def test_bias_and_activation_with_an_empty_product(dn):
         y = dn.deinfer_lowrank_linear_act(to_dev(x), p, ws, bias=to_dev(b).reshape(-1), act=dn.ACT_RELU)
         want = np.tile(np.maximum(b.values.reshape(-1).astype(np.float64), 0.0), (5, 1))
         assert np.array_equal(to_host(y), want)
+
+
+@pytest.mark.parametrize("T", [200, 600])
+def test_first_stage_split_over_k(dn, T):
+    """A few hundred tokens and a long d_in: the first stage of the compute-bound path is cut
+    into k-parts and summed by the reduce kernel, which also writes the rank-space outputs."""
+    import torch
+    d_in = 1096                                   # 35 k-blocks: four parts, the last one shorter
+    x = si.make(8, 1, (T, d_in), 1.0, "bf16")
+    shapes = {"q": (70, 256), "k": (24, 64), "v": (41, 72), "g": (100, 600), "u": (90, 600)}
+    F, host = {}, {}
+    for i, (n, (r, d_out)) in enumerate(shapes.items()):
+        U = si.make(8, 10 + 2 * i, (d_in, r), 1.0 / np.sqrt(d_in), "bf16")
+        V = si.make(8, 11 + 2 * i, (r, d_out), 1.0 / np.sqrt(r), "bf16")
+        F[n], _k = pair(dn, U, V, packed=True)
+        host[n] = (U.values, V.values)
+    xd = to_dev(x)
+    ws = dn.Workspace(max(dn.deinfer_workspace_bytes(T, [F["q"], F["k"], F["v"]]),
+                          dn.deinfer_workspace_bytes(T, [F["g"], F["u"]])))
+    tk = torch.zeros((T, 24), dtype=torch.bfloat16, device="cuda")
+    tv = torch.zeros((T, 48), dtype=torch.bfloat16, device="cuda")     # wider than r_v = 41: the rest stays zero
+    q, k, v = dn.deinfer_lowrank_qkv(xd, F["q"], F["k"], F["v"], ws, t_k=tk, t_v=tv)
+    h = dn.deinfer_lowrank_gateup_silu(xd, F["g"], F["u"], ws)
+    b = si.make(8, 30, (1, 600), 0.5, "bf16")
+    a = dn.deinfer_lowrank_linear_act(xd, F["g"], ws, bias=to_dev(b).reshape(-1), act=dn.ACT_GELU)
+    ws.check()
+    rq, rk, rv, rtk, rtv = oracle.lowrank_qkv(x.values, *host["q"], *host["k"], *host["v"], return_t=True)
+    for got, ref in ((q, rq), (k, rk), (v, rv), (tk, rtk), (tv[:, :41], rtv)):
+        assert max_err(to_host(got), ref) <= TOL["bf16"]
+    assert bool((tv[:, 41:] == 0).all())
+    assert max_err(to_host(h), oracle.lowrank_gateup_silu(x.values, *host["g"], *host["u"])) <= TOL["bf16"]
+    assert max_err(to_host(a), oracle.lowrank_linear_act(x.values, *host["g"], b.values.reshape(-1), oracle.ACT_GELU)) <= TOL["bf16"]
+    # the keys rebuilt from t_k equal the keys of the qkv call up to the output rounding
+    k2 = dn.deinfer_lowrank_up(tk, F["k"], ws)
+    assert max_err(to_host(k2), to_host(k)) <= 2.0 ** -7

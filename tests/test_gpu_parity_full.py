@@ -150,3 +150,8 @@ def test_llama13b_keep60_mixed_8256(dn):
 @pytest.mark.parametrize("T", [64, 4096])
 def test_opt30b_keep60_non_glu(dn, T):
     run_block(dn, "opt30b_keep60", T, seed=5, row_limit=8)
+
+
+def test_llama7b_keep60_chunk_of_512_tokens(dn):
+    """Between the decode sizes and the large prefill: the first stage runs split over k."""
+    run_block(dn, "llama7b_keep60", 512, seed=2, row_limit=10)
