@@ -216,6 +216,31 @@ int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_fact
                        void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The two stages as separate calls (Sec. 4.1 puts the one exchange between tensor-parallel ranks
+ * of a sub-layer exactly between them: a rank multiplies x by its column slice of the downward
+ * matrices, the rank-space results are gathered - or, for the second sub-layer, whose downward
+ * matrix is split by rows, summed - and the rank then applies its shard of the upward matrices;
+ * on one GPU the calls are what one rank runs on its shard).
+ *
+ * deinfer_lowrank_down_proj: t_i = x U_i for 1 to 3 pairs that share x (the concatenated
+ *   downward projection); t_out[i]: device, T x r_i, pitch ldt[i] >= r_i, written in the pairs'
+ *   dtype (bf16: one rounding); f, t_out, ldt: host arrays of n_pairs entries.  No upward
+ *   projection runs and V is not read.
+ * deinfer_lowrank_up_glu_silu: h = silu(t_gate V_gate) * (t_up V_up), the second stage of
+ *   deinfer_lowrank_gateup_silu alone; t_gate / t_up as the t of deinfer_lowrank_up (same
+ *   alignment and padding rules for PACKED pairs), both pairs share d_out.
+ * Otherwise the contract of deinfer_lowrank_linear.
+ */
+int deinfer_lowrank_down_proj(const void *x, int64_t T, int64_t ldx,
+                              const deinfer_factors_t *const *f, int n_pairs,
+                              void *const *t_out, const int64_t *ldt,
+                              void *ws, size_t ws_bytes, void *stream);
+int deinfer_lowrank_up_glu_silu(const void *t_gate, int64_t ldtg, const void *t_up, int64_t ldtu,
+                                int64_t T, const deinfer_factors_t *fgate,
+                                const deinfer_factors_t *fup, void *h, int64_t ldh,
+                                void *ws, size_t ws_bytes, void *stream);
+
+/*
  * First sub-layer of a non-GLU MLP (Table 2 lists GLU-based and non-GLU models; Sec. 4.1
  * "activation computation" after the upward projection):
  *   y = act((x U) V + bias),   bias: device, d_out values of the pair's dtype, may be NULL

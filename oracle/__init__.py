@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_down_projection.argtypes = [_dp, _i64, _i64, _dp, _i64, _i64, _i64, _dp, _i64]
         L.oracle_up_projection.restype = None
         L.oracle_up_projection.argtypes = [_dp, _i64, _i64, _dp, _i64, _i64, _i64, _dp, _i64]
+        L.oracle_up_glu_silu.restype = ctypes.c_int
+        L.oracle_up_glu_silu.argtypes = [_dp, _i64, _dp, _i64, _i64, _dp, _i64, _dp, _i64, _i64, _i64, _i64, _dp, _i64]
         L.oracle_relu.restype = ctypes.c_double
         L.oracle_relu.argtypes = [ctypes.c_double]
         L.oracle_gelu.restype = ctypes.c_double
@@ -143,6 +145,23 @@ def up_projection(t, V) -> np.ndarray:
     if T and d_out:
         lib().oracle_up_projection(_p(t), T, max(r, 1), _p(V), d_out, r, d_out, _p(y), d_out)
     return y
+
+
+def up_glu_silu(t_gate, V_gate, t_up, V_up) -> np.ndarray:
+    """h = silu(t_gate V_gate) * (t_up V_up): the second stage of the GLU sub-layer alone."""
+    tg, Vg, tu, Vu = _f64(t_gate), _f64(V_gate), _f64(t_up), _f64(V_up)
+    T, rg = tg.shape
+    ru = tu.shape[1]
+    d_ff = Vg.shape[1]
+    if Vg.shape[0] != rg or Vu.shape != (ru, d_ff) or tu.shape[0] != T:
+        raise ValueError("shape mismatch")
+    h = np.zeros((T, d_ff), dtype=np.float64)
+    if T and d_ff:
+        rc = lib().oracle_up_glu_silu(_p(tg), max(rg, 1), _p(Vg), d_ff, rg, _p(tu), max(ru, 1), _p(Vu), d_ff, ru,
+                                      T, d_ff, _p(h), d_ff)
+        if rc:
+            raise MemoryError("oracle_up_glu_silu")
+    return h
 
 
 def lowrank_linear(x, U, V, return_t: bool = False):

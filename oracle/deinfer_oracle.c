@@ -190,6 +190,28 @@ int oracle_lowrank_gateup_silu(const double *x, int64_t T, int64_t ldx, int64_t 
 }
 
 /* ------------------------------------------------------------------------
+ * Second stage of the GLU sub-layer alone (Sec. 4.1 under tensor parallelism: the rank-space
+ * results of gate and up are gathered from all ranks first, then every rank applies its column
+ * shard of the upward matrices):  h = silu(t_g V_g) * (t_u V_u).
+ * ---------------------------------------------------------------------- */
+int oracle_up_glu_silu(const double *tg, int64_t ldtg, const double *Vg, int64_t ldvg, int64_t rg,
+                       const double *tu, int64_t ldtu, const double *Vu, int64_t ldvu, int64_t ru,
+                       int64_t T, int64_t d_ff, double *h, int64_t ldh) {
+  if (T <= 0) return 0;
+  size_t n = (size_t)T * (size_t)(d_ff > 0 ? d_ff : 1);
+  double *g = (double *)malloc(sizeof(double) * n);
+  double *u = (double *)malloc(sizeof(double) * n);
+  if (!g || !u) { free(g); free(u); return -1; }
+  oracle_up_projection(tg, T, ldtg, Vg, ldvg, rg, d_ff, g, d_ff);
+  oracle_up_projection(tu, T, ldtu, Vu, ldvu, ru, d_ff, u, d_ff);
+  for (int64_t i = 0; i < T; ++i)
+    for (int64_t j = 0; j < d_ff; ++j)
+      h[i * ldh + j] = oracle_silu(g[i * d_ff + j]) * u[i * d_ff + j];
+  free(g); free(u);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------
  * Non-GLU MLP first sub-layer (Table 2 lists GLU-based and non-GLU models; Sec. 4.1
  * "activation computation" after the upward projection):
  *   y = act((x U) V + b),  b broadcast over the token rows (NULL = no bias),

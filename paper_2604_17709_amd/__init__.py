@@ -55,6 +55,7 @@ EXPORTS = [
     "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
     "deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
     "deinfer_lowrank_down", "deinfer_lowrank_up", "deinfer_lowrank_linear_act",
+    "deinfer_lowrank_down_proj", "deinfer_lowrank_up_glu_silu",
     "deinfer_kv_compact_plan", "deinfer_kv_compact_copy", "deinfer_rope_inplace",
 ]
 
@@ -89,6 +90,9 @@ def lib() -> ctypes.CDLL:
         L.deinfer_lowrank_linear.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_down.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_up.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
+        L.deinfer_lowrank_down_proj.argtypes = [_vp, _i64, _i64, ctypes.POINTER(FP), ctypes.c_int,
+                                                ctypes.POINTER(_vp), ctypes.POINTER(_i64), _vp, _sz, _vp]
+        L.deinfer_lowrank_up_glu_silu.argtypes = [_vp, _i64, _vp, _i64, _i64, FP, FP, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_linear_act.argtypes = [_vp, _i64, _i64, FP, _vp, ctypes.c_int, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_qkv.argtypes = [_vp, _i64, _i64, FP, FP, FP,
                                           _vp, _i64, _vp, _i64, _vp, _i64,
@@ -221,7 +225,10 @@ def deinfer_workspace_bytes(T: int, pairs: Sequence[Pair]) -> int:
 
 
 def _ld(t) -> int:
-    return int(t.stride(0)) if t.shape[0] > 1 else max(int(t.shape[1]), 1)
+    # a single row keeps the pitch of the tensor it was cut from (it decides alignment checks)
+    if t.shape[0] > 1 or int(t.stride(0)) >= int(t.shape[1]):
+        return max(int(t.stride(0)), 1)
+    return max(int(t.shape[1]), 1)
 
 
 def _rows(x, what: str):
@@ -250,6 +257,34 @@ def deinfer_lowrank_down(h, pair: Pair, ws: Workspace, out=None, stream=None):
         out = torch.empty((T, pair.d_out), dtype=h.dtype, device=h.device)
     _check(lib().deinfer_lowrank_down(_ptr(h), T, _ld(h), ctypes.byref(pair.desc),
                                       _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
+    return out
+
+
+def deinfer_lowrank_down_proj(x, pairs, ws: Workspace, t_out=None, stream=None):
+    """t_i = x U_i for 1 to 3 pairs that share x: the first stage alone.  Returns the list of t_i."""
+    import torch
+    T = _rows(x, "x")
+    n = len(pairs)
+    if t_out is None:       # pitch rounded up to 8 elements, zero padding: what deinfer_lowrank_up wants for packed pairs
+        t_out = [torch.zeros((T, max((p.r + 7) // 8 * 8, 8)), dtype=x.dtype, device=x.device)[:, :p.r] for p in pairs]
+    fa = (ctypes.POINTER(Factors) * n)(*[ctypes.pointer(p.desc) for p in pairs])
+    ta = (_vp * n)(*[_ptr(t) for t in t_out])
+    la = (_i64 * n)(*[_ld(t) for t in t_out])
+    _check(lib().deinfer_lowrank_down_proj(_ptr(x), T, _ld(x), fa, n, ta, la, _ptr(ws.buf), ws.nbytes, _stream(stream)))
+    return list(t_out)
+
+
+def deinfer_lowrank_up_glu_silu(t_gate, t_up, fgate: Pair, fup: Pair, ws: Workspace, out=None, stream=None):
+    """h = silu(t_gate V_gate) * (t_up V_up): the second stage of the GLU sub-layer alone."""
+    import torch
+    T = _rows(t_gate, "t_gate")
+    if _rows(t_up, "t_up") != T:
+        raise ValueError("t_gate and t_up must have the same number of rows")
+    if out is None:
+        out = torch.empty((T, fgate.d_out), dtype=t_gate.dtype, device=t_gate.device)
+    _check(lib().deinfer_lowrank_up_glu_silu(_ptr(t_gate), _ld(t_gate), _ptr(t_up), _ld(t_up), T,
+                                             ctypes.byref(fgate.desc), ctypes.byref(fup.desc),
+                                             _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
     return out
 
 

@@ -232,11 +232,13 @@ struct Group {
   bool glu;
   bool up_only;                            // x is the rank-space intermediate t: only the upward projection runs
   const void *bias; int act;               // single non-GLU pair only: y = act(product + bias), bias per output feature
+  bool down_only;                          // only the downward projections run; every pair hands out its t through t_out
+  const void *x2; int64_t ldx2;            // up_only GLU call: rank-space rows of the second (up) pair
   void *ws; size_t ws_bytes; hipStream_t stream;
 };
 
 template <int NT>
-int launch_decode_nt(const DecParams &P, bool glu, int grid2, hipStream_t s) {
+int launch_decode_nt(const DecParams &P, bool glu, int grid2, hipStream_t s, bool down_only) {
   {
     ProfScope ps(DEINFER_PROF_DECODE_DOWN, s);
     hipLaunchKernelGGL((decode_kernel<NT, false, 1>), dim3(P.G1), dim3(DEC_THREADS), 0, s, P);
@@ -251,6 +253,7 @@ int launch_decode_nt(const DecParams &P, bool glu, int grid2, hipStream_t s) {
     }
     if (int rc = check_launch("decode reduce kernel")) return rc;
   }
+  if (down_only) return DEINFER_OK;
   {
     ProfScope ps(DEINFER_PROF_DECODE_UP, s);
     if (glu) hipLaunchKernelGGL((decode_kernel<NT, true, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
@@ -324,10 +327,10 @@ int run_decode(const Group &gq, int64_t row0, int64_t T) {
   P.part_stride = (long long)nt * 16 * P.Rtot_pad;
   const int grid2 = P.n_items2;     // one work item per workgroup
   switch (nt) {
-    case 1: return launch_decode_nt<1>(P, gq.glu, grid2, gq.stream);
-    case 2: return launch_decode_nt<2>(P, gq.glu, grid2, gq.stream);
-    case 4: return launch_decode_nt<4>(P, gq.glu, grid2, gq.stream);
-    default: return launch_decode_nt<8>(P, gq.glu, grid2, gq.stream);
+    case 1: return launch_decode_nt<1>(P, gq.glu, grid2, gq.stream, gq.down_only);
+    case 2: return launch_decode_nt<2>(P, gq.glu, grid2, gq.stream, gq.down_only);
+    case 4: return launch_decode_nt<4>(P, gq.glu, grid2, gq.stream, gq.down_only);
+    default: return launch_decode_nt<8>(P, gq.glu, grid2, gq.stream, gq.down_only);
   }
 }
 
@@ -342,6 +345,15 @@ int run_generic(const Group &gq) {
   int64_t off[3] = {0, 0, 0};
   int64_t acc = 0;
   for (int i = 0; i < gq.n; ++i) { off[i] = acc; acc += gq.f[i]->r; }
+  if (gq.up_only && gq.glu) {
+    const deinfer_factors_t *fg = gq.f[0], *fu = gq.f[1];
+    dim3 grid((unsigned)ceil_div(fg->d_out, GT), (unsigned)ceil_div(T, GT));
+    hipLaunchKernelGGL((gemm_generic_kernel<TE, TE, TE, true>), grid, dim3(GTHREADS), 0, gq.stream,
+                       x, gq.ldx, static_cast<const TE *>(fg->V), fg->ldv, (int)fg->r,
+                       static_cast<const TE *>(gq.x2), gq.ldx2, static_cast<const TE *>(fu->V), fu->ldv, (int)fu->r,
+                       static_cast<TE *>(gq.out[0]), gq.ldo[0], (int)T, (int)fg->d_out);
+    return check_launch("generic GLU upward projection");
+  }
   if (gq.up_only) {
     // the caller's rank-space rows are the activation operand of the upward projection
     const deinfer_factors_t *f = gq.f[0];
@@ -368,6 +380,7 @@ int run_generic(const Group &gq) {
       if (int rc = check_launch("rank-space copy")) return rc;
     }
   }
+  if (gq.down_only) return DEINFER_OK;
   // stage 2: upward projections
   if (gq.glu) {
     const deinfer_factors_t *fg = gq.f[0], *fu = gq.f[1];
@@ -412,11 +425,19 @@ int run_group(Group gq) {
   if (!gq.x) return fail(DEINFER_ERR_INVALID_ARG, "activation pointer is NULL");
   if (gq.up_only) {
     if (gq.ldx < gq.f[0]->r) return fail(DEINFER_ERR_INVALID_ARG, "ldt smaller than r");
+    if (gq.glu) {
+      if (!gq.x2) return fail(DEINFER_ERR_INVALID_ARG, "rank-space pointer of the up pair is NULL");
+      if (gq.ldx2 < gq.f[1]->r) return fail(DEINFER_ERR_INVALID_ARG, "ldt of the up pair smaller than r");
+      if (!aligned(gq.x2, es)) return fail(DEINFER_ERR_MISALIGNED, "rank-space pointer of the up pair not aligned to the element size");
+    }
   } else if (gq.ldx < gq.f[0]->d_in) {
     return fail(DEINFER_ERR_INVALID_ARG, "ldx smaller than d_in");
   }
   if (!aligned(gq.x, es)) return fail(DEINFER_ERR_MISALIGNED, "activation pointer not aligned to the element size");
-  const int n_out = gq.glu ? 1 : gq.n;
+  const int n_out = gq.down_only ? 0 : gq.glu ? 1 : gq.n;
+  if (gq.down_only)
+    for (int i = 0; i < gq.n; ++i)
+      if (!gq.t_out[i] && gq.f[i]->r > 0) return fail(DEINFER_ERR_INVALID_ARG, "rank-space output %d is NULL", i);
   for (int i = 0; i < n_out; ++i) {
     if (!gq.out[i]) return fail(DEINFER_ERR_INVALID_ARG, "output pointer %d is NULL", i);
     if (gq.ldo[i] < gq.f[i]->d_out) return fail(DEINFER_ERR_INVALID_ARG, "output %d: leading dimension smaller than d_out", i);
@@ -434,7 +455,8 @@ int run_group(Group gq) {
     return fail(DEINFER_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", gq.ws_bytes, need);
   const bool packed = gq.f[0]->layout == DEINFER_LAYOUT_PACKED;
   if (packed && gq.up_only) {
-    if (!aligned(gq.x, 16) || gq.ldx % 8 != 0 || gq.ldx < round_up(gq.f[0]->r, 8))
+    if (!aligned(gq.x, 16) || gq.ldx % 8 != 0 || gq.ldx < round_up(gq.f[0]->r, 8) ||
+        (gq.glu && (!aligned(gq.x2, 16) || gq.ldx2 % 8 != 0 || gq.ldx2 < round_up(gq.f[1]->r, 8))))
       return fail(DEINFER_ERR_MISALIGNED,
                   "packed pairs need 16-byte aligned rank-space rows with ldt %% 8 == 0 and ldt >= r rounded up to 8");
   } else if (packed) {
@@ -467,7 +489,17 @@ int run_group(Group gq) {
   // ---- pairs of rank 0: the output is exactly zero (empty sum)
   bool any_zero = false;
   for (int i = 0; i < gq.n; ++i) any_zero |= (gq.f[i]->r == 0);
-  if (any_zero) {
+  if (any_zero && gq.down_only) {          // a pair of rank 0 has no rank-space columns: drop it
+    Group rest = gq;
+    rest.n = 0;
+    for (int i = 0; i < gq.n; ++i)
+      if (gq.f[i]->r != 0) {
+        rest.f[rest.n] = gq.f[i]; rest.t_out[rest.n] = gq.t_out[i]; rest.ldt[rest.n] = gq.ldt[i];
+        ++rest.n;
+      }
+    if (rest.n == 0) return DEINFER_OK;
+    gq = rest;
+  } else if (any_zero) {
     if (gq.glu) {   // silu(0) * u == 0 and silu(g) * 0 == 0
       return dtype == DEINFER_BF16 ? zero_output<uint16_t>(gq.out[0], gq.ldo[0], gq.T, gq.f[0]->d_out, gq.stream)
                                    : zero_output<float>(gq.out[0], gq.ldo[0], gq.T, gq.f[0]->d_out, gq.stream);
@@ -766,6 +798,33 @@ int deinfer_lowrank_linear_act(const void *x, int64_t T, int64_t ldx, const dein
   memset(&g, 0, sizeof(g));
   g.x = x; g.T = T; g.ldx = ldx; g.n = 1; g.f[0] = f; g.out[0] = y; g.ldo[0] = ldy;
   g.glu = false; g.bias = bias; g.act = act; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
+  return run_group(g);
+}
+
+int deinfer_lowrank_down_proj(const void *x, int64_t T, int64_t ldx, const deinfer_factors_t *const *f, int n_pairs,
+                              void *const *t_out, const int64_t *ldt, void *ws, size_t ws_bytes, void *stream) {
+  if (n_pairs < 1 || n_pairs > 3) return fail(DEINFER_ERR_INVALID_ARG, "1 to 3 pairs per call, got %d", n_pairs);
+  if (!f || !t_out || !ldt) return fail(DEINFER_ERR_INVALID_ARG, "pair, output or pitch array is NULL");
+  Group g;
+  memset(&g, 0, sizeof(g));
+  g.x = x; g.T = T; g.ldx = ldx; g.n = n_pairs;
+  for (int i = 0; i < n_pairs; ++i) {
+    if (!f[i]) return fail(DEINFER_ERR_INVALID_ARG, "factor descriptor %d is NULL", i);
+    g.f[i] = f[i]; g.t_out[i] = t_out[i]; g.ldt[i] = ldt[i];
+  }
+  g.down_only = true; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
+  return run_group(g);
+}
+
+int deinfer_lowrank_up_glu_silu(const void *t_gate, int64_t ldtg, const void *t_up, int64_t ldtu, int64_t T,
+                                const deinfer_factors_t *fgate, const deinfer_factors_t *fup,
+                                void *h, int64_t ldh, void *ws, size_t ws_bytes, void *stream) {
+  if (!fgate || !fup) return fail(DEINFER_ERR_INVALID_ARG, "factor descriptor is NULL");
+  Group g;
+  memset(&g, 0, sizeof(g));
+  g.x = t_gate; g.ldx = ldtg; g.x2 = t_up; g.ldx2 = ldtu; g.T = T; g.n = 2; g.f[0] = fgate; g.f[1] = fup;
+  g.out[0] = h; g.ldo[0] = ldh; g.glu = true; g.up_only = true;
+  g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
   return run_group(g);
 }
 

@@ -139,6 +139,27 @@ def test_linear_act_argument_validation():
     assert L.deinfer_lowrank_linear_act(None, 0, 64, ctypes.byref(f), None, 1, None, 48, None, 0, None) == dn.OK
 
 
+def test_staged_calls_argument_validation():
+    L = dn.lib()
+    f, g = make(), make(r=24)
+    FPA = ctypes.POINTER(dn.Factors) * 2
+    fa = FPA(ctypes.pointer(f), ctypes.pointer(g))
+    ta = (ctypes.c_void_p * 2)(FAKE + 0x300000, FAKE + 0x310000)
+    la = (ctypes.c_int64 * 2)(16, 24)
+    dp = lambda n=2, t=ta, l=la, ws=FAKE + 0x400000: L.deinfer_lowrank_down_proj(FAKE + 0x200000, 4, 64, fa, n, t, l, ws, 1 << 26, None)
+    assert dp(n=0) == dn.ERR_INVALID_ARG and dp(n=4) == dn.ERR_INVALID_ARG
+    assert dp(t=(ctypes.c_void_p * 2)(FAKE + 0x300000, None)) == dn.ERR_INVALID_ARG        # every pair hands out its t
+    assert dp(l=(ctypes.c_int64 * 2)(16, 20)) == dn.ERR_INVALID_ARG                         # ldt < r
+    assert dp(ws=None) == dn.ERR_WORKSPACE
+    assert L.deinfer_lowrank_down_proj(FAKE, 4, 64, None, 1, ta, la, FAKE, 1 << 20, None) == dn.ERR_INVALID_ARG
+    up = lambda tg=FAKE + 0x200000, tu=FAKE + 0x210000, ldu=24, gg=g: L.deinfer_lowrank_up_glu_silu(
+        tg, 16, tu, ldu, 4, ctypes.byref(f), ctypes.byref(gg), FAKE + 0x300000, 48, FAKE + 0x400000, 1 << 26, None)
+    assert up(tu=None) == dn.ERR_INVALID_ARG
+    assert up(ldu=20) == dn.ERR_INVALID_ARG
+    assert up(gg=make(r=24, d_out=40)) == dn.ERR_INVALID_ARG                                # gate and up widths differ
+    assert L.deinfer_lowrank_up_glu_silu(FAKE, 16, FAKE, 24, 4, None, ctypes.byref(g), FAKE, 48, FAKE, 1 << 20, None) == dn.ERR_INVALID_ARG
+
+
 def test_group_calls_validate_shared_properties():
     L = dn.lib()
     fq, fk, fv = make(), make(d_out=16, r=8), make(d_out=16, r=8)

@@ -394,3 +394,40 @@ def test_first_stage_split_over_k(dn, T):
     # the keys rebuilt from t_k equal the keys of the qkv call up to the output rounding
     k2 = dn.deinfer_lowrank_up(tk, F["k"], ws)
     assert max_err(to_host(k2), to_host(k)) <= 2.0 ** -7
+
+
+# ------------------------------------------------------------------ the two stages as separate calls
+@pytest.mark.parametrize("kind", ["f32", "raw", "packed"])
+@pytest.mark.parametrize("T", [1, 12, 24, 100, 300, 600])
+def test_stages_as_separate_calls(dn, kind, T):
+    """What one tensor-parallel rank runs: downward projections alone (rank-space results handed
+    out), then the upward projections on rank-space rows; together they reproduce the fused calls."""
+    import torch
+    dtype = "f32" if kind == "f32" else "bf16"
+    d_in = 1096 if kind == "packed" else 200
+    x = si.make(9, 1, (T, d_in), 1.0, dtype)
+    shapes = {"q": (70, 256), "k": (24, 64), "g": (100, 3300), "u": (90, 3300)}
+    F, host = {}, {}
+    for i, (n, (r, d_out)) in enumerate(shapes.items()):
+        U = si.make(9, 10 + 2 * i, (d_in, r), 1.0 / np.sqrt(d_in), dtype)
+        V = si.make(9, 11 + 2 * i, (r, d_out), 1.0 / np.sqrt(r), dtype)
+        F[n], _k = pair(dn, U, V, packed=(kind == "packed"))
+        host[n] = (U.values, V.values)
+    xd = to_dev(x)
+    ws = dn.Workspace(max(dn.deinfer_workspace_bytes(T, [F["q"], F["k"]]), dn.deinfer_workspace_bytes(T, [F["g"], F["u"]])))
+    tq, tk = dn.deinfer_lowrank_down_proj(xd, [F["q"], F["k"]], ws)
+    tg, tu = dn.deinfer_lowrank_down_proj(xd, [F["g"], F["u"]], ws)
+    for got, n in ((tq, "q"), (tk, "k"), (tg, "g"), (tu, "u")):
+        assert max_err(to_host(got), oracle.down_projection(x.values, host[n][0])) <= TOL[dtype]
+    q = dn.deinfer_lowrank_up(tq, F["q"], ws)
+    h = dn.deinfer_lowrank_up_glu_silu(tg, tu, F["g"], F["u"], ws)
+    ws.check()
+    # against the oracle fed the same rank-space rows, and end to end
+    assert max_err(to_host(q), oracle.up_projection(to_host(tq), host["q"][1])) <= TOL[dtype]
+    assert max_err(to_host(h), oracle.up_glu_silu(to_host(tg), host["g"][1], to_host(tu), host["u"][1])) <= TOL[dtype]
+    assert max_err(to_host(q), oracle.lowrank_linear(x.values, *host["q"])) <= TOL[dtype]
+    assert max_err(to_host(h), oracle.lowrank_gateup_silu(x.values, *host["g"], *host["u"])) <= TOL[dtype]
+    if kind == "packed":
+        # the staged GLU call sees bf16 rank-space rows, as the fused call does inside
+        h_fused = dn.deinfer_lowrank_gateup_silu(xd, F["g"], F["u"], ws)
+        assert max_err(to_host(h), to_host(h_fused)) <= 2.0 ** -6

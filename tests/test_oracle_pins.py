@@ -310,3 +310,15 @@ def test_linear_act_against_numpy_and_special_cases():
     assert rel_err(r1, 3.0 * oracle.lowrank_linear_act(x, U, V, b, oracle.ACT_RELU)) < 1e-13
     with pytest.raises(RuntimeError):
         oracle.lowrank_linear_act(x, U, V, b, 7)
+
+
+def test_stage_two_of_the_glu_layer_alone():
+    import scipy.special
+    x, Ug, Vg, Uu, Vu = rnd(6, 17), rnd(17, 5), rnd(5, 11), rnd(17, 3), rnd(3, 11)
+    tg, tu = x @ Ug, x @ Uu
+    h = oracle.up_glu_silu(tg, Vg, tu, Vu)
+    assert rel_err(h, oracle.lowrank_gateup_silu(x, Ug, Vg, Uu, Vu)) < 1e-13      # same thing, staged
+    g, u = tg @ Vg, tu @ Vu
+    assert rel_err(h, g * scipy.special.expit(g) * u) < 1e-13                      # silu(z) = z * logistic(z)
+    # gate and up are not interchangeable
+    assert rel_err(oracle.up_glu_silu(tu, Vu, tg, Vg), h) > 1e-3
