@@ -45,6 +45,9 @@ WORKLOADS = {
     # keys and values of cached tokens rebuilt from the paged low-rank cache (a different step, see kv_rebuild)
     "llama7b_keep80_kv_rebuild": ("llama7b_keep80", 8192, "mfma"),
     # non-GLU block: the MLP is act(x U1 V1 + b1) then a second pair with bias (deinfer_lowrank_linear_act)
+    # what ONE rank of an 8-way tensor-parallel group runs on its shard (no exchange is timed)
+    "llama70b_keep40_tp8_rank_decode": ("llama70b_keep40", 128, "hbm"),
+    "llama70b_keep40_tp8_rank_prefill": ("llama70b_keep40", 4096, "mfma"),
     "opt30b_keep60_decode": ("opt30b_keep60", 64, "hbm"),
     "opt30b_keep60_prefill": ("opt30b_keep60", 4096, "mfma"),
 }
@@ -92,6 +95,8 @@ def main():
     T = args.T or T_default
     if args.workload.endswith("kv_rebuild"):
         return kv_rebuild(args, L, si.BLOCKS[block_name], T)
+    if "_tp8_rank_" in args.workload:
+        return tp_rank(args, L, si.BLOCKS[block_name], T, 8, bound if T > 128 else "hbm")
     if T <= 128:
         bound = "hbm"
     shape = si.BLOCKS[block_name]
@@ -455,6 +460,191 @@ def main():
                                "kind": "oracle",
                                "sample": "%d of %d token rows of the same block, %d passes, fp64 loops, %.1f s in total"
                                          % (rows, T, passes, cpu_s)}
+    print(json.dumps(out))
+
+
+def tp_rank(args, L, shape, T, P, bound):
+    """Step = the calls of ONE rank of a P-way tensor-parallel group for one block (Sec. 4.1): first
+    sub-layers: downward projections with the rank's column slice of U, [all-gather, not run],
+    upward projections with its column shard of V; second sub-layers: downward projection with
+    its row slice of U, [reduce-sum, not run], the replicated upward projection.  The gathered /
+    summed rank-space rows are stand-in tensors of the right shape."""
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    import paper_2604_17709_amd as dn
+    bf = torch.bfloat16
+    proj = shape.projections()
+    rho = 1.0 - shape.keep_num / shape.keep_den
+    ranks = {p: dn.deinfer_rank_for_ratio(m, n, rho) for p, (m, n) in proj.items()}
+    cdiv = lambda a, b: (a + b - 1) // b
+    g = torch.Generator(device="cuda"); g.manual_seed(args.seed)
+    rnd = lambda *sh, std=0.02: (torch.randn(sh, generator=g, device="cuda") * std).to(bf)
+    t0 = time.time()
+
+    def pair_u(d_in, r):          # a pair used for its downward matrix only
+        return dn.deinfer_pack_factors(dn.raw_pair(rnd(d_in, r), rnd(r, 16), rho))
+
+    def pair_v(r, d_out):         # a pair used for its upward matrix only
+        return dn.deinfer_pack_factors(dn.raw_pair(rnd(16, r), rnd(r, d_out), rho))
+
+    H, Fd = shape.hidden, shape.ffn
+    n_copies = 8                  # rotate the weights so that the 256 MB cache does not serve them
+    sets = []
+    for _ in range(n_copies):
+        sets.append({
+            "qkv_d": [pair_u(H, cdiv(ranks[n], P)) for n in ("q", "k", "v")],
+            "qkv_u": [pair_v(ranks[n], proj[n][1] // P) for n in ("q", "k", "v")],
+            "o_d": pair_u(H // P, ranks["o"]), "o_u": pair_v(ranks["o"], H),
+            "gu_d": [pair_u(H, cdiv(ranks[n], P)) for n in ("gate", "up")],
+            "gu_u": [pair_v(ranks[n], Fd // P) for n in ("gate", "up")],
+            "dn_d": pair_u(Fd // P, ranks["down"]), "dn_u": pair_v(ranks["down"], H)})
+    w_bytes = 0
+    s0 = sets[0]
+    for k, v in s0.items():
+        for p_ in (v if isinstance(v, list) else [v]):
+            w_bytes += 2 * (p_.r * p_.d_in if k.endswith("_d") else p_.r * p_.d_out)
+    pad8 = lambda r: (r + 7) // 8 * 8
+    x = rnd(T, H, std=1.0); a_sh = rnd(T, H // P, std=1.0); h_sh = rnd(T, Fd // P, std=1.0)
+    tg = {n: torch.zeros((T, pad8(ranks[n])), dtype=bf, device="cuda") for n in ranks}     # gathered / summed rank-space rows
+    for n in tg:
+        tg[n][:, :ranks[n]] = rnd(T, ranks[n], std=0.3)
+    ts = {n: torch.zeros((T, pad8(cdiv(ranks[n], P))), dtype=bf, device="cuda") for n in ("q", "k", "v", "gate", "up")}
+    tpart = {n: torch.zeros((T, pad8(ranks[n])), dtype=bf, device="cuda") for n in ("o", "down")}
+    outs = {n: torch.empty((T, proj[n][1] // P), dtype=bf, device="cuda") for n in ("q", "k", "v")}
+    outs["o"] = torch.empty((T, H), dtype=bf, device="cuda"); outs["down"] = torch.empty((T, H), dtype=bf, device="cuda")
+    outs["h"] = torch.empty((T, Fd // P), dtype=bf, device="cuda")
+    need = 0
+    for v in s0.values():
+        need = max(need, dn.deinfer_workspace_bytes(T, v if isinstance(v, list) else [v]))
+    ws = dn.Workspace(need)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+    stream = torch.cuda.Stream(); sh = int(stream.cuda_stream)
+    B = ctypes.byref
+    wsp, wsn = ws.buf.data_ptr(), ws.nbytes
+    FP = ctypes.POINTER(dn.Factors)
+
+    def down_proj(xin, pairs, touts):
+        n = len(pairs)
+        fa = (FP * n)(*[ctypes.pointer(p_.desc) for p_ in pairs])
+        ta = (ctypes.c_void_p * n)(*[t.data_ptr() for t in touts])
+        la = (ctypes.c_int64 * n)(*[t.stride(0) for t in touts])
+        return (L.deinfer_lowrank_down_proj, (xin.data_ptr(), T, xin.stride(0), fa, n, ta, la, wsp, wsn, sh))
+
+    def up(tin, p_, out):
+        return (L.deinfer_lowrank_up, (tin.data_ptr(), T, tin.stride(0), B(p_.desc), out.data_ptr(), out.stride(0), wsp, wsn, sh))
+
+    def calls_of(c):
+        return {
+            "qkv_down": [down_proj(x, c["qkv_d"], [ts["q"], ts["k"], ts["v"]])],
+            "qkv_up": [up(tg[n], c["qkv_u"][i], outs[n]) for i, n in enumerate(("q", "k", "v"))],
+            "o_down": [down_proj(a_sh, [c["o_d"]], [tpart["o"]])],
+            "o_up": [up(tg["o"], c["o_u"], outs["o"])],
+            "gateup_down": [down_proj(x, c["gu_d"], [ts["gate"], ts["up"]])],
+            "gateup_up": [(L.deinfer_lowrank_up_glu_silu, (tg["gate"].data_ptr(), tg["gate"].stride(0), tg["up"].data_ptr(),
+                                                           tg["up"].stride(0), T, B(c["gu_u"][0].desc), B(c["gu_u"][1].desc),
+                                                           outs["h"].data_ptr(), outs["h"].stride(0), wsp, wsn, sh))],
+            "down_down": [down_proj(h_sh, [c["dn_d"]], [tpart["down"]])],
+            "down_up": [up(tg["down"], c["dn_u"], outs["down"])],
+        }
+    calls = [calls_of(c) for c in sets]
+    order = list(calls[0].keys())
+
+    def run(i, names=None):
+        for n in (names or order):
+            for fn, a_ in calls[i % n_copies][n]:
+                if fn(*a_) != 0:
+                    raise RuntimeError("%s failed: %s" % (n, dn.last_error()))
+
+    with torch.cuda.stream(stream):
+        run(0)
+    stream.synchronize(); ws.check(stream)
+    graphs = []
+    for i in range(n_copies):
+        gph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gph, stream=stream):
+            run(i)
+        graphs.append(gph)
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            graphs[i % n_copies].replay()
+    stream.synchronize(); torch.cuda.synchronize()
+    t_a = time.perf_counter()
+    with torch.cuda.stream(stream):
+        for i in range(args.steps):
+            graphs[i % n_copies].replay()
+    stream.synchronize(); torch.cuda.synchronize()
+    sec = (time.perf_counter() - t_a) / args.steps
+
+    def ev(names, n):
+        a0 = torch.cuda.Event(enable_timing=True); a1 = torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            for i in range(5): run(i, names)
+            a0.record(stream)
+            for i in range(n): run(i, names)
+            a1.record(stream)
+        stream.synchronize()
+        return a0.elapsed_time(a1) * 1e-3 / n
+    per_call = {n: round(ev((n,), 50) * 1e6, 2) for n in order}
+    # dominant launch: the replicated upward projection of the MLP's second layer
+    decode = T <= 128
+    kind = dn.PROF_DECODE_UP if decode else dn.PROF_PREFILL_UP
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(stream):
+        e0.record(stream); e1.record(stream)
+    stream.synchronize()
+    L.deinfer_set_profile_events(kind, e0.cuda_event, e1.cuda_event)
+    tot = 0.0
+    for i in range(23):
+        with torch.cuda.stream(stream):
+            run(i, ("down_up",))
+        stream.synchronize()
+        if i >= 3: tot += e0.elapsed_time(e1)
+    L.deinfer_set_profile_events(0, None, None)
+    ksec = tot * 1e-3 / 20
+    kb = 2 * (ranks["down"] * H + T * ranks["down"] + T * H)
+    kf = 2.0 * T * ranks["down"] * H
+    step_bytes = w_bytes + 2 * T * (2 * H + H // P + Fd // P) + 2 * T * (sum(proj[n][1] // P for n in ("q", "k", "v")) + 2 * H + Fd // P)
+    step_flops = 2.0 * T * w_bytes / 2
+    if bound == "hbm":
+        ach = kb / ksec / 1e9
+        roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4)}
+    else:
+        ach = kf / ksec / 1e12
+        roof = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4)}
+    roof.update({"traffic": None, "kernel": "%s kernel (deinfer_lowrank_up of the replicated V_down)" % ("skinny_kernel" if decode else "prefill_kernel"),
+                 "avg_launch_us": round(ksec * 1e6, 2), "algorithmic_bytes_per_launch": kb, "algorithmic_flops_per_launch": kf})
+    out = {
+        "metric": "decomposed-layer tokens/sec; % HBM roofline (decode) / % MFMA peak (prefill)",
+        "value": round(T / sec, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s T=%d (one rank of %d: its shard of qkv, o, gate/up, down as downward-projection and "
+                               "upward-projection calls; the exchanges between them are not run)" % (args.workload, T, P),
+                   "ranks_full": ranks, "weight_MB_per_rank": round(w_bytes / 1e6, 1), "weight_copies": n_copies, "launch": "graph"},
+        "step_GBs": round(step_bytes / sec / 1e9, 1), "step_TFLOPs": round(step_flops / sec / 1e12, 2),
+        "step_frac_of_roofline": round((step_bytes / sec / 1e9 / HBM_PEAK_GBS) if bound == "hbm"
+                                       else (step_flops / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS), 4),
+        "calls_us": per_call, "roofline": roof, "setup_s": round(setup_s, 1),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = min(T, 64)
+        f64 = lambda t: t[:rows].to(torch.float32).cpu().numpy().astype(np.float64)
+        Vd = np.random.default_rng(args.seed).standard_normal((ranks["down"], H)) * 0.02
+        Ud = np.random.default_rng(args.seed + 1).standard_normal((Fd // P, ranks["down"])) * 0.02
+        hs, td = f64(h_sh), f64(tg["down"])[:, :ranks["down"]]
+        passes, cpu_s = 0, 0.0
+        while cpu_s < 10.0 and passes < 50:
+            t_a = time.perf_counter()
+            oracle.down_projection(hs, Ud); oracle.up_projection(td, Vd)
+            cpu_s += time.perf_counter() - t_a
+            passes += 1
+        out["cpu_baseline"] = {"value": round(rows * passes / cpu_s, 2), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "%d of %d token rows, the two calls of the MLP's second layer only (%.0f %% of the rank's weights), "
+                                         "%d passes, %.1f s in total" % (rows, T, 100.0 * 2 * ranks["down"] * (Fd // P + H) / w_bytes, passes, cpu_s)}
     print(json.dumps(out))
 
 
