@@ -119,14 +119,14 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
 
   auto fetch_x = [&](int st, int buf) {
     const unsigned kbyte0 = (unsigned)(kb_begin + st * SK_KB) * 64u;
-    const bool live = st < n_stages;                    // uniform
+    const unsigned dead = st < n_stages ? 0u : OOB;     // uniform; OR-ed in: no branch around the loads
 #pragma unroll
     for (int i = 0; i < NX; ++i) {
       // chunks beyond K re-read valid columns (k clamped to K - 8), which meet zero weights
       unsigned kb = kbyte0 + xchunk[i];
       kb = kb < xklim ? kb : xklim;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[buf][(i * 4 + wave) * 4 * SK_XROW], 16,
-                                               live ? xrow[i] + kb : OOB, 0, 0, 0);
+                                               (xrow[i] + kb) | dead, 0, 0, 0);
     }
   };
   auto fetch_w = [&](u32x4_t (&w)[SK_KB * 2], int st) {
@@ -147,18 +147,55 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
     for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
 
   const int b_row = lane & 31;
-  auto compute = [&](const u32x4_t (&w)[SK_KB * 2], int buf) {
+  // A stage is 8 steps (k-block, half) of NB products.  The token operands are read from LDS
+  // DEPTH steps ahead of their use into rotating registers, one read after each product (left to
+  // itself the compiler reads and waits right before every pair of products, which leaves the
+  // matrix pipeline idle two thirds of the time at T = 128).
+  constexpr int STEPS = SK_KB * 2;
+  constexpr int DEPTH = NB >= 4 ? 2 : NB == 2 ? 3 : 6;
+  auto read_b = [&](int buf, int step, int j) -> u32x4_t {
+    const int slot = (step * 2 + (lane >> 5)) ^ (lane & 15);       // step = 2 * k-block + half: 16-byte slot 2 * step + lane / 32
+    return *reinterpret_cast<const u32x4_t *>(&xs[buf][(32 * j + b_row) * SK_XROW + slot * 16]);
+  };
+  // One load of stage `fst` (index 0 .. 7: weights into wn, 8 .. 8 + NX - 1: activation slab rows into slab fbuf).
+  auto fetch_one = [&](u32x4_t (&wn)[SK_KB * 2], int fst, int fbuf, int idx) {
+    if (idx < SK_KB * 2) {
+      const int kb = kb_begin + fst * SK_KB + (idx >> 1);
+      const unsigned off = (wtile_ok && kb < kb_end) ? wlane : OOB;
+      wn[idx] = __builtin_amdgcn_raw_buffer_load_b128(wres, off, kb * 1024 + (idx & 1) * 512, 2);
+    } else {
+      const int i = idx - SK_KB * 2;
+      const unsigned dead = fst < n_stages ? 0u : OOB;
+      unsigned kb = (unsigned)(kb_begin + fst * SK_KB) * 64u + xchunk[i];
+      kb = kb < xklim ? kb : xklim;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[fbuf][(i * 4 + wave) * 4 * SK_XROW], 16,
+                                               (xrow[i] + kb) | dead, 0, 0, 0);
+    }
+  };
+  // The products of the stage in slab `buf`; the loads of stage `fst` are issued along the way,
+  // spread evenly behind the products (all of them in front would hold the first product up
+  // for their issue time).
+  auto compute = [&](const u32x4_t (&w)[SK_KB * 2], int buf, u32x4_t (&wn)[SK_KB * 2], int fst, int fbuf) {
+    constexpr int NLOAD = SK_KB * 2 + NX, NPOS = STEPS * NB;
+    u32x4_t b[DEPTH + 1][NB];
 #pragma unroll
-    for (int kbi = 0; kbi < SK_KB; ++kbi)
+    for (int d = 0; d < DEPTH; ++d)
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const int slot = (kbi * 4 + 2 * ks + (lane >> 5)) ^ (lane & 15);
+      for (int j = 0; j < NB; ++j) b[d][j] = read_b(buf, d, j);
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-          const u32x4_t b = *reinterpret_cast<const u32x4_t *>(&xs[buf][(32 * j + b_row) * SK_XROW + slot * 16]);
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(w[kbi * 2 + ks]), as_bf16x8(b), acc[j], 0, 0, 0);
-        }
+    for (int step = 0; step < STEPS; ++step) {
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        __builtin_amdgcn_sched_barrier(0);
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(w[step]), as_bf16x8(b[step % (DEPTH + 1)][j]), acc[j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (step + DEPTH < STEPS) b[(step + DEPTH) % (DEPTH + 1)][j] = read_b(buf, step + DEPTH, j);
+        const int pos = step * NB + j;
+#pragma unroll
+        for (int idx = pos * NLOAD / NPOS; idx < (pos + 1) * NLOAD / NPOS; ++idx) fetch_one(wn, fst, fbuf, idx);
       }
+    }
+    __builtin_amdgcn_sched_barrier(0);
   };
 
   // Stage s uses register set / slab s % 4.  Every stage issues exactly 8 + NX loads (those past
@@ -177,9 +214,7 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
 #ifdef DEINFER_SK_TRACE
       if (st == 0) tr_first = wall_clock64();
 #endif
-      fetch_w(wn, st + SK_SLABS - 1);
-      fetch_x(st + SK_SLABS - 1, slab == 0 ? SK_SLABS - 1 : slab - 1);
-      compute(w, slab);
+      compute(w, slab, wn, st + SK_SLABS - 1, slab == 0 ? SK_SLABS - 1 : slab - 1);
     };
     for (int st = 0; st < n_stages; st += 4) {
       stage(w0, w3, st, 0);
