@@ -293,12 +293,14 @@ def main():
     kflops = {"down": 2.0 * T * sum(ranks[p] * proj[p][0] for p in ps),
               "up": 2.0 * T * sum(ranks[p] * proj[p][1] for p in ps), "reduce": 0.0}
     if not decode:
-        # the compute-bound path launches one up-projection kernel per factor pair; the library's
-        # profiling events end up around the last of them (for the GLU call: the up product, whose
-        # epilogue also reads the gate values back and writes h)
-        pl = ps[-1]
-        kflops["up"] = 2.0 * T * ranks[pl] * proj[pl][1]
-        kbytes["up"] = s * ranks[pl] * proj[pl][1] + s * T * ranks[pl] + s * T * proj[pl][1] * (2 if dom == "gateup" else 1)
+        # the GLU call launches the gate product and then the up product, whose epilogue also reads
+        # the gate values back and writes h: the library's profiling events end up around the second
+        if dom == "gateup" and shape.glu:
+            pl = ps[-1]
+            kflops["up"] = 2.0 * T * ranks[pl] * proj[pl][1]
+            kbytes["up"] = s * ranks[pl] * proj[pl][1] + s * T * ranks[pl] + s * T * proj[pl][1] * 2
+        else:       # the upward projections of all pairs of the call are one launch
+            kbytes["up"] = w_out + s * T * sum(ranks[p] for p in ps) + s * T * sum(outs)
     entry = {"qkv": "qkv", "o": "linear", "gateup": "gateup_silu" if shape.glu else "linear_act",
              "down": "down" if shape.glu else "linear_act"}[dom]
     traffic = None
@@ -317,7 +319,7 @@ def main():
                     "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
     roofline["kernel"] = ("%s kernel (%s%s-projection launch of deinfer_lowrank_%s)"
                           % (("decode_kernel" if T <= 16 else "skinny_kernel") if decode else "prefill_kernel",
-                             "last " if (not decode and kdom == "up" and len(ps) > 1) else "", kdom, entry))
+                             "last " if (not decode and kdom == "up" and dom == "gateup" and shape.glu) else "", kdom, entry))
     roofline["avg_launch_us"] = round(ksec * 1e6, 2)
     roofline["algorithmic_bytes_per_launch"] = kbytes[kdom]
     roofline["algorithmic_flops_per_launch"] = kflops[kdom]

@@ -72,7 +72,12 @@ struct PfProblem {         // one product  act[T x K] . W^T
 struct PfParams {
   int T;
   int n_tblocks;           // ceil(T / 256)
-  PfProblem prob;
+  // Up to three independent products in one launch (the upward projections of a q/k/v call: a
+  // narrow one alone would leave most of the device idle); product i owns the feature blocks
+  // [fb0[i], fb0[i + 1]) of the grid.
+  int n_prob;
+  int fb0[3];
+  PfProblem prob[3];
   // SPLIT kernels only (few tiles, long k: the k range is cut into parts, one workgroup per part)
   int n_fblocks;           // feature blocks of 256; grid = n_tblocks * n_fblocks * n_parts
   int kb_per_part;         // k-blocks per part
@@ -107,7 +112,11 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   // streams those weights once
   const int tb = blockIdx.x % P.n_tblocks;
   const int fb_all = blockIdx.x / P.n_tblocks;
-  const int fb = SPLIT ? fb_all % P.n_fblocks : fb_all;
+  int fb = SPLIT ? fb_all % P.n_fblocks : fb_all;
+  int pi = 0;                                                   // which product (uniform)
+  if (!SPLIT && P.n_prob > 1 && fb >= P.fb0[1]) pi = 1;
+  if (!SPLIT && P.n_prob > 2 && fb >= P.fb0[2]) pi = 2;
+  fb -= P.fb0[pi];
   const int kpart = SPLIT ? fb_all / P.n_fblocks : 0;
   const int kb0 = SPLIT ? kpart * P.kb_per_part : 0;          // first k-block of this workgroup
   const int tok0 = tb * PF_BT;
@@ -126,7 +135,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const PfProblem &Q = P.prob;
+  const PfProblem &Q = P.prob[pi];
   {
     // ---- load assignment (every instruction moves 1 KiB: lane l -> LDS base + 16 l).
     // Buffer addressing: a scalar resource descriptor, a scalar byte offset for the k position
