@@ -40,10 +40,9 @@ namespace deinfer {
 #endif
 
 constexpr int SK_THREADS = 256;
-constexpr int SK_KB = 4;                   // k-blocks per stage
+constexpr int SK_KB = 4;                   // k-blocks per stage at most (k-ranges are multiples of it)
 constexpr int SK_FEAT = 128;               // features per workgroup
 constexpr int SK_MAX_PARTS = 8;            // k-ranges per product at most
-constexpr int SK_XROW = SK_KB * 64;        // bytes per token row of a stage's activation slab
 constexpr int SK_SLABS = 4;                // activation slabs in LDS = weight register sets
 
 struct SkProblem {           // one product  act[T x K] . W^T,  W packed as [tiles][KB][64] fragments
@@ -70,11 +69,15 @@ struct SkParams {
 #endif
 };
 
-// NB = 32-token blocks (1, 2 or 4)
-template <int NB>
-__global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(const SkParams P) {
+// NB = 32-token blocks (1, 2 or 4); KBS = k-blocks per stage (4, or 2: half the slab, so that two
+// workgroups fit a compute unit also with 128 tokens)
+template <int NB, int KBS>
+__global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
-  __shared__ __attribute__((aligned(16))) unsigned char xs[SK_SLABS][NB * 32 * SK_XROW];
+  constexpr int XROW = KBS * 64;          // bytes per token row of a stage's activation slab
+  constexpr int SPR = KBS * 4;            // 16-byte slots per row = lanes per row of a slab load
+  constexpr int RPI = 64 / SPR;           // rows per slab load instruction
+  __shared__ __attribute__((aligned(16))) unsigned char xs[SK_SLABS][NB * 32 * XROW];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 #ifdef DEINFER_SK_TRACE
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
   const int kb_begin = part * Q.kb_per_part;
   int kb_end = kb_begin + Q.kb_per_part;
   kb_end = kb_end < Q.KB ? kb_end : Q.KB;
-  const int n_stages = kb_end > kb_begin ? (kb_end - kb_begin + SK_KB - 1) / SK_KB : 0;
+  const int n_stages = kb_end > kb_begin ? (kb_end - kb_begin + KBS - 1) / KBS : 0;
 
   // ---- weights: buffer addressing; a lane offset beyond the descriptor's size reads zeros, which
   // is how feature tiles past the last one and k-blocks past the range contribute nothing
@@ -106,33 +109,33 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
   // ---- activations
   const unsigned xbytes = (unsigned)(((long long)(P.T - 1) * Q.lda + Q.K) * 2);
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void *)Q.act, 0, (int)xbytes, 0x00020000);
-  constexpr int NX = NB * 2;                            // slab load instructions per wavefront and stage
+  constexpr int NX = NB * 32 / (4 * RPI);               // slab load instructions per wavefront and stage
   unsigned xrow[NX], xchunk[NX];
 #pragma unroll
   for (int i = 0; i < NX; ++i) {
-    const int m = i * 4 + wave;                         // instruction m covers rows 4 m .. 4 m + 3
-    const int row = 4 * m + (lane >> 4);
+    const int m = i * 4 + wave;                         // instruction m covers rows RPI m .. RPI m + RPI - 1
+    const int row = RPI * m + lane / SPR;
     xrow[i] = row < P.T ? (unsigned)row * (unsigned)(Q.lda * 2) : OOB;
-    xchunk[i] = (unsigned)(((lane & 15) ^ (row & 15)) * 16);
+    xchunk[i] = (unsigned)(((lane & (SPR - 1)) ^ (row & (SPR - 1))) * 16);
   }
   const unsigned xklim = (unsigned)(Q.K * 2 - 16);
 
   auto fetch_x = [&](int st, int buf) {
-    const unsigned kbyte0 = (unsigned)(kb_begin + st * SK_KB) * 64u;
+    const unsigned kbyte0 = (unsigned)(kb_begin + st * KBS) * 64u;
     const unsigned dead = st < n_stages ? 0u : OOB;     // uniform; OR-ed in: no branch around the loads
 #pragma unroll
     for (int i = 0; i < NX; ++i) {
       // chunks beyond K re-read valid columns (k clamped to K - 8), which meet zero weights
       unsigned kb = kbyte0 + xchunk[i];
       kb = kb < xklim ? kb : xklim;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[buf][(i * 4 + wave) * 4 * SK_XROW], 16,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[buf][(i * 4 + wave) * RPI * XROW], 16,
                                                (xrow[i] + kb) | dead, 0, 0, 0);
     }
   };
-  auto fetch_w = [&](u32x4_t (&w)[SK_KB * 2], int st) {
+  auto fetch_w = [&](u32x4_t (&w)[KBS * 2], int st) {
 #pragma unroll
-    for (int kbi = 0; kbi < SK_KB; ++kbi) {
-      const int kb = kb_begin + st * SK_KB + kbi;
+    for (int kbi = 0; kbi < KBS; ++kbi) {
+      const int kb = kb_begin + st * KBS + kbi;
       const unsigned off = (wtile_ok && kb < kb_end) ? wlane : OOB;
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
@@ -151,32 +154,32 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
   // DEPTH steps ahead of their use into rotating registers, one read after each product (left to
   // itself the compiler reads and waits right before every pair of products, which leaves the
   // matrix pipeline idle two thirds of the time at T = 128).
-  constexpr int STEPS = SK_KB * 2;
+  constexpr int STEPS = KBS * 2;
   constexpr int DEPTH = NB >= 4 ? 2 : NB == 2 ? 3 : 6;
   auto read_b = [&](int buf, int step, int j) -> u32x4_t {
-    const int slot = (step * 2 + (lane >> 5)) ^ (lane & 15);       // step = 2 * k-block + half: 16-byte slot 2 * step + lane / 32
-    return *reinterpret_cast<const u32x4_t *>(&xs[buf][(32 * j + b_row) * SK_XROW + slot * 16]);
+    const int slot = (step * 2 + (lane >> 5)) ^ (lane & (SPR - 1));       // step = 2 * k-block + half: 16-byte slot 2 * step + lane / 32
+    return *reinterpret_cast<const u32x4_t *>(&xs[buf][(32 * j + b_row) * XROW + slot * 16]);
   };
   // One load of stage `fst` (index 0 .. 7: weights into wn, 8 .. 8 + NX - 1: activation slab rows into slab fbuf).
-  auto fetch_one = [&](u32x4_t (&wn)[SK_KB * 2], int fst, int fbuf, int idx) {
-    if (idx < SK_KB * 2) {
-      const int kb = kb_begin + fst * SK_KB + (idx >> 1);
+  auto fetch_one = [&](u32x4_t (&wn)[KBS * 2], int fst, int fbuf, int idx) {
+    if (idx < KBS * 2) {
+      const int kb = kb_begin + fst * KBS + (idx >> 1);
       const unsigned off = (wtile_ok && kb < kb_end) ? wlane : OOB;
       wn[idx] = __builtin_amdgcn_raw_buffer_load_b128(wres, off, kb * 1024 + (idx & 1) * 512, 2);
     } else {
-      const int i = idx - SK_KB * 2;
+      const int i = idx - KBS * 2;
       const unsigned dead = fst < n_stages ? 0u : OOB;
-      unsigned kb = (unsigned)(kb_begin + fst * SK_KB) * 64u + xchunk[i];
+      unsigned kb = (unsigned)(kb_begin + fst * KBS) * 64u + xchunk[i];
       kb = kb < xklim ? kb : xklim;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[fbuf][(i * 4 + wave) * 4 * SK_XROW], 16,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[fbuf][(i * 4 + wave) * RPI * XROW], 16,
                                                (xrow[i] + kb) | dead, 0, 0, 0);
     }
   };
   // The products of the stage in slab `buf`; the loads of stage `fst` are issued along the way,
   // spread evenly behind the products (all of them in front would hold the first product up
   // for their issue time).
-  auto compute = [&](const u32x4_t (&w)[SK_KB * 2], int buf, u32x4_t (&wn)[SK_KB * 2], int fst, int fbuf) {
-    constexpr int NLOAD = SK_KB * 2 + NX, NPOS = STEPS * NB;
+  auto compute = [&](const u32x4_t (&w)[KBS * 2], int buf, u32x4_t (&wn)[KBS * 2], int fst, int fbuf) {
+    constexpr int NLOAD = KBS * 2 + NX, NPOS = STEPS * NB;
     u32x4_t b[DEPTH + 1][NB];
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
@@ -202,13 +205,13 @@ __global__ __launch_bounds__(SK_THREADS, NB <= 2 ? 2 : 1) void skinny_kernel(con
   // the k-range read zeros through an out-of-range offset and cost no traffic), so "all but the
   // loads of the next stage have arrived" is one constant wait.
   if (n_stages > 0) {
-    u32x4_t w0[SK_KB * 2], w1[SK_KB * 2], w2[SK_KB * 2], w3[SK_KB * 2];
+    u32x4_t w0[KBS * 2], w1[KBS * 2], w2[KBS * 2], w3[KBS * 2];
     fetch_w(w0, 0); fetch_x(0, 0);
     fetch_w(w1, 1); fetch_x(1, 1);
     fetch_w(w2, 2); fetch_x(2, 2);
-    auto stage = [&](const u32x4_t (&w)[SK_KB * 2], u32x4_t (&wn)[SK_KB * 2], int st, int slab) {
+    auto stage = [&](const u32x4_t (&w)[KBS * 2], u32x4_t (&wn)[KBS * 2], int st, int slab) {
       // stage st has arrived (this wavefront's part): all but the loads of the next two stages
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((SK_SLABS - 2) * (SK_KB * 2 + NX)) : "memory");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((SK_SLABS - 2) * (KBS * 2 + NX)) : "memory");
       __builtin_amdgcn_s_barrier();                     // ... everywhere; nobody reads slab (st - 1) % 4 any more
       asm volatile("" ::: "memory");
 #ifdef DEINFER_SK_TRACE
