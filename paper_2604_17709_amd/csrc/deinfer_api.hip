@@ -103,10 +103,12 @@ SkPlan skinny_plan(int64_t T, const deinfer_factors_t *const *f, int n) {
   // about one long-lived workgroup per compute unit of a 256-unit device (each keeps enough loads in
   // flight to stream at its share of the HBM rate; the kernel time barely moves between 128 and 1024
   // workgroups): more k-ranges only add partial-sum traffic
+  // (more than 8 k-ranges were measured slower also for the longest k, where 8 ranges give fewer
+  // workgroups than compute units)
   for (int s = 0; s < 2; ++s) {
     const int target = 256;
     int p = (target + pl.groups[s] / 2) / (pl.groups[s] > 0 ? pl.groups[s] : 1);
-    pl.P[s] = p < 1 ? 1 : p > SK_MAX_PARTS ? SK_MAX_PARTS : p;
+    pl.P[s] = p < 1 ? 1 : p > 8 ? 8 : p;
   }
   pl.t_bytes = (size_t)round_up((int64_t)pl.NB * 32 * (pl.rtot_pad > 0 ? pl.rtot_pad : 32) * 2, 256);
   const size_t p0 = (size_t)pl.P[0] * pl.NB * 32 * (size_t)pl.groups[0] * SK_FEAT * 4;
@@ -136,7 +138,8 @@ PfSplitPlan prefill_split_plan(int64_t T, const deinfer_factors_t *const *f, int
   const int64_t wgs = (int64_t)pl.n_tblocks * pl.n_fblocks;
   if (wgs <= 0 || wgs > 128 || KB < 16) return pl;
   int64_t p = 256 / wgs;
-  if (p > SK_MAX_PARTS) p = SK_MAX_PARTS;
+  const int64_t cap = wgs <= 8 ? SK_MAX_PARTS : 8;      // 16 parts only for a handful of tiles
+  if (p > cap) p = cap;
   if (p > KB / 8) p = KB / 8;                       // at least 8 pipeline stages per part
   if (p < 2) return pl;
   pl.kb_per_part = (int)ceil_div(KB, p);

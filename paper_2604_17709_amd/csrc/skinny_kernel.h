@@ -42,7 +42,7 @@ namespace deinfer {
 constexpr int SK_THREADS = 256;
 constexpr int SK_KB = 4;                   // k-blocks per stage at most (k-ranges are multiples of it)
 constexpr int SK_FEAT = 128;               // features per workgroup
-constexpr int SK_MAX_PARTS = 8;            // k-ranges per product at most
+constexpr int SK_MAX_PARTS = 16;           // k-ranges per product at most
 constexpr int SK_SLABS = 4;                // activation slabs in LDS = weight register sets
 
 struct SkProblem {           // one product  act[T x K] . W^T,  W packed as [tiles][KB][64] fragments
@@ -300,35 +300,41 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkReduceParams
   float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float u[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const float *src = R.part + (long long)tok * R.F + col;
-  // all loads first (independent, one round trip), then the sums in a fixed order: deterministic
-  f32x4_t a[SK_MAX_PARTS][2];
+  // eight parts at a time: all loads first (independent, one round trip), then the sums in part
+  // order (deterministic)
+  constexpr int CH = 8;
+  auto chunk = [&](const int p0) {
+    f32x4_t a[CH][2];
 #pragma unroll
-  for (int p = 0; p < SK_MAX_PARTS; ++p) {
-    a[p][0] = a[p][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    if (p < R.P) {
-      a[p][0] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + p * R.part_stride));
-      a[p][1] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + 4));
-    }
-  }
-  if (R.glu_delta > 0) {
-    f32x4_t b[SK_MAX_PARTS][2];
-#pragma unroll
-    for (int p = 0; p < SK_MAX_PARTS; ++p) {
-      b[p][0] = b[p][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-      if (p < R.P) {
-        b[p][0] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + R.glu_delta));
-        b[p][1] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + p * R.part_stride + R.glu_delta + 4));
+    for (int p = 0; p < CH; ++p) {
+      a[p][0] = a[p][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      if (p0 + p < R.P) {
+        a[p][0] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + (p0 + p) * R.part_stride));
+        a[p][1] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + (p0 + p) * R.part_stride + 4));
       }
     }
+    if (R.glu_delta > 0) {
+      f32x4_t b[CH][2];
 #pragma unroll
-    for (int p = 0; p < SK_MAX_PARTS; ++p)
+      for (int p = 0; p < CH; ++p) {
+        b[p][0] = b[p][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (p0 + p < R.P) {
+          b[p][0] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + (p0 + p) * R.part_stride + R.glu_delta));
+          b[p][1] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(src + (p0 + p) * R.part_stride + R.glu_delta + 4));
+        }
+      }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { u[e] += b[p][0][e]; u[4 + e] += b[p][1][e]; }
-  }
+      for (int p = 0; p < CH; ++p)
 #pragma unroll
-  for (int p = 0; p < SK_MAX_PARTS; ++p)
+        for (int e = 0; e < 4; ++e) { u[e] += b[p][0][e]; u[4 + e] += b[p][1][e]; }
+    }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { v[e] += a[p][0][e]; v[4 + e] += a[p][1][e]; }
+    for (int p = 0; p < CH; ++p)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { v[e] += a[p][0][e]; v[4 + e] += a[p][1][e]; }
+  };
+  chunk(0);                                               // the usual case: at most eight parts, no loop
+  for (int p0 = CH; p0 < R.P; p0 += CH) chunk(p0);
   if (R.glu_delta > 0) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = silu_f32(v[e]) * u[e];
