@@ -101,8 +101,10 @@ typedef DEINFER_GLOBAL uint16_t *g_u16_p;
 typedef DEINFER_GLOBAL unsigned long long *g_u64_p;
 
 // fragments per wavefront and batch
-template <int NT>
-struct DecFM { static constexpr int value = NT == 1 ? 16 : NT == 2 ? 6 : NT == 4 ? 3 : 2; };
+// (one token tile: 16 per batch in the down kernel - d_in = 4096 is exactly two batches - and 20 in
+// the up kernel, where a rank of up to 2560 then is a single round trip)
+template <int NT, int PHASE>
+struct DecFM { static constexpr int value = NT == 1 ? (PHASE == 2 ? 20 : 16) : NT == 2 ? 6 : NT == 4 ? 3 : 2; };
 
 struct Batch {
   const u32x4_t *a;     // fragment of k-block 0 of this tile (lane offset not included)
@@ -127,7 +129,7 @@ __device__ __forceinline__ void scalarize(Batch &d) {
 // kernel (PHASE 2).  All members are wave-uniform.
 template <int NT, bool DUAL, int PHASE>
 struct Cursor {
-  static constexpr int SPAN = DEC_WAVES * DecFM<NT>::value;
+  static constexpr int SPAN = DEC_WAVES * DecFM<NT, PHASE>::value;
   int tile, kbp;        // down: position (rank tile, k-block inside it)
   int tile_e, kb_e;     // down: end of the range (tile index, exclusive k-block inside it)
   int g, G1;
@@ -205,10 +207,10 @@ struct Cursor {
   }
 };
 
-template <int NT>
+template <int NT, int PHASE>
 struct Frags {
-  u32x4_t a[DecFM<NT>::value];
-  u32x4_t b[DecFM<NT>::value][NT];
+  u32x4_t a[DecFM<NT, PHASE>::value];
+  u32x4_t b[DecFM<NT, PHASE>::value][NT];
 };
 
 #ifndef DEINFER_LOCAL
@@ -233,8 +235,8 @@ struct Frags {
 // re-reads the last 8 valid columns of its row, which meet zero-padded weights.
 template <int NT, int PHASE>
 __device__ __forceinline__ void load_frags(const Batch &d, int wave, int lane, int k_lane,
-                                           const int (&rowoff)[NT], Frags<NT> &F, uint4 *xlds) {
-  constexpr int FM = DecFM<NT>::value;
+                                           const int (&rowoff)[NT], Frags<NT, PHASE> &F, uint4 *xlds) {
+  constexpr int FM = DecFM<NT, PHASE>::value;
   constexpr bool XLDS = (PHASE == 1 && NT >= 2);
   const gc_u32x4_p a = (gc_u32x4_p)d.a;
   const DEINFER_GLOBAL char *b = (const DEINFER_GLOBAL char *)d.b;
@@ -277,9 +279,9 @@ __device__ __forceinline__ void load_frags(const Batch &d, int wave, int lane, i
     }
   }
 }
-template <int NT>
-__device__ __forceinline__ void multiply(const Batch &d, int wave, const Frags<NT> &F, f32x4_t (&acc)[NT]) {
-  constexpr int FM = DecFM<NT>::value;
+template <int NT, int PHASE>
+__device__ __forceinline__ void multiply(const Batch &d, int wave, const Frags<NT, PHASE> &F, f32x4_t (&acc)[NT]) {
+  constexpr int FM = DecFM<NT, PHASE>::value;
 #pragma unroll
   for (int f = 0; f < FM; ++f) {
     if (d.kb0 + wave + f * DEC_WAVES < d.kb1) {     // wave-uniform
@@ -295,7 +297,7 @@ template <int NT, bool DUAL, int PHASE>
 __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams Pk) {
   __shared__ float4 red[(DUAL && PHASE == 2) ? 2 : 1][DEC_WAVES][NT][kWave];
   constexpr bool XLDS = (PHASE == 1 && NT >= 2);
-  __shared__ uint4 xstage[XLDS ? DEC_WAVES * DecFM<NT>::value * NT * 64 : 1];   // per-wavefront x tiles
+  __shared__ uint4 xstage[XLDS ? DEC_WAVES * DecFM<NT, PHASE>::value * NT * 64 : 1];   // per-wavefront x tiles
   // The parameter block is fetched once, by one vector load per thread, and read from LDS
   // afterwards: lazily scheduled scalar loads from the kernel-argument segment would put
   // several dependent memory round trips in front of the first weight request.
@@ -323,7 +325,7 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
 
   // per-lane activation row offsets (elements): x rows are clamped to the last token, t rows are padded
   // (host guarantees that T * ldx and T16 * Rtot_pad fit 30 bits)
-  uint4 *const xlds = xstage + (XLDS ? wave * DecFM<NT>::value * NT * 64 : 0);
+  uint4 *const xlds = xstage + (XLDS ? wave * DecFM<NT, PHASE>::value * NT * 64 : 0);
   int rowoff[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
@@ -340,7 +342,7 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
   Cursor<NT, DUAL, PHASE> cur;
   cur.init(P, g, G);
   if (trace && cur.G1 >= 0) trace[2] = wall_clock64();
-  Frags<NT> F;
+  Frags<NT, PHASE> F;
   f32x4_t acc[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -350,7 +352,7 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
   auto step = [&](const Batch &dc) {
     load_frags<NT, PHASE>(dc, wave, lane, lkg * 8, rowoff, F, xlds);
     if (trace && n_steps == 0) trace[4] = wall_clock64();
-    multiply<NT>(dc, wave, F, acc);
+    multiply<NT, PHASE>(dc, wave, F, acc);
     if (trace && n_steps == 0 && acc[0][0] != 12345.678f) trace[5] = wall_clock64();
     ++n_steps;
     if (!dc.end_seg) return;

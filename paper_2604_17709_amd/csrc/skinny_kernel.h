@@ -82,7 +82,7 @@ __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P)
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 #ifdef DEINFER_SK_TRACE
   const unsigned long long tr_entry = wall_clock64();
-  unsigned long long tr_first = 0, tr_loop = 0;
+  unsigned long long tr_first = 0, tr_loop = 0, tr_issue = 0;
 #endif
   // consecutive workgroups share the k-range (the same activation slab, kept hot in L2)
   const int g = blockIdx.x % P.n_groups;
@@ -206,6 +206,9 @@ __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P)
   // loads of the next stage have arrived" is one constant wait.
   if (n_stages > 0) {
     u32x4_t w0[KBS * 2], w1[KBS * 2], w2[KBS * 2], w3[KBS * 2];
+#ifdef DEINFER_SK_TRACE
+    tr_issue = wall_clock64();
+#endif
     fetch_w(w0, 0); fetch_x(0, 0);
     fetch_w(w1, 1); fetch_x(1, 1);
     fetch_w(w2, 2); fetch_x(2, 2);
@@ -255,7 +258,7 @@ __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P)
     tr[0] = tr_entry; tr[1] = tr_first; tr[2] = tr_loop; tr[3] = wall_clock64();
     tr[4] = __builtin_amdgcn_s_getreg(6164);      // XCC_ID
     tr[5] = __builtin_amdgcn_s_getreg(63492);     // HW_ID
-    tr[6] = n_stages;
+    tr[6] = n_stages; tr[7] = tr_issue;
   }
 #endif
 #else
