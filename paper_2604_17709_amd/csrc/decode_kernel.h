@@ -1,4 +1,5 @@
-// Memory-bound ("decode", T <= 128 tokens) kernels for PACKED bf16 factor pairs.
+// Memory-bound ("decode") kernels for PACKED bf16 factor pairs; the library uses them for calls
+// of at most 16 tokens (one token tile, NT = 1; the code also covers 2, 4 and 8 tiles).
 //
 // A call is three launches on the caller's stream; kernel boundaries are the only
 // synchronisation (on this part a boundary costs about a microsecond, a software barrier

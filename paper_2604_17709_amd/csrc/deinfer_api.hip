@@ -75,11 +75,6 @@ Geometry geometry(const deinfer_factors_t *f) {
   return g;
 }
 
-int token_tiles(int64_t T) {   // padded 16-token tiles of a decode call: 1, 2, 4 or 8
-  int nt = (int)ceil_div(T, 16);
-  return nt <= 1 ? 1 : nt <= 2 ? 2 : nt <= 4 ? 4 : 8;
-}
-
 // ---- split of a memory-bound call with 16 < T <= 128 tokens
 struct SkPlan {              // split of one call; a pure function of the shapes (also sizes the workspace)
   int NB;                    // 32-token blocks: 1, 2 or 4
@@ -182,10 +177,9 @@ size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
   if (!packed) {
     scratch = (size_t)T * (size_t)(rtot > 0 ? rtot : 1) * sizeof(float);
   } else {
-    const int64_t Tc = T <= 128 ? T : 128;                       // decode-sized chunk
-    const int nt = token_tiles(Tc);
     const size_t rp = (size_t)(rtot_pad > 0 ? rtot_pad : 32);
-    const size_t tdec = (size_t)round_up((int64_t)nt * 16 * rp * 2, 256) + (size_t)DEC_MAX_PARTS * nt * 16 * rp * 4;
+    // T <= 16: t in fragment order and up to DEC_MAX_PARTS fp32 part buffers of one 16-token tile
+    const size_t tdec = T <= 16 ? (size_t)round_up((int64_t)16 * rp * 2, 256) + (size_t)DEC_MAX_PARTS * 16 * rp * 4 : 0;
     size_t tpre = T > 128 ? (size_t)round_up(T, 256) * rp * 2 : 0;
     if (T > 128) tpre = (size_t)round_up((int64_t)tpre, 256) + prefill_split_plan(T, pairs, n).part_bytes;
     scratch = round_up((int64_t)tdec, 256) + round_up((int64_t)tpre, 256);
@@ -279,15 +273,16 @@ int max_parts(long long total, int KB1, int G1) {
   return worst;
 }
 
-// Decode-sized call (T <= 128) on packed pairs; rows [row0, row0 + T) of the group's tensors.
-int run_decode(const Group &gq, int64_t row0, int64_t T) {
+// Call of at most 16 tokens on packed pairs.
+int run_decode(const Group &gq) {
+  const int64_t T = gq.T;
   const int cus = device_cus();
   if (cus <= 0) return fail(DEINFER_ERR_DEVICE, "no usable HIP device");
-  const int nt = token_tiles(T);
+  const int nt = 1;          // 16-token tiles
   char *ws = static_cast<char *>(gq.ws);
   DecParams P;
   memset(&P, 0, sizeof(P));
-  P.x = static_cast<const uint16_t *>(gq.x) + row0 * gq.ldx;
+  P.x = static_cast<const uint16_t *>(gq.x);
   P.ldx = gq.ldx; P.T = (int)T; P.d_in = (int)gq.f[0]->d_in; P.KB1 = (int)ceil_div(gq.f[0]->d_in, 32);
   P.bias = static_cast<const uint16_t *>(gq.bias); P.act = gq.act;
   P.n_pairs = gq.n;
@@ -297,9 +292,9 @@ int run_decode(const Group &gq, int64_t row0, int64_t T) {
     DecPair &d = P.p[i];
     d.Up = static_cast<const uint4 *>(gq.f[i]->U);
     d.Vp = static_cast<const uint4 *>(gq.f[i]->V);
-    d.y = gq.out[i] ? static_cast<uint16_t *>(gq.out[i]) + row0 * gq.ldo[i] : nullptr;
+    d.y = static_cast<uint16_t *>(gq.out[i]);
     d.ldy = gq.ldo[i];
-    d.t_out = gq.t_out[i] ? static_cast<uint16_t *>(gq.t_out[i]) + row0 * gq.ldt[i] : nullptr;
+    d.t_out = static_cast<uint16_t *>(gq.t_out[i]);
     d.ldt_out = gq.ldt[i];
     d.r = (int)gq.f[i]->r; d.r_pad = (int)ge.r_pad; d.d_out = (int)gq.f[i]->d_out;
     d.n_otiles = (int)ge.n_otiles; d.tile0 = tile0;
@@ -329,12 +324,9 @@ int run_decode(const Group &gq, int64_t row0, int64_t T) {
   P.part = reinterpret_cast<float *>(ws + WS_HEADER + t_bytes);
   P.part_stride = (long long)nt * 16 * P.Rtot_pad;
   const int grid2 = P.n_items2;     // one work item per workgroup
-  switch (nt) {
-    case 1: return launch_decode_nt<1>(P, gq.glu, grid2, gq.stream, gq.down_only);
-    case 2: return launch_decode_nt<2>(P, gq.glu, grid2, gq.stream, gq.down_only);
-    case 4: return launch_decode_nt<4>(P, gq.glu, grid2, gq.stream, gq.down_only);
-    default: return launch_decode_nt<8>(P, gq.glu, grid2, gq.stream, gq.down_only);
-  }
+  // (the kernel is written for 1, 2, 4 or 8 token tiles; calls with more than 16 tokens take the
+  // streaming kernels of skinny_host.inc, so only the one-tile form is instantiated)
+  return launch_decode_nt<1>(P, gq.glu, grid2, gq.stream, gq.down_only);
 }
 
 template <typename TE>
@@ -526,7 +518,7 @@ int run_group(Group gq) {
 
   // ---- dispatch
   if (!packed) return dtype == DEINFER_BF16 ? run_generic<uint16_t>(gq) : run_generic<float>(gq);
-  if (gq.T <= 16 && !gq.up_only) return run_decode(gq, 0, gq.T);
+  if (gq.T <= 16 && !gq.up_only) return run_decode(gq);
   if (gq.T <= 128) return run_skinny(gq);
   return run_prefill(gq);
 }
