@@ -67,6 +67,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time the other decode batch sizes")
     ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"], help="storage type of weights, activations and outputs")
     ap.add_argument("--rank-override", default="", help="e.g. gate=2357,up=2357,down=2357: ranks not taken from the rule")
     ap.add_argument("--no-second-row", action="store_true",
                     help="skip the second row of the default workload (the ranks that the configuration prints, 2357)")
@@ -93,13 +94,18 @@ def main():
 
     block_name, T_default, bound = WORKLOADS[args.workload]
     T = args.T or T_default
+    if (args.workload.endswith("kv_rebuild") or "_tp8_rank_" in args.workload) and args.dtype != "bf16":
+        print("bench.py: --dtype f16 is for the block workloads", file=sys.stderr)
+        sys.exit(2)
     if args.workload.endswith("kv_rebuild"):
         return kv_rebuild(args, L, si.BLOCKS[block_name], T)
     if "_tp8_rank_" in args.workload:
         return tp_rank(args, L, si.BLOCKS[block_name], T, 8, bound if T > 128 else "hbm")
     if T <= 128:
         bound = "hbm"
-    shape = si.BLOCKS[block_name]
+    import dataclasses
+    shape = dataclasses.replace(si.BLOCKS[block_name], dtype=args.dtype)
+    tdt = torch.float16 if args.dtype == "f16" else torch.bfloat16
     proj = shape.projections()
     rho = 1.0 - shape.keep_num / shape.keep_den
     ranks = {p: dn.deinfer_rank_for_ratio(m, n, rho) for p, (m, n) in proj.items()}
@@ -112,7 +118,7 @@ def main():
     host = si.block_tensors(shape, ranks, max(T, 1), args.seed)
 
     def dev(t):
-        return torch.from_numpy(t.bits.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(t.bits.view(np.int16)).cuda().view(tdt)
 
     params = sum(ranks[p] * (m + n) for p, (m, n) in proj.items())
     weight_bytes = 2 * params
@@ -136,7 +142,7 @@ def main():
     x = dev(host["x"]); a = dev(host["a"]); h_in = dev(host["h_in"])
     if not shape.glu:
         b_gate = dev(host["b_gate"]).reshape(-1); b_down = dev(host["b_down"]).reshape(-1)
-    bf = torch.bfloat16
+    bf = tdt
     q = torch.empty((T, proj["q"][1]), dtype=bf, device="cuda")
     k = torch.empty((T, proj["k"][1]), dtype=bf, device="cuda")
     v = torch.empty((T, proj["v"][1]), dtype=bf, device="cuda")
@@ -393,7 +399,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec_per_step * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": "%s T=%d (%s of one block)" % (args.workload, T, "qkv+o+gateup_silu+down" if shape.glu else
                                                               "qkv+o+linear_act(bias, ReLU)+linear_act(bias)"),
                    "ranks": ranks, "weight_MB": round(weight_bytes / 1e6, 1), "weight_copies": n_copies,
@@ -424,7 +430,7 @@ def main():
     # ---------------------------------------------------------------- second row: the ranks the configuration prints
     # (its rule gives 2388 for gate / up / down, its text 2357; the rule is what is benchmarked
     # above, the printed value here, in a child process with the same settings)
-    if args.workload == "llama7b_keep80_decode" and not args.rank_override and not args.no_second_row:
+    if args.workload == "llama7b_keep80_decode" and not args.rank_override and not args.no_second_row and args.dtype == "bf16":
         import subprocess
         cmd = [sys.executable, os.path.abspath(__file__), "--workload", args.workload, "--T", str(T), "--steps", str(args.steps),
                "--warmup", str(args.warmup), "--launch", args.launch, "--seed", str(args.seed), "--no-cpu-baseline",

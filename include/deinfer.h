@@ -41,11 +41,11 @@ typedef enum {
   DEINFER_ERR_DEVICE = -5        /* the HIP runtime reported an error (no GPU, bad launch) */
 } deinfer_status_t;
 
-typedef enum { DEINFER_F32 = 0, DEINFER_BF16 = 1 } deinfer_dtype_t;
+typedef enum { DEINFER_F32 = 0, DEINFER_BF16 = 1, DEINFER_F16 = 2 } deinfer_dtype_t;
 
 typedef enum {
   DEINFER_LAYOUT_RAW = 0,    /* U[d_in x r] (ldu), V[r x d_out] (ldv), row-major          */
-  DEINFER_LAYOUT_PACKED = 1  /* produced by deinfer_pack_factors (bf16 only), see below   */
+  DEINFER_LAYOUT_PACKED = 1  /* produced by deinfer_pack_factors (bf16 or fp16), see below */
 } deinfer_layout_t;
 
 /*
@@ -127,16 +127,16 @@ int deinfer_probe_mfma_bf16(const void *operands, size_t operand_bytes, int64_t 
 int deinfer_rank_for_ratio(int64_t m, int64_t n, double param_reduction, int64_t *r_out);
 
 /*
- * Packed weight format (bf16 only).  Weights are static, so they are re-laid once
+ * Packed weight format (the 16-bit types: bf16, fp16).  Weights are static, so they are re-laid once
  * for the matrix cores: each factor is stored transposed ("feature" rows, reduction
  * index contiguous), zero-padded (r to a multiple of 32, feature counts to 16,
  * d_in to 32), and cut into 16-feature x 32-k fragments of 1 KiB held in the lane
- * order of the gfx950 16x16x32 bf16 MFMA operand, fragment (tile, kblock) at
+ * order of the gfx950 16x16x32 MFMA operand (same for bf16 and fp16), fragment (tile, kblock) at
  * ((tile * n_kblocks) + kblock) KiB.  A wavefront then reads one fragment with a
  * single fully coalesced 16-byte-per-lane load.  Zero rank rows are exact no-ops.
  *
  * deinfer_packed_bytes: size of the packed image of `raw` (host-only).
- * deinfer_pack_factors: enqueue the re-layout of `raw` (RAW, bf16) into dst
+ * deinfer_pack_factors: enqueue the re-layout of `raw` (RAW, bf16 or fp16) into dst
  *   (device, 256-byte aligned, >= packed bytes) and fill *packed (host struct) with
  *   a descriptor that points into dst.  dst must outlive every use of *packed.
  */
@@ -194,7 +194,7 @@ int deinfer_lowrank_qkv(const void *x, int64_t T, int64_t ldx,
  *   h = silu((x U_g) V_g) * ((x U_u) V_u),   silu(z) = z / (1 + exp(-z)),
  * element-wise product, evaluated in fp32 and rounded once.  Both pairs share d_in
  * and d_out (= FFN width).  For T <= 128 the full-width gate and up results never reach
- * memory in the output type; for larger T the gate product is staged (bf16) in h itself
+ * memory in the output type; for larger T the gate product is staged (in the output type) in h itself
  * before the final values overwrite it.
  */
 int deinfer_lowrank_gateup_silu(const void *x, int64_t T, int64_t ldx,
@@ -224,7 +224,7 @@ int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_fact
  *
  * deinfer_lowrank_down_proj: t_i = x U_i for 1 to 3 pairs that share x (the concatenated
  *   downward projection); t_out[i]: device, T x r_i, pitch ldt[i] >= r_i, written in the pairs'
- *   dtype (bf16: one rounding); f, t_out, ldt: host arrays of n_pairs entries.  No upward
+ *   dtype (bf16 / fp16: one rounding); f, t_out, ldt: host arrays of n_pairs entries.  No upward
  *   projection runs and V is not read.
  * deinfer_lowrank_up_glu_silu: h = silu(t_gate V_gate) * (t_up V_up), the second stage of
  *   deinfer_lowrank_gateup_silu alone; t_gate / t_up as the t of deinfer_lowrank_up (same
@@ -297,7 +297,7 @@ int deinfer_kv_compact_copy(const void *pool, int64_t n_pool_blocks, int64_t blo
 /*
  * Rotary position embedding in place (Sec. 4.3 applies it to the rebuilt keys; the paper prints
  * no formula, this is the one of LLaMA-type models): x is T x (n_heads * head_dim), pitch ldx,
- * device, dtype DEINFER_BF16 or DEINFER_F32; inside every head the elements i and i + head_dim/2
+ * device, dtype DEINFER_BF16, DEINFER_F16 or DEINFER_F32; inside every head the elements i and i + head_dim/2
  * (i < head_dim/2) are replaced by
  *   x_i cos(a) - x_{i + D/2} sin(a),   x_{i + D/2} cos(a) + x_i sin(a),   a = pos * theta^(-2 i / D),
  * pos = positions[token] (device, int32).  Angles in double precision, products in fp32, one

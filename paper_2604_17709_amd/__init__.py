@@ -24,6 +24,7 @@ ERR_DEVICE = -5
 
 F32 = 0
 BF16 = 1
+F16 = 2
 LAYOUT_RAW = 0
 LAYOUT_PACKED = 1
 PROF_DECODE_DOWN, PROF_DECODE_REDUCE, PROF_DECODE_UP, PROF_PREFILL_DOWN, PROF_PREFILL_UP = 1, 2, 3, 4, 5
@@ -128,6 +129,8 @@ def _dtype_code(t) -> int:
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
+    if t.dtype == torch.float16:
+        return F16
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
@@ -340,7 +343,7 @@ def deinfer_kv_compact_copy(pool, block_bytes: int, plan_dev, buffer, stream=Non
 def deinfer_rope_inplace(x, n_heads: int, head_dim: int, positions_dev, theta: float = 10000.0, stream=None) -> None:
     """Rotary position embedding in place on x [T, n_heads * head_dim] (pairs i, i + head_dim / 2)."""
     import torch
-    dt = {torch.bfloat16: BF16, torch.float32: F32}[x.dtype]
+    dt = _dtype_code(x)
     _check(lib().deinfer_rope_inplace(_ptr(x), _rows(x, "x"), _ld(x), int(n_heads), int(head_dim), _ptr(positions_dev),
                                       float(theta), dt, _stream(stream)))
 

@@ -26,7 +26,34 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   return static_cast<uint16_t>(pack_bf16x2(f, 0.0f) & 0xffffu);
 }
 
+// ---- the two 16-bit storage types of the packed path, selected by a template integer that equals
+// the dtype code of the boundary (1 = bf16, 2 = fp16).  Storage is a raw 16-bit pattern; sums are
+// fp32; results are rounded once, to nearest even, by the device's packed conversion instructions.
+constexpr int DT_BF16 = 1, DT_F16 = 2;
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+template <int DT> __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  if constexpr (DT == DT_F16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, f16x2_t));
+  else return pack_bf16x2(lo, hi);
+}
+template <int DT> __device__ __forceinline__ float lo_f32(uint32_t w) {      // element in the low half of a word
+  if constexpr (DT == DT_F16) return (float)__builtin_bit_cast(f16x2_t, w)[0];
+  else return __uint_as_float(w << 16);
+}
+template <int DT> __device__ __forceinline__ float hi_f32(uint32_t w) {
+  if constexpr (DT == DT_F16) return (float)__builtin_bit_cast(f16x2_t, w)[1];
+  else return __uint_as_float(w & 0xffff0000u);
+}
+template <int DT> __device__ __forceinline__ float cvt_in(uint16_t b) { return lo_f32<DT>(b); }
+template <int DT> __device__ __forceinline__ uint16_t cvt_out(float f) { return static_cast<uint16_t>(pack2<DT>(f, 0.0f) & 0xffffu); }
+
+struct f16_bits { uint16_t v; };          // element type of fp16 tensors in the generic kernels
+
 template <typename T> struct Elem;
+template <> struct Elem<f16_bits> {
+  static __device__ __forceinline__ float load(const f16_bits *p) { return cvt_in<DT_F16>(p->v); }
+  static __device__ __forceinline__ void store(f16_bits *p, float v) { p->v = cvt_out<DT_F16>(v); }
+};
 template <> struct Elem<float> {
   static __device__ __forceinline__ float load(const float *p) { return *p; }
   static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
@@ -35,6 +62,9 @@ template <> struct Elem<uint16_t> {  // bf16
   static __device__ __forceinline__ float load(const uint16_t *p) { return bf16_to_f32(*p); }
   static __device__ __forceinline__ void store(uint16_t *p, float v) { *p = f32_to_bf16(v); }
 };
+template <typename T> struct DtOf { static constexpr int value = 0; };          // storage-type code of an element type
+template <> struct DtOf<uint16_t> { static constexpr int value = DT_BF16; };
+template <> struct DtOf<f16_bits> { static constexpr int value = DT_F16; };
 
 // SiLU in fp32: z * sigmoid(z) = z / (1 + exp(-z))
 __device__ __forceinline__ float silu_f32(float z) { return z * __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
@@ -50,6 +80,28 @@ __device__ __forceinline__ float act_f32(float z, int act) {
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(const u32x4_t &v) {
   return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// The two matrix instructions of the kernels, on 8 packed 16-bit values per lane and operand.
+template <int DT> __device__ __forceinline__ f32x16_t mfma32(const u32x4_t &a, const u32x4_t &b, const f32x16_t &c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  if constexpr (DT == DT_F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
+#else
+  return c;
+#endif
+}
+template <int DT> __device__ __forceinline__ f32x4_t mfma16(const u32x4_t &a, const u32x4_t &b, const f32x4_t &c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  if constexpr (DT == DT_F16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
+#else
+  return c;
+#endif
 }
 
 }  // namespace deinfer

@@ -280,7 +280,7 @@ __device__ __forceinline__ void load_frags(const Batch &d, int wave, int lane, i
     }
   }
 }
-template <int NT, int PHASE>
+template <int DT, int NT, int PHASE>
 __device__ __forceinline__ void multiply(const Batch &d, int wave, const Frags<NT, PHASE> &F, f32x4_t (&acc)[NT]) {
   constexpr int FM = DecFM<NT, PHASE>::value;
 #pragma unroll
@@ -288,13 +288,13 @@ __device__ __forceinline__ void multiply(const Batch &d, int wave, const Frags<N
     if (d.kb0 + wave + f * DEC_WAVES < d.kb1) {     // wave-uniform
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(F.a[f]), as_bf16x8(F.b[f][nt]), acc[nt], 0, 0, 0);
+        acc[nt] = mfma16<DT>(F.a[f], F.b[f][nt], acc[nt]);
     }
   }
 }
 
 // PHASE 1: down kernel (grid = P.G1).  PHASE 2: up kernel (grid = any, items round-robin).
-template <int NT, bool DUAL, int PHASE>
+template <int DT, int NT, bool DUAL, int PHASE>
 __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams Pk) {
   __shared__ float4 red[(DUAL && PHASE == 2) ? 2 : 1][DEC_WAVES][NT][kWave];
   constexpr bool XLDS = (PHASE == 1 && NT >= 2);
@@ -353,7 +353,7 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
   auto step = [&](const Batch &dc) {
     load_frags<NT, PHASE>(dc, wave, lane, lkg * 8, rowoff, F, xlds);
     if (trace && n_steps == 0) trace[4] = wall_clock64();
-    multiply<NT, PHASE>(dc, wave, F, acc);
+    multiply<DT, NT, PHASE>(dc, wave, F, acc);
     if (trace && n_steps == 0 && acc[0][0] != 12345.678f) trace[5] = wall_clock64();
     ++n_steps;
     if (!dc.end_seg) return;
@@ -383,8 +383,8 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
         const int col = dc.tile * 16 + lkg * 4;
         if (tok >= P.T) s = make_float4(0.f, 0.f, 0.f, 0.f);
         uint2 pk;
-        pk.x = pack_bf16x2(s.x, s.y);
-        pk.y = pack_bf16x2(s.z, s.w);
+        pk.x = pack2<DT>(s.x, s.y);
+        pk.y = pack2<DT>(s.z, s.w);
         const int frag = nt * (P.Rtot_pad >> 5) + (col >> 5);
         const int tl = lrow + 16 * ((col & 31) >> 3);
         *(g_uint2_p)((const DEINFER_GLOBAL uint16_t *)uni_ptr(P.t) + (frag * 512 + tl * 8 + (col & 7))) = pk;
@@ -397,7 +397,7 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
           const float sv[4] = {s.x, s.y, s.z, s.w};
 #pragma unroll
           for (int v = 0; v < 4; ++v)
-            if (c0 + v < pr.r) ((g_u16_p)pr.t_out)[(long long)tok * pr.ldt_out + c0 + v] = f32_to_bf16(sv[v]);
+            if (c0 + v < pr.r) ((g_u16_p)pr.t_out)[(long long)tok * pr.ldt_out + c0 + v] = cvt_out<DT>(sv[v]);
         }
       } else if (PHASE == 1) {
         // fp32 partial sums of this workgroup's share of the tile: 4 consecutive rank columns
@@ -426,7 +426,7 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
           if (bp != nullptr) {
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-              if (f0 + v < pr.d_out) b[v] = bf16_to_f32(bp[f0 + v]);
+              if (f0 + v < pr.d_out) b[v] = cvt_in<DT>(bp[f0 + v]);
           }
           s.x = act_f32(s.x + b[0], act); s.y = act_f32(s.y + b[1], act);
           s.z = act_f32(s.z + b[2], act); s.w = act_f32(s.w + b[3], act);
@@ -435,14 +435,14 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
           uint16_t *dst = pr.y + (long long)tok * pr.ldy + f0;
           if (f0 + 3 < pr.d_out && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
             uint2 pk;
-            pk.x = pack_bf16x2(s.x, s.y);
-            pk.y = pack_bf16x2(s.z, s.w);
+            pk.x = pack2<DT>(s.x, s.y);
+            pk.y = pack2<DT>(s.z, s.w);
             *(g_uint2_p)(dst) = pk;
           } else {
             const float sv[4] = {s.x, s.y, s.z, s.w};
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-              if (f0 + v < pr.d_out) ((g_u16_p)dst)[v] = f32_to_bf16(sv[v]);
+              if (f0 + v < pr.d_out) ((g_u16_p)dst)[v] = cvt_out<DT>(sv[v]);
           }
         }
       }
@@ -462,6 +462,7 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
 // t[tok][c] = bf16(sum over the parts of rank tile c / 16, in part order); rows T..T16-1 of t
 // are zero.  One thread per token row and group of 4 rank columns.  Also writes the optional
 // rank-space outputs.  Grid: ceil(T16 * Rtot_pad / 4 / 256) x 256 threads.
+template <int DT>
 __global__ __launch_bounds__(256) void decode_reduce_kernel(const DecParams P, int T16) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const int groups = P.Rtot_pad >> 2;
@@ -489,12 +490,12 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const DecParams P, i
       const float sv[4] = {s.x, s.y, s.z, s.w};
 #pragma unroll
       for (int v = 0; v < 4; ++v)
-        if (c0 + v < pr.r) pr.t_out[(long long)tok * pr.ldt_out + c0 + v] = f32_to_bf16(sv[v]);
+        if (c0 + v < pr.r) pr.t_out[(long long)tok * pr.ldt_out + c0 + v] = cvt_out<DT>(sv[v]);
     }
   }
   uint2 pk;
-  pk.x = pack_bf16x2(s.x, s.y);
-  pk.y = pack_bf16x2(s.z, s.w);
+  pk.x = pack2<DT>(s.x, s.y);
+  pk.y = pack2<DT>(s.z, s.w);
   // fragment order: (token tile, k-block) -> 1 KiB, lane = token % 16 + 16 * ((k % 32) / 8)
   const long long frag = (long long)(tok >> 4) * (P.Rtot_pad >> 5) + (col >> 5);
   const int lane = (tok & 15) + 16 * ((col & 31) >> 3);

@@ -48,7 +48,15 @@ int fail(int code, const char *fmt, ...) {
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
-inline size_t elem_size(int dtype) { return dtype == DEINFER_BF16 ? 2 : 4; }
+inline size_t elem_size(int dtype) { return dtype == DEINFER_F32 ? 4 : 2; }
+static_assert(DT_BF16 == DEINFER_BF16 && DT_F16 == DEINFER_F16, "the kernels' storage-type codes are the boundary's dtype codes");
+// Calls f with a value of the element type of `dtype` (float, uint16_t for bf16, f16_bits for fp16).
+template <typename F>
+int by_dtype(int dtype, F f) {
+  if (dtype == DEINFER_F32) return f(float{});
+  if (dtype == DEINFER_F16) return f(f16_bits{});
+  return f(uint16_t{});
+}
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 // ---- workspace layout -------------------------------------------------------------
@@ -150,7 +158,7 @@ int validate_pair(const deinfer_factors_t *f, const char *name) {
                 (long long)f->d_in, (long long)f->d_out, (long long)f->r);
   if (f->d_in > (1 << 30) || f->d_out > (1 << 30) || f->r > (1 << 30))
     return fail(DEINFER_ERR_INVALID_ARG, "%s: sizes above 2^30 are not supported", name);
-  if (f->dtype != DEINFER_F32 && f->dtype != DEINFER_BF16)
+  if (f->dtype != DEINFER_F32 && f->dtype != DEINFER_BF16 && f->dtype != DEINFER_F16)
     return fail(DEINFER_ERR_UNSUPPORTED, "%s: unknown dtype %d", name, f->dtype);
   if (f->layout != DEINFER_LAYOUT_RAW && f->layout != DEINFER_LAYOUT_PACKED)
     return fail(DEINFER_ERR_UNSUPPORTED, "%s: unknown layout %d", name, f->layout);
@@ -162,7 +170,8 @@ int validate_pair(const deinfer_factors_t *f, const char *name) {
     if (f->r > 0 && (!aligned(f->U, elem_size(f->dtype)) || !aligned(f->V, elem_size(f->dtype))))
       return fail(DEINFER_ERR_MISALIGNED, "%s: U / V not aligned to the element size", name);
   } else {
-    if (f->dtype != DEINFER_BF16) return fail(DEINFER_ERR_UNSUPPORTED, "%s: packed layout is bf16 only", name);
+    if (f->dtype != DEINFER_BF16 && f->dtype != DEINFER_F16)
+      return fail(DEINFER_ERR_UNSUPPORTED, "%s: the packed layout holds 16-bit types (bf16, fp16) only", name);
     if (f->r > 0 && (!aligned(f->U, 16) || !aligned(f->V, 16)))
       return fail(DEINFER_ERR_MISALIGNED, "%s: packed U / V must be 16-byte aligned", name);
   }
@@ -234,11 +243,11 @@ struct Group {
   void *ws; size_t ws_bytes; hipStream_t stream;
 };
 
-template <int NT>
+template <int DT, int NT>
 int launch_decode_nt(const DecParams &P, bool glu, int grid2, hipStream_t s, bool down_only) {
   {
     ProfScope ps(DEINFER_PROF_DECODE_DOWN, s);
-    hipLaunchKernelGGL((decode_kernel<NT, false, 1>), dim3(P.G1), dim3(DEC_THREADS), 0, s, P);
+    hipLaunchKernelGGL((decode_kernel<DT, NT, false, 1>), dim3(P.G1), dim3(DEC_THREADS), 0, s, P);
   }
   if (int rc = check_launch("decode down kernel")) return rc;
   if (!P.direct1) {
@@ -246,15 +255,15 @@ int launch_decode_nt(const DecParams &P, bool glu, int grid2, hipStream_t s, boo
     const long long n = (long long)T16 * (P.Rtot_pad / 4);
     {
       ProfScope ps(DEINFER_PROF_DECODE_REDUCE, s);
-      hipLaunchKernelGGL(decode_reduce_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, P, T16);
+      hipLaunchKernelGGL(decode_reduce_kernel<DT>, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, P, T16);
     }
     if (int rc = check_launch("decode reduce kernel")) return rc;
   }
   if (down_only) return DEINFER_OK;
   {
     ProfScope ps(DEINFER_PROF_DECODE_UP, s);
-    if (glu) hipLaunchKernelGGL((decode_kernel<NT, true, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
-    else     hipLaunchKernelGGL((decode_kernel<NT, false, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
+    if (glu) hipLaunchKernelGGL((decode_kernel<DT, NT, true, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
+    else     hipLaunchKernelGGL((decode_kernel<DT, NT, false, 2>), dim3(grid2), dim3(DEC_THREADS), 0, s, P);
   }
   return check_launch("decode up kernel");
 }
@@ -326,7 +335,8 @@ int run_decode(const Group &gq) {
   const int grid2 = P.n_items2;     // one work item per workgroup
   // (the kernel is written for 1, 2, 4 or 8 token tiles; calls with more than 16 tokens take the
   // streaming kernels of skinny_host.inc, so only the one-tile form is instantiated)
-  return launch_decode_nt<1>(P, gq.glu, grid2, gq.stream, gq.down_only);
+  return gq.f[0]->dtype == DEINFER_F16 ? launch_decode_nt<DT_F16, 1>(P, gq.glu, grid2, gq.stream, gq.down_only)
+                                      : launch_decode_nt<DT_BF16, 1>(P, gq.glu, grid2, gq.stream, gq.down_only);
 }
 
 template <typename TE>
@@ -469,14 +479,13 @@ int run_group(Group gq) {
     if (gq.f[0]->r == 0) {       // empty product: y = act(bias)
       const int64_t cnt = gq.T * gq.f[0]->d_out;
       if (cnt == 0) return DEINFER_OK;
-      if (dtype == DEINFER_BF16)
-        hipLaunchKernelGGL((bias_act_fill_kernel<uint16_t>), dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, gq.stream,
-                           static_cast<uint16_t *>(gq.out[0]), gq.ldo[0], (int)gq.T, (int)gq.f[0]->d_out,
-                           static_cast<const uint16_t *>(gq.bias), gq.act);
-      else
-        hipLaunchKernelGGL((bias_act_fill_kernel<float>), dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, gq.stream,
-                           static_cast<float *>(gq.out[0]), gq.ldo[0], (int)gq.T, (int)gq.f[0]->d_out,
-                           static_cast<const float *>(gq.bias), gq.act);
+      by_dtype(dtype, [&](auto tag) {
+        using TE = decltype(tag);
+        hipLaunchKernelGGL((bias_act_fill_kernel<TE>), dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, gq.stream,
+                           static_cast<TE *>(gq.out[0]), gq.ldo[0], (int)gq.T, (int)gq.f[0]->d_out,
+                           static_cast<const TE *>(gq.bias), gq.act);
+        return 0;
+      });
       return check_launch("bias / activation fill");
     }
   }
@@ -496,15 +505,13 @@ int run_group(Group gq) {
     gq = rest;
   } else if (any_zero) {
     if (gq.glu) {   // silu(0) * u == 0 and silu(g) * 0 == 0
-      return dtype == DEINFER_BF16 ? zero_output<uint16_t>(gq.out[0], gq.ldo[0], gq.T, gq.f[0]->d_out, gq.stream)
-                                   : zero_output<float>(gq.out[0], gq.ldo[0], gq.T, gq.f[0]->d_out, gq.stream);
+      return by_dtype(dtype, [&](auto tag) { return zero_output<decltype(tag)>(gq.out[0], gq.ldo[0], gq.T, gq.f[0]->d_out, gq.stream); });
     }
     Group rest = gq;
     rest.n = 0;
     for (int i = 0; i < gq.n; ++i) {
       if (gq.f[i]->r == 0) {
-        int rc = dtype == DEINFER_BF16 ? zero_output<uint16_t>(gq.out[i], gq.ldo[i], gq.T, gq.f[i]->d_out, gq.stream)
-                                       : zero_output<float>(gq.out[i], gq.ldo[i], gq.T, gq.f[i]->d_out, gq.stream);
+        int rc = by_dtype(dtype, [&](auto tag) { return zero_output<decltype(tag)>(gq.out[i], gq.ldo[i], gq.T, gq.f[i]->d_out, gq.stream); });
         if (rc) return rc;
       } else {
         rest.f[rest.n] = gq.f[i]; rest.out[rest.n] = gq.out[i]; rest.ldo[rest.n] = gq.ldo[i];
@@ -517,7 +524,7 @@ int run_group(Group gq) {
   }
 
   // ---- dispatch
-  if (!packed) return dtype == DEINFER_BF16 ? run_generic<uint16_t>(gq) : run_generic<float>(gq);
+  if (!packed) return by_dtype(dtype, [&](auto tag) { return run_generic<decltype(tag)>(gq); });
   if (gq.T <= 16 && !gq.up_only) return run_decode(gq);
   if (gq.T <= 128) return run_skinny(gq);
   return run_prefill(gq);
@@ -650,7 +657,7 @@ int deinfer_rope_inplace(void *x, int64_t T, int64_t ldx, int64_t n_heads, int64
                          double theta, int dtype, void *stream) {
   if (T < 0 || n_heads <= 0 || head_dim <= 0 || head_dim % 2 != 0)
     return fail(DEINFER_ERR_INVALID_ARG, "rope: T >= 0, n_heads > 0 and an even head_dim > 0 are required");
-  if (dtype != DEINFER_F32 && dtype != DEINFER_BF16) return fail(DEINFER_ERR_UNSUPPORTED, "rope: unknown dtype %d", dtype);
+  if (dtype != DEINFER_F32 && dtype != DEINFER_BF16 && dtype != DEINFER_F16) return fail(DEINFER_ERR_UNSUPPORTED, "rope: unknown dtype %d", dtype);
   if (!(theta > 0.0)) return fail(DEINFER_ERR_INVALID_ARG, "rope: theta must be positive");
   if (n_heads > (1 << 20) || head_dim > (1 << 20) || ldx < n_heads * head_dim)
     return fail(DEINFER_ERR_INVALID_ARG, "rope: ldx smaller than n_heads * head_dim, or sizes out of range");
@@ -662,12 +669,12 @@ int deinfer_rope_inplace(void *x, int64_t T, int64_t ldx, int64_t n_heads, int64
   if (ceil_div(n, (int64_t)256) > INT32_MAX) return fail(DEINFER_ERR_UNSUPPORTED, "rope: too many tokens");
   const dim3 grid((unsigned)ceil_div(n, (int64_t)256));
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (dtype == DEINFER_BF16)
-    hipLaunchKernelGGL((rope_inplace_kernel<uint16_t>), grid, dim3(256), 0, s, static_cast<uint16_t *>(x), (long long)T,
+  by_dtype(dtype, [&](auto tag) {
+    using TE = decltype(tag);
+    hipLaunchKernelGGL((rope_inplace_kernel<TE>), grid, dim3(256), 0, s, static_cast<TE *>(x), (long long)T,
                        (long long)ldx, (int)n_heads, (int)head_dim, positions, log2(theta));
-  else
-    hipLaunchKernelGGL((rope_inplace_kernel<float>), grid, dim3(256), 0, s, static_cast<float *>(x), (long long)T,
-                       (long long)ldx, (int)n_heads, (int)head_dim, positions, log2(theta));
+    return 0;
+  });
   return check_launch("rope");
 }
 
@@ -697,7 +704,8 @@ int deinfer_pack_factors(const deinfer_factors_t *raw, void *dst, size_t dst_byt
   if (int rc = validate_pair(raw, "raw")) return rc;
   if (!packed) return fail(DEINFER_ERR_INVALID_ARG, "packed descriptor is NULL");
   if (raw->layout != DEINFER_LAYOUT_RAW) return fail(DEINFER_ERR_INVALID_ARG, "source pair is not in RAW layout");
-  if (raw->dtype != DEINFER_BF16) return fail(DEINFER_ERR_UNSUPPORTED, "only bf16 pairs can be packed");
+  if (raw->dtype != DEINFER_BF16 && raw->dtype != DEINFER_F16)
+    return fail(DEINFER_ERR_UNSUPPORTED, "only pairs of a 16-bit type (bf16, fp16) can be packed");
   size_t need = 0;
   deinfer_packed_bytes(raw, &need);
   if (need > 0 && !dst) return fail(DEINFER_ERR_INVALID_ARG, "dst is NULL");

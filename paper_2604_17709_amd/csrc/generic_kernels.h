@@ -100,7 +100,7 @@ __global__ void bias_act_fill_kernel(TC *C, int64_t ldc, int M, int N, const TC 
 template <typename TC>
 __global__ void zero2d_kernel(TC *C, int64_t ldc, int M, int N) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < (int64_t)M * N) C[(i / N) * ldc + (i % N)] = TC(0);
+  if (i < (int64_t)M * N) C[(i / N) * ldc + (i % N)] = TC{};
 }
 __global__ void fill_words_kernel(uint32_t *p, size_t n, uint32_t v) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -87,10 +87,11 @@ __global__ __launch_bounds__(256) void rope_inplace_kernel(TE *x, long long T, l
       u32x4_t ra, rb;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const float a0 = __uint_as_float(va[w] << 16), a1 = __uint_as_float(va[w] & 0xffff0000u);
-        const float b0 = __uint_as_float(vb[w] << 16), b1 = __uint_as_float(vb[w] & 0xffff0000u);
-        ra[w] = pack_bf16x2(a0 * cs[2 * w] - b0 * sn[2 * w], a1 * cs[2 * w + 1] - b1 * sn[2 * w + 1]);
-        rb[w] = pack_bf16x2(b0 * cs[2 * w] + a0 * sn[2 * w], b1 * cs[2 * w + 1] + a1 * sn[2 * w + 1]);
+        constexpr int DT = DtOf<TE>::value == DT_F16 ? DT_F16 : DT_BF16;
+        const float a0 = lo_f32<DT>(va[w]), a1 = hi_f32<DT>(va[w]);
+        const float b0 = lo_f32<DT>(vb[w]), b1 = hi_f32<DT>(vb[w]);
+        ra[w] = pack2<DT>(a0 * cs[2 * w] - b0 * sn[2 * w], a1 * cs[2 * w + 1] - b1 * sn[2 * w + 1]);
+        rb[w] = pack2<DT>(b0 * cs[2 * w] + a0 * sn[2 * w], b1 * cs[2 * w + 1] + a1 * sn[2 * w + 1]);
       }
       *reinterpret_cast<u32x4_t *>(pa) = ra;
       *reinterpret_cast<u32x4_t *>(pb) = rb;

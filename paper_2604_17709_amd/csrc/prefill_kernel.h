@@ -98,7 +98,8 @@ struct PfShared {
 // POST = true: bias and activation of the non-GLU MLP sub-layer on the fp32 accumulators.
 // SPLIT = true: this workgroup multiplies only its part of the k range and stores the fp32
 // accumulators to a partial buffer (the sum and the epilogue are a second, small kernel's).
-template <int MF, bool GLU, bool POST = false, bool SPLIT = false>
+// DT = storage type of weights, activations and outputs (DT_BF16 or DT_F16).
+template <int DT, int MF, bool GLU, bool POST = false, bool SPLIT = false>
 __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -250,7 +251,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       for (int j = 0; j < 4; ++j) {
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a0[i]), as_bf16x8(b[j]), acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma32<DT>(a0[i], b[j], acc[i][j]);
           __builtin_amdgcn_sched_barrier(0);
           if (F2 && i == 0 && H1 + j < LPS) fetch_part(st + 2, H1 + j);
           if (i == 1 || MB == 1) b[(j + 2) & 3] = read_bg(j + 2);
@@ -285,7 +286,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       for (int j = 0; j < 4; ++j) {
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a1[i]), as_bf16x8(b[j]), acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma32<DT>(a1[i], b[j], acc[i][j]);
           __builtin_amdgcn_sched_barrier(0);
           if (F3 && i == 0 && j < H1) fetch_part(st + 3, j);
           if (i == 1 || MB == 1) b[(j + 2) & 3] = read_bg(j + 6);
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
         const int f0 = (fb * BF_TILES + wf_e * MF) * 16 + 32 * i + 8 * g + 4 * (lane_e >> 5);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (f0 + e < Q.width) b[e] = bf16_to_f32(Q.bias[f0 + e]);
+          if (f0 + e < Q.width) b[e] = cvt_in<DT>(Q.bias[f0 + e]);
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -355,8 +356,8 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = act_f32(v[e] + b[e], Q.post_act);
         }
-        pk[i][j][g].x = pack_bf16x2(v[0], v[1]);
-        pk[i][j][g].y = pack_bf16x2(v[2], v[3]);
+        pk[i][j][g].x = pack2<DT>(v[0], v[1]);
+        pk[i][j][g].y = pack2<DT>(v[2], v[3]);
       }
     }
   __syncthreads();         // the epilogue reuses the LDS buffers
@@ -421,9 +422,9 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     u32x4_t r;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float h0 = silu_f32(__uint_as_float(g[w] << 16)) * __uint_as_float(u[w] << 16);
-      const float h1 = silu_f32(__uint_as_float(g[w] & 0xffff0000u)) * __uint_as_float(u[w] & 0xffff0000u);
-      r[w] = pack_bf16x2(h0, h1);
+      const float h0 = silu_f32(lo_f32<DT>(g[w])) * lo_f32<DT>(u[w]);
+      const float h1 = silu_f32(hi_f32<DT>(g[w])) * hi_f32<DT>(u[w]);
+      r[w] = pack2<DT>(h0, h1);
     }
     return r;
   };
@@ -472,7 +473,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       for (int e = 0; e < 8; ++e) {
         if (col + e >= width) break;
         unsigned v = (d[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
-        if (GLU) v = f32_to_bf16(silu_f32(bf16_to_f32(o[e])) * __uint_as_float(v << 16));
+        if (GLU) v = cvt_out<DT>(silu_f32(cvt_in<DT>(o[e])) * cvt_in<DT>((uint16_t)v));
         o[e] = (uint16_t)v;
       }
     }

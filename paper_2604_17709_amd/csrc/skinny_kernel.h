@@ -71,7 +71,8 @@ struct SkParams {
 
 // NB = 32-token blocks (1, 2 or 4); KBS = k-blocks per stage (4, or 2: half the slab, so that two
 // workgroups fit a compute unit also with 128 tokens)
-template <int NB, int KBS>
+// DT = storage type of weights and activations (DT_BF16 or DT_F16)
+template <int DT, int NB, int KBS>
 __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   constexpr int XROW = KBS * 64;          // bytes per token row of a stage's activation slab
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P)
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
         __builtin_amdgcn_sched_barrier(0);
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(w[step]), as_bf16x8(b[step % (DEPTH + 1)][j]), acc[j], 0, 0, 0);
+        acc[j] = mfma32<DT>(w[step], b[step % (DEPTH + 1)][j], acc[j]);
         __builtin_amdgcn_sched_barrier(0);
         if (step + DEPTH < STEPS) b[(step + DEPTH) % (DEPTH + 1)][j] = read_b(buf, step + DEPTH, j);
         const int pos = step * NB + j;
@@ -288,6 +289,7 @@ struct SkReduceParams {
 };
 
 // one thread = 8 consecutive columns of one token row
+template <int DT>
 __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkReduceParams R) {
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
   const int c8 = R.F / 8;
@@ -346,9 +348,9 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkReduceParams
   if (R.glu_delta <= 0 && (R.bias != nullptr || R.act != ACT_NONE)) {
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      v[e] = act_f32(v[e] + ((R.bias != nullptr && oc + e < o.width) ? bf16_to_f32(R.bias[oc + e]) : 0.f), R.act);
+      v[e] = act_f32(v[e] + ((R.bias != nullptr && oc + e < o.width) ? cvt_in<DT>(R.bias[oc + e]) : 0.f), R.act);
   }
-  const u32x4_t pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+  const u32x4_t pk = {pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]), pack2<DT>(v[4], v[5]), pack2<DT>(v[6], v[7])};
   uint16_t *dst = o.out + (long long)tok * o.ldo + oc;
   if (oc + 8 <= o.width && ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0)) {
     *reinterpret_cast<u32x4_t *>(dst) = pk;

@@ -54,7 +54,7 @@ struct StParams {
 };
 
 // NB = 32-token blocks (1 or 2)
-template <int NB>
+template <int DT, int NB>
 __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   constexpr int ST_SKB = 2 / NB;                                    // k-blocks per slot: 16 KiB of slab per wavefront
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P)
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
           const u32x4_t b = *reinterpret_cast<const u32x4_t *>(slab0 + buf * SLAB + (kbi * NB * 32 + 32 * j + b_row) * 64 + slot16);
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(w[kbi * 2 + ks]), as_bf16x8(b), acc[j], 0, 0, 0);
+          acc[j] = mfma32<DT>(w[kbi * 2 + ks], b, acc[j]);
         }
       }
   };
@@ -202,12 +202,12 @@ __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P)
     if (!P.glu && (P.bias != nullptr || P.act != ACT_NONE)) {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        v[e] = act_f32(v[e] + ((P.bias != nullptr && col + e < O.width) ? bf16_to_f32(P.bias[col + e]) : 0.f), P.act);
+        v[e] = act_f32(v[e] + ((P.bias != nullptr && col + e < O.width) ? cvt_in<DT>(P.bias[col + e]) : 0.f), P.act);
     }
     if (tok < P.T && col < O.width) {
       uint2 pk;
-      pk.x = pack_bf16x2(v[0], v[1]);
-      pk.y = pack_bf16x2(v[2], v[3]);
+      pk.x = pack2<DT>(v[0], v[1]);
+      pk.y = pack2<DT>(v[2], v[3]);
       uint16_t *dst = O.out + (long long)tok * O.ldo + col;
       if (col + 4 <= O.width && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
         *reinterpret_cast<uint2 *>(dst) = pk;

@@ -94,8 +94,8 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 @dataclass
 class Tensor:
     """A generated tensor: ``bits`` is what goes to the GPU (float32 array, or uint16
-    bf16 patterns); ``values`` are the same numbers as exact float32."""
-    dtype: str          # "f32" | "bf16"
+    bf16 / fp16 patterns); ``values`` are the same numbers as exact float32."""
+    dtype: str          # "f32" | "bf16" | "f16"
     bits: np.ndarray
     values: np.ndarray
 
@@ -124,6 +124,9 @@ def store(v: np.ndarray, dtype: str) -> Tensor:
     if dtype == "bf16":
         b = f32_to_bf16_bits(v)
         return Tensor("bf16", b, bf16_bits_to_f32(b).reshape(v.shape))
+    if dtype == "f16":
+        h = v.astype(np.float16)                     # round to nearest even (storage rounding, no arithmetic of the method)
+        return Tensor("f16", h.view(np.uint16), h.astype(np.float32))
     raise ValueError(dtype)
 
 

@@ -4,14 +4,15 @@ import numpy as np
 
 import synth_inputs as si
 
-TOL = {"bf16": 1e-2, "f32": 1e-5}
+# bf16 and fp32: the stated bars; fp16: the bf16 bar scaled by the ratio of the unit roundoffs (2^-11 / 2^-8), rounded up
+TOL = {"bf16": 1e-2, "f16": 2e-3, "f32": 1e-5}
 
 
 def to_dev(t: si.Tensor):
     import torch
     if t.dtype == "f32":
         return torch.from_numpy(np.ascontiguousarray(t.bits)).cuda()
-    return torch.from_numpy(np.ascontiguousarray(t.bits).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(t.bits).view(np.int16)).cuda().view(torch.float16 if t.dtype == "f16" else torch.bfloat16)
 
 
 def to_host(y) -> np.ndarray:

@@ -78,7 +78,7 @@ def test_linear_argument_validation():
     assert "needed" in dn.last_error()
     assert _linear(make(), ws=FAKE + 0x400010) == dn.ERR_MISALIGNED
     assert _linear(make(U=FAKE + 1)) == dn.ERR_MISALIGNED
-    assert _linear(make(dtype=dn.F32, layout=dn.LAYOUT_PACKED)) == dn.ERR_UNSUPPORTED   # packed is bf16 only
+    assert _linear(make(dtype=dn.F32, layout=dn.LAYOUT_PACKED)) == dn.ERR_UNSUPPORTED   # packed holds 16-bit types only
     assert _linear(make(layout=dn.LAYOUT_PACKED), x=FAKE + 0x200002) == dn.ERR_MISALIGNED
     assert _linear(make(layout=dn.LAYOUT_PACKED, d_in=60), ldx=60) == dn.ERR_MISALIGNED   # d_in % 8
     assert _linear(make(layout=dn.LAYOUT_PACKED), ldx=68) == dn.ERR_MISALIGNED           # ldx % 8

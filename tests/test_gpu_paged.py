@@ -75,6 +75,8 @@ def test_copy_skips_runs_that_point_outside(dn):
     ("bf16", 130, 8, 128, 8, 500000.0),
     ("bf16", 5, 2, 20, 3, 10000.0),          # half = 10: a full group of 8 pair indices and a ragged one, unaligned rows
     ("f32", 33, 2, 64, 4, 10000.0),
+    ("f16", 130, 8, 128, 8, 10000.0),
+    ("f16", 5, 2, 20, 3, 10000.0),
 ])
 def test_rope_matches_oracle(dn, dtype, T, H, D, extra, theta):
     import torch

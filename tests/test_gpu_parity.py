@@ -41,7 +41,7 @@ def test_single_linear_fp32(dn):
     assert max_err(to_host(y), ref) <= TOL["f32"]
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("T,d_in,r,d_out", [(1, 7, 3, 5), (5, 33, 9, 17), (70, 130, 65, 129), (64, 64, 1, 64)])
 def test_linear_raw_odd_shapes(dn, dtype, T, d_in, r, d_out):
     x, U, V = gen(3, T, d_in, r, d_out, dtype)

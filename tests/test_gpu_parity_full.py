@@ -21,10 +21,10 @@ pytestmark = pytest.mark.gpu
 _cache = {}
 
 
-def block(dn, name, seed):
+def block(dn, name, seed, dtype="bf16"):
     """Packed device weights + fp64 host weights of one benchmark block (cached per module)."""
     import torch
-    key = (name, seed)
+    key = (name, seed, dtype)
     if key not in _cache:
         _cache.clear()                          # one block at a time: bounded host / device memory
         shape = si.BLOCKS[name]
@@ -38,8 +38,8 @@ def block(dn, name, seed):
             if p not in proj:
                 continue
             m, n = proj[p]
-            U = si.make(seed, 16 + 2 * i, (m, ranks[p]), shape.weight_std, "bf16")
-            V = si.make(seed, 17 + 2 * i, (ranks[p], n), shape.weight_std, "bf16")
+            U = si.make(seed, 16 + 2 * i, (m, ranks[p]), shape.weight_std, dtype)
+            V = si.make(seed, 17 + 2 * i, (ranks[p], n), shape.weight_std, dtype)
             P[p] = dn.deinfer_pack_factors(dn.raw_pair(to_dev(U), to_dev(V)))
             torch.cuda.synchronize()
             H[p] = (U.values.astype(np.float64), V.values.astype(np.float64))
@@ -71,41 +71,42 @@ def sample_rows(T, limit):
     return rows
 
 
-def activations(seed, stream, T, width, rows):
+def activations(seed, stream, T, width, rows, dtype="bf16"):
     """Device tensor [T x width] whose `rows` are the seeded rows; returns (device, host rows)."""
     import torch
-    sub = si.make_rows(seed, stream, rows, width, 1.0, "bf16")
+    sub = si.make_rows(seed, stream, rows, width, 1.0, dtype)
     if len(rows) == T:
         return to_dev(sub), sub.values.astype(np.float64)
     g = torch.Generator(device="cuda")
     g.manual_seed(1000 * seed + stream)
-    full = torch.randn((T, width), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    full = torch.randn((T, width), generator=g, device="cuda", dtype=torch.float32).to(torch.float16 if dtype == "f16" else torch.bfloat16)
     full[torch.tensor(rows, device="cuda")] = to_dev(sub)
     return full, sub.values.astype(np.float64)
 
 
-def run_block(dn, name, T, seed, row_limit):
+def run_block(dn, name, T, seed, row_limit, dtype="bf16"):
     import torch
-    shape, proj, ranks, P, H = block(dn, name, seed)
+    tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+    shape, proj, ranks, P, H = block(dn, name, seed, dtype)
     rows = list(range(T)) if T <= row_limit else sample_rows(T, row_limit)
-    xd, xh = activations(seed, 1, T, shape.hidden, rows)
-    ad, ah = activations(seed, 2, T, shape.hidden, rows)
-    hd, hh = activations(seed, 3, T, shape.ffn, rows)
+    xd, xh = activations(seed, 1, T, shape.hidden, rows, dtype)
+    ad, ah = activations(seed, 2, T, shape.hidden, rows, dtype)
+    hd, hh = activations(seed, 3, T, shape.ffn, rows, dtype)
     nbytes = max(dn.deinfer_workspace_bytes(T, [P["q"], P["k"], P["v"]]),
                  dn.deinfer_workspace_bytes(T, [P["o"]]),
                  dn.deinfer_workspace_bytes(T, [P["gate"], P["up"]] if shape.glu else [P["gate"]]),
                  dn.deinfer_workspace_bytes(T, [P["down"]]))
     ws = dn.Workspace(nbytes)
-    tk = torch.zeros((T, ranks["k"]), dtype=torch.bfloat16, device="cuda")
-    tv = torch.zeros((T, ranks["v"]), dtype=torch.bfloat16, device="cuda")
+    tk = torch.zeros((T, ranks["k"]), dtype=tdt, device="cuda")
+    tv = torch.zeros((T, ranks["v"]), dtype=tdt, device="cuda")
     q, k, v = dn.deinfer_lowrank_qkv(xd, P["q"], P["k"], P["v"], ws, t_k=tk, t_v=tv)
     o = dn.deinfer_lowrank_linear(ad, P["o"], ws)
     if shape.glu:
         h = dn.deinfer_lowrank_gateup_silu(xd, P["gate"], P["up"], ws)
         y = dn.deinfer_lowrank_down(hd, P["down"], ws)
     else:       # non-GLU MLP: act(x U1 V1 + b1), then the second pair with its bias
-        b1 = si.make(seed, 4, (1, shape.ffn), shape.weight_std, "bf16")
-        b2 = si.make(seed, 5, (1, shape.hidden), shape.weight_std, "bf16")
+        b1 = si.make(seed, 4, (1, shape.ffn), shape.weight_std, dtype)
+        b2 = si.make(seed, 5, (1, shape.hidden), shape.weight_std, dtype)
         h = dn.deinfer_lowrank_linear_act(xd, P["gate"], ws, bias=to_dev(b1).reshape(-1), act=dn.ACT_RELU)
         y = dn.deinfer_lowrank_linear_act(hd, P["down"], ws, bias=to_dev(b2).reshape(-1), act=dn.ACT_NONE)
     ws.check()
@@ -119,7 +120,7 @@ def run_block(dn, name, T, seed, row_limit):
                   oracle.lowrank_linear_act(hh, *H["down"], b2.values.reshape(-1), oracle.ACT_NONE))}
     errs = {n: max_err(to_host(got[sel]), ref) for n, (got, ref) in refs.items()}
     print(name, "T=%d" % T, "rows=%d" % len(rows), {n: "%.2e" % e for n, e in errs.items()}, flush=True)
-    assert max(errs.values()) <= TOL["bf16"], errs
+    assert max(errs.values()) <= TOL[dtype], errs
     # invariants that hold at any size: finite everywhere, untouched rows stay plausible
     for t in (q, k, v, o, h, y):
         assert bool(torch.isfinite(t.float()).all())
@@ -150,6 +151,12 @@ def test_llama13b_keep60_mixed_8256(dn):
 @pytest.mark.parametrize("T", [64, 4096])
 def test_opt30b_keep60_non_glu(dn, T):
     run_block(dn, "opt30b_keep60", T, seed=5, row_limit=8)
+
+
+@pytest.mark.parametrize("T", [8, 64, 512])
+def test_llama7b_keep60_fp16(dn, T):
+    """The same block with fp16 storage (weights, activations, outputs), fp32 sums."""
+    run_block(dn, "llama7b_keep60", T, seed=6, row_limit=8, dtype="f16")
 
 
 def test_llama7b_keep60_chunk_of_512_tokens(dn):

@@ -33,16 +33,17 @@ def draw(case):
     return T, d_in, ranks, outs
 
 
-@pytest.mark.parametrize("case", range(48))
-def test_random_shapes(dn, case):
+@pytest.mark.parametrize("dtype,case", [("bf16", c) for c in range(48)] + [("f16", c) for c in range(30)])
+def test_random_shapes(dn, dtype, case):
     import torch
+    tdt = torch.float16 if dtype == "f16" else torch.bfloat16
     T, d_in, ranks, outs = draw(case)
-    x = si.make(100 + case, 1, (T, d_in), 1.0, "bf16")
+    x = si.make(100 + case, 1, (T, d_in), 1.0, dtype)
     F, H = [], []
     for i in range(3):
         d_out = outs[0] if i == 1 and case % 3 == 1 else outs[i]        # gate / up share their width
-        U = si.make(100 + case, 10 + 2 * i, (d_in, ranks[i]), 1.0 / np.sqrt(d_in), "bf16")
-        V = si.make(100 + case, 11 + 2 * i, (ranks[i], d_out), 1.0 / np.sqrt(ranks[i]), "bf16")
+        U = si.make(100 + case, 10 + 2 * i, (d_in, ranks[i]), 1.0 / np.sqrt(d_in), dtype)
+        V = si.make(100 + case, 11 + 2 * i, (ranks[i], d_out), 1.0 / np.sqrt(ranks[i]), dtype)
         p, _keep = pair(dn, U, V, packed=True)
         F.append(p); H.append((U.values, V.values))
     xd = to_dev(x)
@@ -50,26 +51,26 @@ def test_random_shapes(dn, case):
     kind = case % 3
     if kind == 0:          # three pairs, rank-space outputs, then the keys rebuilt from t_k
         pad8 = lambda r: (r + 7) // 8 * 8
-        tk = torch.zeros((T, pad8(ranks[1])), dtype=torch.bfloat16, device="cuda")[:, :ranks[1]]
-        tv = torch.zeros((T, ranks[2] + 3), dtype=torch.bfloat16, device="cuda")[:, :ranks[2]]
+        tk = torch.zeros((T, pad8(ranks[1])), dtype=tdt, device="cuda")[:, :ranks[1]]
+        tv = torch.zeros((T, ranks[2] + 3), dtype=tdt, device="cuda")[:, :ranks[2]]
         q, k, v = dn.deinfer_lowrank_qkv(xd, F[0], F[1], F[2], ws, t_k=tk, t_v=tv)
         rq, rk, rv, rtk, rtv = oracle.lowrank_qkv(x.values, *H[0], *H[1], *H[2], return_t=True)
         for got, ref in ((q, rq), (k, rk), (v, rv), (tk, rtk), (tv, rtv)):
-            assert max_err(to_host(got), ref) <= TOL["bf16"]
+            assert max_err(to_host(got), ref) <= TOL[dtype]
         k2 = dn.deinfer_lowrank_up(tk, F[1], ws)
-        assert max_err(to_host(k2), rk) <= TOL["bf16"]
+        assert max_err(to_host(k2), rk) <= TOL[dtype]
     elif kind == 1:        # GLU sub-layer, fused and staged
         h = dn.deinfer_lowrank_gateup_silu(xd, F[0], F[1], ws)
         ref = oracle.lowrank_gateup_silu(x.values, *H[0], *H[1])
-        assert max_err(to_host(h), ref) <= TOL["bf16"]
+        assert max_err(to_host(h), ref) <= TOL[dtype]
         tg, tu = dn.deinfer_lowrank_down_proj(xd, [F[0], F[1]], ws)
         h2 = dn.deinfer_lowrank_up_glu_silu(tg, tu, F[0], F[1], ws)
-        assert max_err(to_host(h2), ref) <= TOL["bf16"]
+        assert max_err(to_host(h2), ref) <= TOL[dtype]
     else:                  # single pair: plain, and with bias and activation
         y = dn.deinfer_lowrank_linear(xd, F[0], ws)
-        assert max_err(to_host(y), oracle.lowrank_linear(x.values, *H[0])) <= TOL["bf16"]
-        b = si.make(100 + case, 40, (1, outs[0]), 0.5, "bf16")
+        assert max_err(to_host(y), oracle.lowrank_linear(x.values, *H[0])) <= TOL[dtype]
+        b = si.make(100 + case, 40, (1, outs[0]), 0.5, dtype)
         act = 1 + case % 2
         ya = dn.deinfer_lowrank_linear_act(xd, F[0], ws, bias=to_dev(b).reshape(-1), act=act)
-        assert max_err(to_host(ya), oracle.lowrank_linear_act(x.values, *H[0], b.values.reshape(-1), act)) <= TOL["bf16"]
+        assert max_err(to_host(ya), oracle.lowrank_linear_act(x.values, *H[0], b.values.reshape(-1), act)) <= TOL[dtype]
     ws.check()
