@@ -20,7 +20,8 @@
  *    enqueued and deinfer_last_error() describes the problem.  Argument validation
  *    happens on the host before any device call.
  *  - T == 0 is a successful no-op.  A pair with r == 0 yields an all-zero output.
- *  - No bias term (the paper's layers carry none).
+ *  - No bias term (the paper's layers carry none), except the optional one of
+ *    deinfer_lowrank_linear_act.
  */
 #ifndef DEINFER_H
 #define DEINFER_H
@@ -127,12 +128,12 @@ int deinfer_probe_mfma_bf16(const void *operands, size_t operand_bytes, int64_t 
 int deinfer_rank_for_ratio(int64_t m, int64_t n, double param_reduction, int64_t *r_out);
 
 /*
- * Packed weight format (the 16-bit types: bf16, fp16).  Weights are static, so they are re-laid once
- * for the matrix cores: each factor is stored transposed ("feature" rows, reduction
+ * Packed weight format (the 16-bit types: bf16, fp16).  Weights are static, so they are
+ * re-laid once for the matrix cores: each factor is stored transposed ("feature" rows, reduction
  * index contiguous), zero-padded (r to a multiple of 32, feature counts to 16,
  * d_in to 32), and cut into 16-feature x 32-k fragments of 1 KiB held in the lane
- * order of the gfx950 16x16x32 MFMA operand (same for bf16 and fp16), fragment (tile, kblock) at
- * ((tile * n_kblocks) + kblock) KiB.  A wavefront then reads one fragment with a
+ * order of the gfx950 16x16x32 MFMA operand (the same for bf16 and fp16), fragment
+ * (tile, kblock) at ((tile * n_kblocks) + kblock) KiB.  A wavefront then reads one fragment with a
  * single fully coalesced 16-byte-per-lane load.  Zero rank rows are exact no-ops.
  *
  * deinfer_packed_bytes: size of the packed image of `raw` (host-only).
