@@ -74,3 +74,36 @@ def test_random_shapes(dn, dtype, case):
         ya = dn.deinfer_lowrank_linear_act(xd, F[0], ws, bias=to_dev(b).reshape(-1), act=act)
         assert max_err(to_host(ya), oracle.lowrank_linear_act(x.values, *H[0], b.values.reshape(-1), act)) <= TOL[dtype]
     ws.check()
+
+
+@pytest.mark.parametrize("dtype,case", [(d, c) for d in ("f32", "bf16", "f16") for c in range(8)])
+def test_random_shapes_raw_layout(dn, dtype, case):
+    """The same through the generic kernels (RAW pairs, any alignment, any width)."""
+    import torch
+    rng = np.random.default_rng(5000 + case)
+    T, d_in = int(rng.integers(1, 150)), int(rng.integers(1, 300))
+    ranks = [int(rng.integers(1, 90)) for _ in range(3)]
+    outs = [int(rng.integers(1, 260)) for _ in range(3)]
+    outs[1] = outs[0]
+    x = si.make(200 + case, 1, (T, d_in), 1.0, dtype)
+    F, H = [], []
+    for i in range(3):
+        U = si.make(200 + case, 10 + 2 * i, (d_in, ranks[i]), 1.0 / np.sqrt(d_in), dtype)
+        V = si.make(200 + case, 11 + 2 * i, (ranks[i], outs[i]), 1.0 / np.sqrt(ranks[i]), dtype)
+        p, _keep = pair(dn, U, V, packed=False)
+        F.append(p); H.append((U.values, V.values))
+    xd = to_dev(x)
+    ws = dn.Workspace(dn.deinfer_workspace_bytes(T, F))
+    q, k, v = dn.deinfer_lowrank_qkv(xd, F[0], F[1], F[2], ws)
+    rq, rk, rv = oracle.lowrank_qkv(x.values, *H[0], *H[1], *H[2])
+    for got, ref in ((q, rq), (k, rk), (v, rv)):
+        assert max_err(to_host(got), ref) <= TOL[dtype]
+    h = dn.deinfer_lowrank_gateup_silu(xd, F[0], F[1], ws)
+    ref = oracle.lowrank_gateup_silu(x.values, *H[0], *H[1])
+    assert max_err(to_host(h), ref) <= TOL[dtype]
+    tg, tu = dn.deinfer_lowrank_down_proj(xd, [F[0], F[1]], ws)
+    h2 = dn.deinfer_lowrank_up_glu_silu(tg, tu, F[0], F[1], ws)
+    assert max_err(to_host(h2), ref) <= TOL[dtype]
+    b = si.make(200 + case, 40, (1, outs[2]), 0.5, dtype)
+    ya = dn.deinfer_lowrank_linear_act(xd, F[2], ws, bias=to_dev(b).reshape(-1), act=2)
+    assert max_err(to_host(ya), oracle.lowrank_linear_act(x.values, *H[2], b.values.reshape(-1), 2)) <= TOL[dtype]
