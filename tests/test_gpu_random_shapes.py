@@ -47,7 +47,8 @@ def test_random_shapes(dn, dtype, case):
         p, _keep = pair(dn, U, V, packed=True)
         F.append(p); H.append((U.values, V.values))
     xd = to_dev(x)
-    ws = dn.Workspace(max(dn.deinfer_workspace_bytes(T, F), dn.deinfer_workspace_bytes(T, F[:2]), dn.deinfer_workspace_bytes(T, F[:1])))
+    ws = dn.Workspace(max(dn.deinfer_workspace_bytes(T, F), dn.deinfer_workspace_bytes(T, F[:2]), dn.deinfer_workspace_bytes(T, F[:1]),
+                          dn.deinfer_workspace_bytes(T, F[1:2])))
     kind = case % 3
     if kind == 0:          # three pairs, rank-space outputs, then the keys rebuilt from t_k
         pad8 = lambda r: (r + 7) // 8 * 8
