@@ -701,13 +701,24 @@ def kv_rebuild(args, L, shape, T):
     cap_runs = (plan.size - dn.KV_PLAN_HEADER) // 3
     B = ctypes.byref
 
-    def run(names=("copy", "up", "rope")):
+    table_d = torch.empty((T, head_dim), dtype=torch.float32, device="cuda")
+
+    def run(names=("copy", "table", "up")):
+        # "up": keys through the projection whose epilogue rotates them, values through the plain one;
+        # "up_plain" + "rope": the keys the other way (projection, then rotation in place), timed for comparison
+        if "table" in names:
+            rc = L.deinfer_rope_table(pos_d.data_ptr(), T, head_dim, 10000.0, table_d.data_ptr(), sh)
+            if rc: raise RuntimeError(dn.last_error())
         for n in ("k", "v"):
             if "copy" in names:
                 rc = L.deinfer_kv_compact_copy(pools[n].data_ptr(), n_pool, block_bytes, plan_d.data_ptr(), cap_runs,
                                                bufs[n].data_ptr(), cap_blocks, sh)
                 if rc: raise RuntimeError(dn.last_error())
-            if "up" in names:
+            if "up" in names and n == "k":
+                rc = L.deinfer_lowrank_up_rope(bufs[n].data_ptr(), T, pitch, B(pairs[n].desc), table_d.data_ptr(), head_dim,
+                                               outs[n].data_ptr(), d_kv, ws.buf.data_ptr(), ws.nbytes, sh)
+                if rc: raise RuntimeError(dn.last_error())
+            elif "up" in names or "up_plain" in names:
                 rc = L.deinfer_lowrank_up(bufs[n].data_ptr(), T, pitch, B(pairs[n].desc), outs[n].data_ptr(), d_kv,
                                           ws.buf.data_ptr(), ws.nbytes, sh)
                 if rc: raise RuntimeError(dn.last_error())
@@ -746,7 +757,7 @@ def kv_rebuild(args, L, shape, T):
             a1.record(stream)
         stream.synchronize()
         return a0.elapsed_time(a1) * 1e-3 / n
-    parts = {n: ev(lambda n=n: run((n,)), 50) for n in ("copy", "up", "rope")}
+    parts = {n: ev(lambda n=n: run((n,)), 50) for n in ("copy", "table", "up", "up_plain", "rope")}
     # the dominant kernel: one upward projection (the GEMM "of large size", bf16 MFMA)
     e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
     with torch.cuda.stream(stream):
@@ -756,7 +767,9 @@ def kv_rebuild(args, L, shape, T):
     tot = 0.0
     for i in range(23):
         with torch.cuda.stream(stream):
-            run(("up",))
+            rc = L.deinfer_lowrank_up_rope(bufs["k"].data_ptr(), T, pitch, B(pairs["k"].desc), table_d.data_ptr(), head_dim,
+                                           outs["k"].data_ptr(), d_kv, ws.buf.data_ptr(), ws.nbytes, sh)
+            if rc: raise RuntimeError(dn.last_error())
         stream.synchronize()
         if i >= 3: tot += e0.elapsed_time(e1)
     L.deinfer_set_profile_events(0, None, None)
@@ -778,15 +791,19 @@ def kv_rebuild(args, L, shape, T):
         "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s T=%d (keys and values of T cached tokens rebuilt from the paged low-rank cache: "
-                               "compacting copy k, v + upward projection k, v + rotary embedding k)" % (args.workload, T),
+                               "compacting copy k, v + table of rotary angles + upward projection k with the rotary "
+                               "embedding in its epilogue + upward projection v)" % (args.workload, T),
                    "ranks": {"k": r, "v": r}, "block_tokens": bt, "sequences": n_seqs, "runs": int(plan[0]),
                    "blocks": n_run_blocks, "launch": "graph"},
         "calls": {"copy_k_v": {"us": round(parts["copy"] * 1e6, 2), "bytes": copy_bytes, "GBs": round(copy_bytes / parts["copy"] / 1e9, 1)},
                   "up_k_v": {"us": round(parts["up"] * 1e6, 2), "flops": 2 * kflops, "TFLOPs": round(2 * kflops / parts["up"] / 1e12, 2)},
-                  "rope_k": {"us": round(parts["rope"] * 1e6, 2), "bytes": rope_bytes, "GBs": round(rope_bytes / parts["rope"] / 1e9, 1)}},
+                  "rope_table": {"us": round(parts["table"] * 1e6, 2)},
+                  "not_in_the_step": {"up_k_v_plain_us": round(parts["up_plain"] * 1e6, 2),
+                                      "rope_k_in_place": {"us": round(parts["rope"] * 1e6, 2), "bytes": rope_bytes,
+                                                          "GBs": round(rope_bytes / parts["rope"] / 1e9, 1)}}},
         "roofline": {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
-                     "kernel": "prefill_kernel kernel (upward projection of one of k, v: deinfer_lowrank_up)",
+                     "kernel": "prefill_kernel kernel (upward projection of k with the rotary epilogue: deinfer_lowrank_up_rope)",
                      "avg_launch_us": round(ksec * 1e6, 2), "algorithmic_flops_per_launch": kflops,
                      "algorithmic_bytes_per_launch": 2 * (r * d_kv + T * r + T * d_kv)},
         "setup_s": round(setup_s, 1),

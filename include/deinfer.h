@@ -308,6 +308,31 @@ int deinfer_rope_inplace(void *x, int64_t T, int64_t ldx, int64_t n_heads, int64
                          const int32_t *positions, double theta, int dtype, void *stream);
 
 /*
+ * Upward projection of keys with the rotary embedding applied on the way out (Sec. 4.3 rebuilds
+ * the keys from k_low_rank and then rotates them; here the rotation is the last step of the
+ * product's kernel, so the rebuilt keys cross HBM once instead of three times):
+ *   deinfer_rope_table:      table[t][i] = cos(a_ti), table[t][head_dim/2 + i] = sin(a_ti),
+ *                            a_ti = positions[t] * theta^(-2 i / head_dim), i < head_dim/2;
+ *                            positions: device int32 [T]; table: device fp32 [T][head_dim],
+ *                            16-byte aligned, owned by the caller (angles in double precision).
+ *   deinfer_lowrank_up_rope: y = rope(t V) with the angles of `table`: the contract of
+ *                            deinfer_lowrank_up, then that of deinfer_rope_inplace with
+ *                            n_heads = d_out / head_dim (head_dim must divide d_out).  The
+ *                            product is rounded to the storage type, rotated in fp32 and rounded
+ *                            again, exactly as the two separate calls do.
+ * PACKED pairs with head_dim = 128, d_out % 128 == 0, T > 128, y 16-byte aligned and
+ * ldy % 8 == 0 rotate inside the product's kernel; every other case writes the product and
+ * rotates it in place with a second launch.  The table depends only on the positions: one table
+ * serves every layer of a step, and as device memory it may change between replays of a graph.
+ * Asynchronous on `stream`, no allocation.
+ */
+int deinfer_rope_table(const int32_t *positions, int64_t T, int64_t head_dim, double theta,
+                       float *table, void *stream);
+int deinfer_lowrank_up_rope(const void *t, int64_t T, int64_t ldt, const deinfer_factors_t *f,
+                            const float *table, int64_t head_dim, void *y, int64_t ldy,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/*
  * MLP second sub-layer (Sec. 4.1): y = (h U_d) V_d with d_in = FFN width.
  * Same contract as deinfer_lowrank_linear.
  */

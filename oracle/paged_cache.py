@@ -103,3 +103,18 @@ def rope(x, positions, n_heads, head_dim, theta=10000.0):
                 y[t, base + i] = a * c - b * s
                 y[t, base + i + half] = b * c + a * s
     return y
+
+
+def rope_table(positions, head_dim, theta=10000.0):
+    """The angles of `rope` as a table, float64 [T, head_dim]: row t holds cos(a_ti) for i < D/2 and
+    then sin(a_ti), a_ti = positions[t] * theta^(-2 i / D).  (The upward projection with a rotary
+    epilogue takes its angles in this form.)"""
+    half = head_dim // 2
+    assert head_dim % 2 == 0
+    tab = np.empty((len(positions), head_dim), dtype=np.float64)
+    for t in range(len(positions)):
+        for i in range(half):
+            ang = float(positions[t]) * theta ** (-2.0 * i / head_dim)
+            tab[t, i] = np.cos(ang)
+            tab[t, half + i] = np.sin(ang)
+    return tab

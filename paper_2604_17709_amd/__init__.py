@@ -58,6 +58,7 @@ EXPORTS = [
     "deinfer_lowrank_down", "deinfer_lowrank_up", "deinfer_lowrank_linear_act",
     "deinfer_lowrank_down_proj", "deinfer_lowrank_up_glu_silu",
     "deinfer_kv_compact_plan", "deinfer_kv_compact_copy", "deinfer_rope_inplace",
+    "deinfer_rope_table", "deinfer_lowrank_up_rope",
 ]
 
 _lib = None
@@ -83,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.deinfer_kv_compact_plan.argtypes = [_ip, _i64, _i64, _ip, _i64, _i64, _i64, _ip, _i64, _ip, _i64, _ip]
         L.deinfer_kv_compact_copy.argtypes = [_vp, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
         L.deinfer_rope_inplace.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, ctypes.c_double, ctypes.c_int, _vp]
+        L.deinfer_rope_table.argtypes = [_vp, _i64, _i64, ctypes.c_double, _vp, _vp]
+        L.deinfer_lowrank_up_rope.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_packed_bytes.argtypes = [FP, ctypes.POINTER(_sz)]
         L.deinfer_pack_factors.argtypes = [FP, _vp, _sz, FP, _vp]
         L.deinfer_workspace_bytes.argtypes = [_i64, ctypes.POINTER(FP), ctypes.c_int, ctypes.POINTER(_sz)]
@@ -374,6 +377,29 @@ def deinfer_lowrank_up(t, pair: Pair, ws: Workspace, out=None, stream=None):
         out = torch.empty((T, pair.d_out), dtype=t.dtype, device=t.device)
     _check(lib().deinfer_lowrank_up(_ptr(t), T, _ld(t), ctypes.byref(pair.desc),
                                     _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
+    return out
+
+
+def deinfer_rope_table(positions_dev, head_dim: int, theta: float = 10000.0, table=None, stream=None):
+    """cos | sin of the rotary angles per token: fp32 [T, head_dim] (cos in the first half of a row)."""
+    import torch
+    T = int(positions_dev.numel())
+    if table is None:
+        table = torch.empty((T, int(head_dim)), dtype=torch.float32, device=positions_dev.device)
+    _check(lib().deinfer_rope_table(_ptr(positions_dev), T, int(head_dim), float(theta), _ptr(table), _stream(stream)))
+    return table
+
+
+def deinfer_lowrank_up_rope(t, pair: Pair, table, ws: Workspace, out=None, stream=None):
+    """y = rope(t V): the upward projection of keys with the rotary embedding of ``table`` applied."""
+    import torch
+    T = _rows(t, "t")
+    if table.dim() != 2 or table.shape[0] < T or not table.is_contiguous() or table.dtype != torch.float32:
+        raise ValueError("table: contiguous float32 [>= T, head_dim] expected")
+    if out is None:
+        out = torch.empty((T, pair.d_out), dtype=t.dtype, device=t.device)
+    _check(lib().deinfer_lowrank_up_rope(_ptr(t), T, _ld(t), ctypes.byref(pair.desc), _ptr(table), int(table.shape[1]),
+                                         _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
     return out
 
 

@@ -78,6 +78,16 @@ __device__ __forceinline__ float act_f32(float z, int act) {
   return z;
 }
 
+// value of the lane 8 further round the same row of 16 lanes (lane ^ 8); every lane of the row must be active
+__device__ __forceinline__ uint32_t across8(uint32_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128 /* row_ror:8 */, 0xf, 0xf, false);
+#else
+  return v;
+#endif
+}
+__device__ __forceinline__ float across8(float v) { return __uint_as_float(across8(__float_as_uint(v))); }
+
 __device__ __forceinline__ bf16x8_t as_bf16x8(const u32x4_t &v) {
   return __builtin_bit_cast(bf16x8_t, v);
 }

@@ -240,6 +240,7 @@ struct Group {
   const void *bias; int act;               // single non-GLU pair only: y = act(product + bias), bias per output feature
   bool down_only;                          // only the downward projections run; every pair hands out its t through t_out
   const void *x2; int64_t ldx2;            // up_only GLU call: rank-space rows of the second (up) pair
+  const float *rope; int64_t rope_dim;     // single up_only pair: rotary embedding of the output from a [T][rope_dim] cos | sin table
   void *ws; size_t ws_bytes; hipStream_t stream;
 };
 
@@ -524,6 +525,27 @@ int run_group(Group gq) {
   }
 
   // ---- dispatch
+  if (gq.rope != nullptr) {
+    // the large-T kernel rotates in its epilogue when one wavefront's 128 features are one head and
+    // its 16-byte stores apply; otherwise the product is written first and rotated in place
+    const bool fused = packed && gq.T > 128 && gq.rope_dim == 128 && gq.f[0]->d_out % 128 == 0 &&
+                       aligned(gq.out[0], 16) && gq.ldo[0] % 8 == 0;
+    if (!fused) {
+      Group plain = gq;
+      plain.rope = nullptr;
+      if (int rc = run_group(plain)) return rc;
+      const int64_t n = gq.T * gq.f[0]->d_out / 2;
+      if (ceil_div(n, (int64_t)256) > INT32_MAX) return fail(DEINFER_ERR_UNSUPPORTED, "up + rope: output too large");
+      by_dtype(dtype, [&](auto tag) {
+        using TE = decltype(tag);
+        hipLaunchKernelGGL((rope_from_table_kernel<TE>), dim3((unsigned)ceil_div(n, (int64_t)256)), dim3(256), 0, gq.stream,
+                           static_cast<TE *>(gq.out[0]), (long long)gq.T, (long long)gq.ldo[0],
+                           (int)(gq.f[0]->d_out / gq.rope_dim), (int)gq.rope_dim, gq.rope);
+        return 0;
+      });
+      return check_launch("rotary embedding from the table");
+    }
+  }
   if (!packed) return by_dtype(dtype, [&](auto tag) { return run_generic<decltype(tag)>(gq); });
   if (gq.T <= 16 && !gq.up_only) return run_decode(gq);
   if (gq.T <= 128) return run_skinny(gq);
@@ -789,6 +811,36 @@ int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_fact
   memset(&g, 0, sizeof(g));
   g.x = t; g.T = T; g.ldx = ldt; g.n = 1; g.f[0] = f; g.out[0] = y; g.ldo[0] = ldy;
   g.glu = false; g.up_only = true; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
+  return run_group(g);
+}
+
+int deinfer_rope_table(const int32_t *positions, int64_t T, int64_t head_dim, double theta, float *table, void *stream) {
+  if (T < 0 || head_dim <= 0 || head_dim % 2 != 0 || head_dim > (1 << 20))
+    return fail(DEINFER_ERR_INVALID_ARG, "rope table: T >= 0 and an even head_dim in (0, 2^20] are required");
+  if (!(theta > 0.0)) return fail(DEINFER_ERR_INVALID_ARG, "rope table: theta must be positive");
+  if (T == 0) return DEINFER_OK;
+  if (!positions || !table) return fail(DEINFER_ERR_INVALID_ARG, "rope table: positions or table is NULL");
+  if (!aligned(positions, 4) || !aligned(table, 16)) return fail(DEINFER_ERR_MISALIGNED, "rope table: the table must be 16-byte aligned");
+  const int64_t n = T * (head_dim / 2);
+  if (ceil_div(n, (int64_t)256) > INT32_MAX) return fail(DEINFER_ERR_UNSUPPORTED, "rope table: too many tokens");
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)ceil_div(n, (int64_t)256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     positions, (long long)T, (int)head_dim, log2(theta), table);
+  return check_launch("rope table");
+}
+
+int deinfer_lowrank_up_rope(const void *t, int64_t T, int64_t ldt, const deinfer_factors_t *f, const float *table,
+                            int64_t head_dim, void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream) {
+  if (!f) return fail(DEINFER_ERR_INVALID_ARG, "factor descriptor is NULL");
+  if (head_dim <= 0 || head_dim % 2 != 0 || head_dim > (1 << 20) || f->d_out % head_dim != 0)
+    return fail(DEINFER_ERR_INVALID_ARG, "up + rope: head_dim must be even, positive and divide d_out");
+  if (T > 0 && !table) return fail(DEINFER_ERR_INVALID_ARG, "up + rope: table is NULL");
+  if (!aligned(table, 16)) return fail(DEINFER_ERR_MISALIGNED, "up + rope: the table must be 16-byte aligned");
+  if (T > INT32_MAX / 2) return fail(DEINFER_ERR_UNSUPPORTED, "up + rope: too many tokens");
+  Group g;
+  memset(&g, 0, sizeof(g));
+  g.x = t; g.T = T; g.ldx = ldt; g.n = 1; g.f[0] = f; g.out[0] = y; g.ldo[0] = ldy;
+  g.glu = false; g.up_only = true; g.rope = table; g.rope_dim = head_dim;
+  g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
   return run_group(g);
 }
 

@@ -105,4 +105,38 @@ __global__ __launch_bounds__(256) void rope_inplace_kernel(TE *x, long long T, l
   }
 }
 
+// cos / sin of the rotary angles of every token: table[t][i] = cos(pos_t theta^(-2 i / D)),
+// table[t][D / 2 + i] = sin(...), i < D / 2 (fp32, angles in double precision).  One thread per
+// (token, i).  The upward projection with a rotary epilogue reads it.
+__global__ __launch_bounds__(256) void rope_table_kernel(const int *positions, long long T, int head_dim, double log2_theta, float *table) {
+  const int half = head_dim / 2;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= T * half) return;
+  const long long tok = idx / half;
+  const int i = (int)(idx - tok * half);
+  const double ang = (double)positions[tok] * exp2(-2.0 * (double)i / (double)head_dim * log2_theta);
+  double s, c;
+  sincos(ang, &s, &c);
+  table[tok * head_dim + i] = (float)c;
+  table[tok * head_dim + half + i] = (float)s;
+}
+
+// Rotary embedding in place from the table (the path of deinfer_lowrank_up_rope where the
+// epilogue of the large-T kernel does not apply).  One thread per (token, head, pair index).
+template <typename TE>
+__global__ __launch_bounds__(256) void rope_from_table_kernel(TE *x, long long T, long long ldx, int n_heads, int head_dim, const float *table) {
+  const int half = head_dim / 2;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= T * n_heads * half) return;
+  const int i = (int)(idx % half);
+  const long long th = idx / half;
+  const int h = (int)(th % n_heads);
+  const long long tok = th / n_heads;
+  const float c = table[tok * head_dim + i], sn = table[tok * head_dim + half + i];
+  TE *pa = x + tok * ldx + (long long)h * head_dim + i, *pb = pa + half;
+  const float a = Elem<TE>::load(pa), b = Elem<TE>::load(pb);
+  Elem<TE>::store(pa, a * c - b * sn);
+  Elem<TE>::store(pb, b * c + a * sn);
+}
+
 }  // namespace deinfer

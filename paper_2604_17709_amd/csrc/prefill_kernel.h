@@ -67,6 +67,7 @@ struct PfProblem {         // one product  act[T x K] . W^T
   int width;               // valid output columns
   const uint16_t *bias;    // POST kernels only: out = act(product + bias[column]); may be null
   int post_act;            // see act_f32
+  const float *rope;       // ROPE kernels only: [T][128] cos | sin of the rotary angles (heads of 128 features)
 };
 
 struct PfParams {
@@ -99,8 +100,12 @@ struct PfShared {
 // SPLIT = true: this workgroup multiplies only its part of the k range and stores the fp32
 // accumulators to a partial buffer (the sum and the epilogue are a second, small kernel's).
 // DT = storage type of weights, activations and outputs (DT_BF16 or DT_F16).
-template <int DT, int MF, bool GLU, bool POST = false, bool SPLIT = false>
+// ROPE = true: rotary embedding of the output (heads of 128 features = one wavefront's features:
+// feature i of a head pairs with feature i + 64 of the same token, both in this wavefront's LDS
+// tile), on the rounded products, cos / sin from a table; the result is rounded once more.
+template <int DT, int MF, bool GLU, bool POST = false, bool SPLIT = false, bool ROPE = false>
 __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
+  static_assert(!(ROPE && (GLU || POST || SPLIT)), "the rotary epilogue goes with a plain product");
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   PfShared<MF> &S = *reinterpret_cast<PfShared<MF> *>(smem_raw);
@@ -360,9 +365,8 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
         pk[i][j][g].y = pack2<DT>(v[2], v[3]);
       }
     }
-  __syncthreads();         // the epilogue reuses the LDS buffers
 
-  // ---- epilogue: through LDS (free by now; the barrier above has passed), so that the global
+  // ---- epilogue: through LDS (free once the barrier below has passed), so that the global
   // stores are 16 bytes per lane and whole contiguous rows per group of lanes (storing straight
   // from the accumulator arrangement, 32 bytes per row and instruction, measured slower).
   // Accumulator element 4 g + e of block (i, j) is feature 32 i + 8 g + 4 (l / 32) + e of token
@@ -402,6 +406,24 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     }
   };
   if (GLU) load_gate(0);
+  // ROPE: this lane's 8 table values per row (cosines for the chunks of a head's first half, sines for
+  // the others; the lane 8 further round the row of 16 lanes holds the other kind), one batch ahead
+  // like the gate values.  All lanes load: the table row is clamped to the last token, never skipped.
+  f32x4_t tab[2][ROPE ? BQ : 1][2];
+  auto load_tab = [&](int bt) {
+    if constexpr (ROPE) {
+      static_assert(!ROPE || CPR == 16, "one wavefront's features are one head of 128");
+#pragma unroll
+      for (int qq = 0; qq < BQ; ++qq) {
+        const int tok = min(tok_base + (bt * BQ + qq) * RPI, P.T - 1);
+        const float *tb = Q.rope + (long long)tok * 128 + (c & 7) * 8 + (c & 8) * 8;
+        tab[bt & 1][qq][0] = *reinterpret_cast<const f32x4_t *>(tb);
+        tab[bt & 1][qq][1] = *reinterpret_cast<const f32x4_t *>(tb + 4);
+      }
+    }
+  };
+  load_tab(0);
+  __syncthreads();         // the epilogue reuses the LDS buffers (the loads above are in flight meanwhile)
 #ifdef DEINFER_PF_TRACE
   unsigned long long es[4];
   es[0] = __builtin_readcyclecounter();
@@ -447,6 +469,26 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       const int q = bt * BQ + qq;
       if (((q * RPI) >> 3) & 1) dd[qq] = u32x4_t{dd[qq][2], dd[qq][3], dd[qq][0], dd[qq][1]};
       if (GLU) dd[qq] = glu(gate[bt & 1][GLU ? qq : 0], dd[qq]);
+      if constexpr (ROPE) {
+        // This lane's chunk c holds features 8 (c % 8) .. + 7 of the first (c < 8) or the second half
+        // of a head, the lane 8 further round its row of 16 lanes holds the other element of each pair
+        // and needs the same 8 angles: lanes c < 8 load the cosines, the others the sines, and the
+        // values cross within the row (all lanes take part: the table row is clamped, not skipped).
+        const f32x4_t m0 = tab[bt & 1][ROPE ? qq : 0][0], m1 = tab[bt & 1][ROPE ? qq : 0][1];
+        const bool first = c < 8;
+        u32x4_t r;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const float mine_l = w < 2 ? m0[2 * w] : m1[2 * w - 4], mine_h = w < 2 ? m0[2 * w + 1] : m1[2 * w - 3];
+          const float othr_l = across8(mine_l), othr_h = across8(mine_h);
+          const uint32_t pw = across8(dd[qq][w]);                      // the partner elements
+          const float cl = first ? mine_l : othr_l, ch = first ? mine_h : othr_h;
+          const float sl = first ? -othr_l : mine_l, sh = first ? -othr_h : mine_h;   // a cos - b sin | b cos + a sin
+          r[w] = pack2<DT>(lo_f32<DT>(dd[qq][w]) * cl + lo_f32<DT>(pw) * sl,
+                           hi_f32<DT>(dd[qq][w]) * ch + hi_f32<DT>(pw) * sh);
+        }
+        dd[qq] = r;
+      }
       if (lane_wide && tok_base + q * RPI < P.T)
         *reinterpret_cast<u32x4_t *>(dst + (long long)(q * RPI) * ldo) = dd[qq];
     }
@@ -455,6 +497,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #pragma unroll
   for (int bt = 0; bt < NBATCH; ++bt) {
     if (GLU && bt + 1 < NBATCH) load_gate(bt + 1);
+    if (ROPE && bt + 1 < NBATCH) load_tab(bt + 1);
     if (bt + 1 < NBATCH) read_batch(bt + 1, d[(bt + 1) & 1]);
     store_batch(bt, d[bt & 1]);
 #ifdef DEINFER_PF_TRACE

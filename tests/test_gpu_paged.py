@@ -207,3 +207,70 @@ def test_rebuild_at_the_benchmark_size(dn):
     t_rows = si.bf16_bits_to_f32(want.reshape(T, pitch)[rows][:, :r]).astype(np.float64)
     ref = pc.rope(oracle.up_projection(t_rows, V.values.astype(np.float64)), pos[rows], H, D)
     assert max_err(to_host(keys[rows]), ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("T,D,theta", [(1, 128, 10000.0), (300, 128, 500000.0), (77, 20, 10000.0)])
+def test_rope_table_matches_oracle(dn, T, D, theta):
+    import torch
+    pos = (si.small_ints(23, 4, T, 0, 100000)).astype(np.int32)
+    pos[0] = 0
+    tab = dn.deinfer_rope_table(torch.from_numpy(pos).cuda(), D, theta)
+    torch.cuda.synchronize()
+    got = tab.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - pc.rope_table(pos, D, theta))) <= 2e-7        # fp32 rounding of values in [-1, 1]
+    assert np.array_equal(got[0], np.r_[np.ones(D // 2), np.zeros(D // 2)])
+
+
+@pytest.mark.parametrize("dtype,packed,T,r,H,D,extra", [
+    ("bf16", True, 300, 72, 3, 128, 0),       # rotation inside the product's kernel: three token blocks, ragged tail
+    ("bf16", True, 1024, 200, 32, 128, 64),   # 16 feature blocks of 256, output pitch wider than the keys
+    ("bf16", True, 129, 8, 1, 128, 0),        # one head: a half-empty feature block
+    ("f16", True, 257, 40, 5, 128, 8),
+    ("bf16", True, 300, 72, 6, 64, 0),        # heads of 64: product, then rotation from the table
+    ("bf16", True, 300, 72, 3, 128, 4),       # output rows not 16-byte aligned: same
+    ("bf16", True, 64, 72, 3, 128, 0),        # T <= 128: same
+    ("bf16", True, 7, 33, 2, 32, 0),
+    ("f16", True, 100, 40, 4, 64, 0),
+    ("f32", False, 150, 19, 2, 24, 3),        # row-major fp32 pairs
+    ("bf16", False, 150, 19, 2, 128, 0),
+])
+def test_up_rope_matches_oracle(dn, dtype, packed, T, r, H, D, extra):
+    """y = rope(t V) in one call, against the oracle's upward projection followed by its rotation,
+    and against the two separate calls of the library (same roundings: close to the last bit)."""
+    import torch
+    d_out = H * D
+    V = si.make(31, 1, (r, d_out), 0.25, dtype)
+    U = si.make(31, 2, (16, r), 0.25, dtype)
+    r8 = max(8, (r + 7) // 8 * 8)
+    t = si.make(31, 3, (T, r8), 1.0, dtype)
+    pos = (si.small_ints(31, 4, T, 0, 8192)).astype(np.int32)
+    pos[0] = 0
+    p, keep = pair(dn, U, V, packed=packed)
+    ws = dn.Workspace(dn.deinfer_workspace_bytes(T, [p]))
+    td = to_dev(t)
+    pos_d = torch.from_numpy(pos).cuda()
+    tab = dn.deinfer_rope_table(pos_d, D, 10000.0)
+    y = torch.full((T, d_out + extra), 3.0, dtype=td.dtype, device="cuda")
+    dn.deinfer_lowrank_up_rope(td[:, :r], p, tab, ws, out=y[:, :d_out])
+    torch.cuda.synchronize()
+    ws.check()
+    ref = pc.rope(oracle.up_projection(t.values[:, :r].astype(np.float64), V.values.astype(np.float64)), pos, H, D)
+    got = to_host(y)
+    assert max_err(got[:, :d_out], ref) <= TOL[dtype]
+    assert np.all(got[:, d_out:] == 3.0)
+    y2 = dn.deinfer_lowrank_up(td[:, :r], p, ws)
+    dn.deinfer_rope_inplace(y2, H, D, pos_d, 10000.0)
+    torch.cuda.synchronize()
+    assert max_err(got[:, :d_out], to_host(y2)) <= (2.0 ** -7 if dtype == "bf16" else 2.0 ** -10 if dtype == "f16" else 1e-6)
+
+
+def test_up_rope_of_a_rank_zero_pair_is_zero(dn):
+    import torch
+    p0 = dn.deinfer_pack_factors(dn.raw_pair(torch.zeros((64, 0), dtype=torch.bfloat16, device="cuda"),
+                                             torch.zeros((0, 256), dtype=torch.bfloat16, device="cuda")))
+    T = 200
+    ws = dn.Workspace(dn.deinfer_workspace_bytes(T, [p0]))
+    tab = dn.deinfer_rope_table(torch.arange(T, dtype=torch.int32, device="cuda"), 128)
+    y = torch.full((T, 256), 7.0, dtype=torch.bfloat16, device="cuda")
+    dn.deinfer_lowrank_up_rope(torch.zeros((T, 8), dtype=torch.bfloat16, device="cuda"), p0, tab, ws, out=y)
+    assert float(y.abs().max()) == 0.0

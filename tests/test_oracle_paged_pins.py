@@ -140,3 +140,24 @@ def test_rope_heads_are_independent_and_pairing_is_half_apart():
         y = pc.rope(x, [3], H, D)
         nz = set(np.nonzero(np.abs(y[0]) > 1e-15)[0])
         assert nz <= {h * D + i, h * D + (i + D // 2) % D}
+
+
+def test_rope_table_is_the_rotation_of_rope():
+    """The table form of the angles: unit rows (cos^2 + sin^2 = 1), position 0 gives (1, 0), pair index 0
+    turns by the position itself, and multiplying (x_i + j x_{i+D/2}) by (cos + j sin) of the table
+    gives what `rope` gives."""
+    H, D = 3, 16
+    pos = np.array([0, 1, 7, 4097, 99999])
+    tab = pc.rope_table(pos, D, theta=500000.0)
+    half = D // 2
+    assert tab.shape == (5, D)
+    assert np.allclose(tab[:, :half] ** 2 + tab[:, half:] ** 2, 1.0, atol=1e-14)
+    assert np.array_equal(tab[0], np.r_[np.ones(half), np.zeros(half)])
+    assert np.allclose(tab[:, 0], np.cos(pos), atol=1e-9) and np.allclose(tab[:, half], np.sin(pos), atol=1e-9)
+    # the last pair index turns by pos / theta^((D - 2) / D)
+    assert np.allclose(tab[:, half - 1], np.cos(pos / 500000.0 ** ((D - 2) / D)), atol=1e-9)
+    x = np.random.default_rng(5).standard_normal((5, H * D))
+    z = x.reshape(5, H, D)[:, :, :half] + 1j * x.reshape(5, H, D)[:, :, half:]
+    w = z * (tab[:, None, :half] + 1j * tab[:, None, half:])
+    y = np.concatenate([w.real, w.imag], axis=2).reshape(5, H * D)
+    assert np.allclose(y, pc.rope(x, pos, H, D, theta=500000.0), atol=1e-12)
