@@ -111,6 +111,32 @@ def test_up_projection_argument_validation():
     assert _up(make(**pk), T=0, ldt=16, t=None, y=None, ws=None, ws_bytes=0) == dn.OK
 
 
+def test_up_rope_argument_validation():
+    """Errors of the rotating upward projection and of its table are found on the host, before any launch."""
+    L = dn.lib()
+    TAB = FAKE + 0x500000
+
+    def up_rope(f, table=TAB, head_dim=16, T=4, t=FAKE + 0x200000, y=FAKE + 0x300000, ws=FAKE + 0x400000):
+        return L.deinfer_lowrank_up_rope(t, T, f.r, ctypes.byref(f), table, head_dim, y, f.d_out, ws, 1 << 26, None)
+
+    assert L.deinfer_lowrank_up_rope(FAKE, 4, 16, None, TAB, 16, FAKE, 48, FAKE, 1 << 20, None) == dn.ERR_INVALID_ARG
+    assert up_rope(make(), head_dim=32) == dn.ERR_INVALID_ARG       # 32 does not divide d_out = 48
+    assert "head_dim" in dn.last_error()
+    assert up_rope(make(), head_dim=3) == dn.ERR_INVALID_ARG        # odd
+    assert up_rope(make(), head_dim=0) == dn.ERR_INVALID_ARG
+    assert up_rope(make(), table=None) == dn.ERR_INVALID_ARG
+    assert up_rope(make(), table=TAB + 4) == dn.ERR_MISALIGNED
+    assert up_rope(make(), t=None) == dn.ERR_INVALID_ARG            # then the contract of the plain upward projection
+    assert up_rope(make(), ws=None) == dn.ERR_WORKSPACE
+    assert up_rope(make(), T=0, table=None) == dn.OK
+    assert L.deinfer_rope_table(FAKE, 4, 7, 10000.0, TAB, None) == dn.ERR_INVALID_ARG
+    assert L.deinfer_rope_table(FAKE, -1, 8, 10000.0, TAB, None) == dn.ERR_INVALID_ARG
+    assert L.deinfer_rope_table(FAKE, 4, 8, 0.0, TAB, None) == dn.ERR_INVALID_ARG
+    assert L.deinfer_rope_table(None, 4, 8, 10000.0, TAB, None) == dn.ERR_INVALID_ARG
+    assert L.deinfer_rope_table(FAKE, 4, 8, 10000.0, TAB + 8, None) == dn.ERR_MISALIGNED
+    assert L.deinfer_rope_table(None, 0, 8, 10000.0, None, None) == dn.OK
+
+
 def test_probe_argument_validation():
     L = dn.lib()
     sink, big = FAKE + 0x500000, dn.PROBE_SINK_BYTES
