@@ -100,6 +100,16 @@ int deinfer_set_profile_events(int which, void *start_event, void *stop_event);
 int deinfer_set_trace_buffer(void *buf, size_t bytes);
 
 /*
+ * Test and measurement aid: the token tile of the compute-bound (T > 128) kernel.  0 (the
+ * default) lets every launch choose: 256-token workgroup tiles, or 128-token tiles while the
+ * 256-token tiles of the launch would occupy at most half of the compute units.  128 or 256
+ * force that tile for every launch that has the choice (launches with a split k range always use
+ * 256).  Results do not depend on the tile: each output element is the same sum taken in the
+ * same order.  Process-wide, not thread-safe.
+ */
+int deinfer_set_prefill_token_tile(int tokens);
+
+/*
  * Measurement aids: what this device delivers on the two rooflines of the path (Sec. 5 reports
  * throughput only; the denominators are this build's), for a benchmark that prints a measured
  * ceiling beside the published one.  Both enqueue one kernel on `stream`, allocate nothing and

@@ -26,6 +26,7 @@ namespace {
 thread_local char g_err[512] = "no error";
 unsigned long long *g_trace = nullptr;   // diagnostic stamp buffer (deinfer_set_trace_buffer)
 size_t g_trace_bytes = 0;
+int g_token_tile = 0;                 // 0: chosen per launch; 128 or 256: forced (test and measurement aid)
 int g_prof_kernel = 0;                   // deinfer_set_profile_events: which internal launch to bracket
 hipEvent_t g_prof_ev[2] = {nullptr, nullptr};
 
@@ -565,6 +566,12 @@ int deinfer_set_profile_events(int which, void *start_event, void *stop_event) {
   g_prof_kernel = (start_event && stop_event) ? which : 0;
   g_prof_ev[0] = static_cast<hipEvent_t>(start_event);
   g_prof_ev[1] = static_cast<hipEvent_t>(stop_event);
+  return DEINFER_OK;
+}
+
+int deinfer_set_prefill_token_tile(int tokens) {
+  if (tokens != 0 && tokens != 128 && tokens != 256) return fail(DEINFER_ERR_INVALID_ARG, "token tile: 0, 128 or 256, got %d", tokens);
+  g_token_tile = tokens;
   return DEINFER_OK;
 }
 

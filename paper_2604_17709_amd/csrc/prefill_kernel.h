@@ -46,7 +46,9 @@ namespace deinfer {
 constexpr int PF_THREADS = 256;
 constexpr int PF_BT = 256;                 // tokens per workgroup tile
 constexpr int PF_BK = 32;                  // k per pipeline stage (one k-block)
-constexpr int PF_STAGES = 4;               // LDS stage buffers
+constexpr int PF_STAGES = 4;               // LDS stage buffers of the 256-token tile
+constexpr int PF_STAGES_TB2 = 6;           // ... of the 128-token tile (half the products per stage: a deeper queue for the same cover)
+constexpr int pf_stages(int tb) { return tb == 4 ? PF_STAGES : PF_STAGES_TB2; }
 constexpr int PF_XPITCH = PF_BK * 2;       // bytes per token row of the activation tile in LDS
 
 struct PfSeg {             // a run of 16-feature tiles that belongs to one factor
@@ -89,10 +91,10 @@ struct PfParams {
 #endif
 };
 
-template <int MF>
+template <int MF, int TB = 4>
 struct PfShared {
-  uint4 w[PF_STAGES][2 * MF][64];                  // [stage][feature tile][lane]
-  unsigned char x[PF_STAGES][PF_BT * PF_XPITCH];   // [stage][token row * 64 bytes], slots swizzled
+  uint4 w[pf_stages(TB)][2 * MF][64];                       // [stage][feature tile][lane]
+  unsigned char x[pf_stages(TB)][64 * TB * PF_XPITCH];      // [stage][token row * 64 bytes], slots swizzled
 };
 
 // GLU = true: the output buffer already holds the gate values g (bf16); store silu(g) * result.
@@ -103,12 +105,19 @@ struct PfShared {
 // ROPE = true: rotary embedding of the output (heads of 128 features = one wavefront's features:
 // feature i of a head pairs with feature i + 64 of the same token, both in this wavefront's LDS
 // tile), on the rounded products, cos / sin from a table; the result is rounded once more.
-template <int DT, int MF, bool GLU, bool POST = false, bool SPLIT = false, bool ROPE = false>
+// TB = 32-token blocks per wavefront: 4 (workgroup tile of 256 tokens) or 2 (128 tokens: twice the
+// workgroups, for launches whose 256-token tiles are fewer than the compute units; its loop keeps a
+// whole k-step of operands ahead instead of the hand-placed reads of the TB = 4 loop).
+template <int DT, int MF, bool GLU, bool POST = false, bool SPLIT = false, bool ROPE = false, int TB = 4>
 __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   static_assert(!(ROPE && (GLU || POST || SPLIT)), "the rotary epilogue goes with a plain product");
+  static_assert(TB == 4 || (TB == 2 && !SPLIT), "token blocks per wavefront");
+  constexpr int WTOK = 32 * TB;                    // tokens per wavefront
+  constexpr int BT = 2 * WTOK;                     // tokens per workgroup tile
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  PfShared<MF> &S = *reinterpret_cast<PfShared<MF> *>(smem_raw);
+  PfShared<MF, TB> &S = *reinterpret_cast<PfShared<MF, TB> *>(smem_raw);
+  constexpr int NST = pf_stages(TB);               // LDS stage buffers; loads run NST - 1 stages ahead
   constexpr int BF_TILES = 2 * MF;                 // 16-feature tiles per workgroup
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wf = wave & 1, wt = wave >> 1;         // wavefront position: features x tokens
@@ -125,7 +134,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   fb -= P.fb0[pi];
   const int kpart = SPLIT ? fb_all / P.n_fblocks : 0;
   const int kb0 = SPLIT ? kpart * P.kb_per_part : 0;          // first k-block of this workgroup
-  const int tok0 = tb * PF_BT;
+  const int tok0 = tb * BT;
 
 #ifdef DEINFER_PF_TRACE
   const unsigned long long w_start = wall_clock64(), k_start = __builtin_readcyclecounter();
@@ -133,11 +142,11 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #endif
   constexpr int MB = MF / 2;                       // 32-feature blocks per wavefront
   static_assert(MF == 8, "the placement of the operand reads in the loop is written for four 32-feature blocks per wavefront");
-  f32x16_t acc[MB][4];                             // [feature block][32-token block]
+  f32x16_t acc[MB][TB];                            // [feature block][32-token block]
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < TB; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
@@ -149,7 +158,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     // beyond a descriptor's size (token rows >= T, feature tiles past the last one) return
     // zeros instead of faulting.  (Host guarantees every tensor here is below 2^31 bytes.)
     constexpr int WT = BF_TILES / 4;       // feature tiles fetched per wavefront and stage
-    constexpr int LPS = WT + 4;            // load instructions per wavefront and stage
+    constexpr int LPS = WT + TB;           // load instructions per wavefront and stage
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
     __amdgpu_buffer_rsrc_t wres[WT];
     unsigned wtile_off[WT];
@@ -172,16 +181,16 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     const __amdgpu_buffer_rsrc_t xres =
         __builtin_amdgcn_make_buffer_rsrc((void *)Q.act, 0, (int)((unsigned)P.T * (unsigned)(Q.lda * 2)), 0x00020000);
     const int chunk = (lane & 3) ^ ((lane >> 4) & 3);
-    unsigned xrow[4];
+    unsigned xrow[TB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) xrow[i] = (unsigned)(tok0 + 16 * (4 * i + wave) + (lane >> 2)) * (unsigned)(Q.lda * 2);
+    for (int i = 0; i < TB; ++i) xrow[i] = (unsigned)(tok0 + 16 * (4 * i + wave) + (lane >> 2)) * (unsigned)(Q.lda * 2);
     const int n_stages = SPLIT ? (Q.KB - kb0 < P.kb_per_part ? Q.KB - kb0 : P.kb_per_part) : Q.KB;
 
     // one load instruction (index 0 .. LPS - 1) of stage st: weight tiles first, then activation rows.
     // Activation chunks beyond K re-read valid columns (k clamped to K - 8), which meet zero weights.
     const unsigned xchunk = (unsigned)(chunk * 16), xklim = (unsigned)(Q.K * 2 - 16);
     auto fetch_part = [&](int st, int idx) {
-      const int buf = st & (PF_STAGES - 1);
+      const int buf = st % NST;
       if (idx < WT) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(wres[idx], (DEINFER_LOCAL void *)&S.w[buf][uwave * WT + idx][0], 16,
                                                  wlane, wtile_off[idx] + (unsigned)(st + kb0) * 1024u, 0, 0);
@@ -198,7 +207,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     // two k-steps of a stage.  In a packed 16-feature fragment that k-group of feature f % 16
     // sits at lane position (f % 16) + 16 * group.
     const int a_off = ((lane >> 4) & 1) * 64 + (lane & 15) + 16 * (lane >> 5);     // in uint4 units
-    const int b_row = wt * 128 + (lane & 31);
+    const int b_row = wt * WTOK + (lane & 31);
     const int b_swz = ((lane & 31) >> 2) & 3;
     auto read_a = [&](int buf, int ib, int ks) -> u32x4_t {
       return *reinterpret_cast<const u32x4_t *>(&S.w[buf][wf * MF + 2 * ib][0] + a_off + 32 * ks);
@@ -215,20 +224,42 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
                                            // load after each group of products, so their issue never holds
                                            // the matrix pipeline up
     static_assert(LPS - H1 <= 4 && H1 <= 4, "one load per token block and k-step");
+    if constexpr (TB == 4) {
 #pragma unroll
-    for (int i = 0; i < LPS; ++i) fetch_part(0, i);
-    if (n_stages > 1) {
+      for (int i = 0; i < LPS; ++i) fetch_part(0, i);
+      if (n_stages > 1) {
 #pragma unroll
-      for (int i = 0; i < LPS; ++i) fetch_part(1, i);
-    }
-    if (n_stages > 2) {
+        for (int i = 0; i < LPS; ++i) fetch_part(1, i);
+      }
+      if (n_stages > 2) {
 #pragma unroll
-      for (int i = 0; i < H1; ++i) fetch_part(2, i);
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS + H1) : "memory");
-    } else if (n_stages > 1) {
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");
+        for (int i = 0; i < H1; ++i) fetch_part(2, i);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS + H1) : "memory");
+      } else if (n_stages > 1) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");
+      } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
     } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      // stages 0 .. D - 2 whole and the first half of stage D - 1, then wait for stage 0
+      constexpr int D = NST - 1;
+      static_assert((D - 2) * LPS + H1 < 64, "the load counter has 6 bits");
+#pragma unroll
+      for (int sg = 0; sg < D - 1; ++sg)
+        if (sg < n_stages) {
+#pragma unroll
+          for (int i = 0; i < LPS; ++i) fetch_part(sg, i);
+        }
+      if (D - 1 < n_stages) {
+#pragma unroll
+        for (int i = 0; i < H1; ++i) fetch_part(D - 1, i);
+      }
+      static_assert(D == 5, "the waits below are written out for a queue of five stages");
+      if (n_stages > 4) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LPS + H1) : "memory");
+      else if (n_stages == 4) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LPS) : "memory");
+      else if (n_stages == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPS) : "memory");
+      else if (n_stages == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();          // stage 0 has landed everywhere
@@ -241,8 +272,9 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     for (int i = 0; i < MB; ++i) a0[i] = read_a(0, i, 0);
     b[0] = read_b(0, 0, 0);
     b[1] = read_b(0, 1, 0);
+    // (TB = 2: b[0..1] are the token operands of k-step 0, b[2..3] those of k-step 1)
     // one stage; F2: the second half of stage st + 2 is still to be requested, F3: stage st + 3 exists
-    auto stage = [&](int st, auto f2, auto f3) {
+    auto stage4 = [&](int st, auto f2, auto f3) {
       constexpr bool F2 = decltype(f2)::value, F3 = decltype(f3)::value;
       const int buf = st & (PF_STAGES - 1);
       const int nbuf = (st + 1) & (PF_STAGES - 1);
@@ -302,13 +334,70 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
         }
       }
     };
+    // TB = 2: the operands of a whole k-step are read while the previous one is multiplied
+    // (MB + TB reads and up to H1 load requests over the MB * TB products of a k-step); loads run
+    // D = NST - 1 stages ahead.  STEADY: stage st + D exists (no conditions in the loop body).
+    auto stage2 = [&](int st, auto steady) {
+      constexpr bool STEADY = decltype(steady)::value;
+      constexpr int D = NST - 1;
+      const int buf = st % NST;
+      const int nbuf = (st + 1) % NST;
+      const bool i2 = STEADY || st + D - 1 < n_stages;     // second half of stage st + D - 1 still to request
+      const bool i3 = STEADY || st + D < n_stages;         // stage st + D exists
+      constexpr int NS = MB * TB;                          // products = slots of a k-step
+      static_assert(TB == 4 || (MB + TB <= NS && LPS - H1 <= NS && H1 <= NS), "slots of a k-step");
+#pragma unroll
+      for (int j = 0; j < TB; ++j) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+          const int slot = j * MB + i;
+          acc[i][j] = mfma32<DT>(a0[i], b[j], acc[i][j]);
+          __builtin_amdgcn_sched_barrier(0);
+          if (slot < MB) a1[slot] = read_a(buf, slot, 1);
+          else if (slot - MB < TB) b[2 + slot - MB] = read_b(buf, slot - MB, 1);
+          if (slot >= NS - (LPS - H1) && i2) fetch_part(st + D - 1, H1 + slot - (NS - (LPS - H1)));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      // stage st + 1 has landed once at most the loads of the stages st + 2 .. st + D - 1 are outstanding
+      if (STEADY) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS) : "memory");
+      } else {
+        const int rem = n_stages - (st + 2);
+        if (rem >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LPS) : "memory");
+        else if (rem == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPS) : "memory");
+        else if (rem == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();          // ... everywhere, and nobody reads the buffer of stage st - 1 any more
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < TB; ++j) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+          const int slot = j * MB + i;
+          acc[i][j] = mfma32<DT>(a1[i], b[2 + j], acc[i][j]);
+          __builtin_amdgcn_sched_barrier(0);
+          if (slot < MB) a0[slot] = read_a(nbuf, slot, 0);
+          else if (slot - MB < TB) b[slot - MB] = read_b(nbuf, slot - MB, 0);
+          if (slot >= NS - H1 && i3) fetch_part(st + D, slot - (NS - H1));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    };
     {
       const std::true_type yes;
       const std::false_type no;
       int st = 0;
-      for (; st + 3 < n_stages; ++st) stage(st, yes, yes);
-      if (st + 2 < n_stages) { stage(st, yes, no); ++st; }
-      for (; st < n_stages; ++st) stage(st, no, no);
+      if constexpr (TB == 4) {
+        for (; st + 3 < n_stages; ++st) stage4(st, yes, yes);
+        if (st + 2 < n_stages) { stage4(st, yes, no); ++st; }
+        for (; st < n_stages; ++st) stage4(st, no, no);
+      } else {
+        for (; st + NST - 1 < n_stages; ++st) stage2(st, yes);
+        for (; st < n_stages; ++st) stage2(st, no);
+      }
     }
 #ifdef DEINFER_PF_TRACE
     c1 = __builtin_readcyclecounter();
@@ -341,7 +430,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     return;
   }
   // accumulators -> bf16 pairs first (registers only): it overlaps the wait for the slowest wavefront
-  uint2 pk[MB][4][4];
+  uint2 pk[MB][TB][4];
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -355,7 +444,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
           if (f0 + e < Q.width) b[e] = cvt_in<DT>(Q.bias[f0 + e]);
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < TB; ++j) {
         float v[4] = {acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
         if (POST) {
 #pragma unroll
@@ -378,8 +467,8 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   constexpr int CPR = 2 * MF;                      // chunks per row
   constexpr int PITCH = CPR * 16;
   constexpr int RPI = 64 / CPR;                    // token rows per store instruction
-  static_assert(4 * 128 * PITCH <= (int)sizeof(PfShared<MF>), "epilogue tile fits the stage buffers");
-  unsigned char *E = smem_raw + wave_e * (128 * PITCH);
+  static_assert(4 * WTOK * PITCH <= (int)sizeof(PfShared<MF, TB>), "epilogue tile fits the stage buffers");
+  unsigned char *E = smem_raw + wave_e * (WTOK * PITCH);
   // this lane's chunk: 8 consecutive features
   const int c = lane_e & (CPR - 1), rsub = lane_e / CPR;
   uint16_t *const out = Q.out;
@@ -388,21 +477,23 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   const int col = (fb * BF_TILES + wf_e * MF) * 16 + c * 8;
   const bool lane_on = col < width;
   const bool wide = col + 8 <= width && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) && (ldo & 7) == 0;
-  const int tok_base = tok0 + wt_e * 128 + rsub;
+  const int tok_base = tok0 + wt_e * WTOK + rsub;
   uint16_t *dst = out + (long long)tok_base * ldo + col;
-  constexpr int NQ = 128 / RPI;                    // store instructions per wavefront
-  constexpr int NBATCH = GLU ? 8 : 4, BQ = NQ / NBATCH;   // ... handled in batches (register budget)
+  constexpr int NQ = WTOK / RPI;                   // store instructions per wavefront
+  constexpr int NBATCH = (GLU ? 8 : 4) * TB / 4, BQ = NQ / NBATCH;   // ... handled in batches (register budget)
   const bool lane_wide = lane_on && wide;
-  // GLU: the gate values of a batch are requested one batch ahead (the first one before the
-  // accumulators go through LDS), so their latency is covered
-  u32x4_t gate[2][GLU ? BQ : 1];
+  // GLU: the gate values of a batch are requested two batches ahead (the first one before the
+  // accumulators go through LDS): one batch of silu and stores is shorter than a loaded device's
+  // memory latency
+  constexpr int GR = 3;                            // gate batches in registers: loads run two batches ahead
+  u32x4_t gate[GR][GLU ? BQ : 1];
   auto load_gate = [&](int bt) {
 #pragma unroll
     for (int qq = 0; qq < BQ; ++qq) {
       const int q = bt * BQ + qq;
-      gate[bt & 1][GLU ? qq : 0] = u32x4_t{0u, 0u, 0u, 0u};
+      gate[bt % GR][GLU ? qq : 0] = u32x4_t{0u, 0u, 0u, 0u};
       if (lane_wide && tok_base + q * RPI < P.T)
-        gate[bt & 1][GLU ? qq : 0] = *reinterpret_cast<const u32x4_t *>(dst + (long long)(q * RPI) * ldo);
+        gate[bt % GR][GLU ? qq : 0] = *reinterpret_cast<const u32x4_t *>(dst + (long long)(q * RPI) * ldo);
     }
   };
   if (GLU) load_gate(0);
@@ -434,11 +525,12 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < TB; ++j)
 #pragma unroll
         for (int g = 0; g < 4; ++g)
           *reinterpret_cast<uint2 *>(E + (32 * j + wrow) * PITCH + (((4 * i + g) ^ wswz) * 16) + whalf) = pk[i][j][g];
   }
+  if (GLU && NBATCH > 1) load_gate(1);             // (the packed accumulators have left their registers)
   // h = silu(g) * u on the bf16 values of both products, one rounding of the result
   auto glu = [&](u32x4_t g, u32x4_t u) -> u32x4_t {
     u32x4_t r;
@@ -468,7 +560,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
     for (int qq = 0; qq < BQ; ++qq) {
       const int q = bt * BQ + qq;
       if (((q * RPI) >> 3) & 1) dd[qq] = u32x4_t{dd[qq][2], dd[qq][3], dd[qq][0], dd[qq][1]};
-      if (GLU) dd[qq] = glu(gate[bt & 1][GLU ? qq : 0], dd[qq]);
+      if (GLU) dd[qq] = glu(gate[bt % GR][GLU ? qq : 0], dd[qq]);
       if constexpr (ROPE) {
         // This lane's chunk c holds features 8 (c % 8) .. + 7 of the first (c < 8) or the second half
         // of a head, the lane 8 further round its row of 16 lanes holds the other element of each pair
@@ -496,7 +588,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   read_batch(0, d[0]);
 #pragma unroll
   for (int bt = 0; bt < NBATCH; ++bt) {
-    if (GLU && bt + 1 < NBATCH) load_gate(bt + 1);
+    if (GLU && bt + 2 < NBATCH) load_gate(bt + 2);
     if (ROPE && bt + 1 < NBATCH) load_tab(bt + 1);
     if (bt + 1 < NBATCH) read_batch(bt + 1, d[(bt + 1) & 1]);
     store_batch(bt, d[bt & 1]);

@@ -21,6 +21,15 @@ def dn():
     return dn
 
 
+@pytest.fixture(autouse=True, params=[0, 256], ids=["tiles-auto", "tiles-256"])
+def token_tile(request, dn):
+    """Every test runs with the token tile of the T > 128 kernel chosen per launch (small shapes then
+    take the 128-token tile) and with the 256-token tile forced."""
+    dn.deinfer_set_prefill_token_tile(request.param)
+    yield request.param
+    dn.deinfer_set_prefill_token_tile(0)
+
+
 def pool_bits(seed, n_pool, block_tokens, pitch):
     """Seeded bf16 bit patterns for a whole pool (finite values)."""
     t = si.make(seed, 7, (n_pool * block_tokens, pitch), 1.0, "bf16")

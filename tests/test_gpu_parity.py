@@ -20,6 +20,15 @@ def dn():
     return dn
 
 
+@pytest.fixture(autouse=True, params=[0, 256], ids=["tiles-auto", "tiles-256"])
+def token_tile(request, dn):
+    """Every test runs with the token tile of the T > 128 kernel chosen per launch (small shapes then
+    take the 128-token tile) and with the 256-token tile forced."""
+    dn.deinfer_set_prefill_token_tile(request.param)
+    yield request.param
+    dn.deinfer_set_prefill_token_tile(0)
+
+
 def ws_for(dn, T, pairs):
     return dn.Workspace(dn.deinfer_workspace_bytes(T, pairs))
 
@@ -431,3 +440,46 @@ def test_stages_as_separate_calls(dn, kind, T):
         # the staged GLU call sees bf16 rank-space rows, as the fused call does inside
         h_fused = dn.deinfer_lowrank_gateup_silu(xd, F["g"], F["u"], ws)
         assert max_err(to_host(h), to_host(h_fused)) <= 2.0 ** -6
+
+
+# ------------------------------------------------------------------ the two token tiles of the T > 128 kernel
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("T", [129, 700])
+def test_token_tiles_give_identical_results(dn, dtype, T):
+    """128- and 256-token workgroup tiles take the same sums in the same order: the outputs of every
+    kind of call (grouped, GLU, bias + activation, rank-space outputs) agree bit for bit, and with
+    the oracle within the tolerance.  T = 700: ragged last tile for both (188 and 60 rows)."""
+    import torch
+    d_in = 264
+    x = si.make(61, 1, (T, d_in), 1.0, dtype)
+    shapes = {"q": (70, 384), "k": (24, 128), "v": (41, 72), "g": (100, 600), "u": (90, 600)}
+    F, host = {}, {}
+    for i, (n, (r, d_out)) in enumerate(shapes.items()):
+        U = si.make(61, 10 + 2 * i, (d_in, r), 1.0 / np.sqrt(d_in), dtype)
+        V = si.make(61, 11 + 2 * i, (r, d_out), 1.0 / np.sqrt(r), dtype)
+        F[n], _k = pair(dn, U, V, packed=True)
+        host[n] = (U.values, V.values)
+    xd = to_dev(x)
+    b = si.make(61, 30, (1, 600), 0.5, dtype)
+    ws = dn.Workspace(max(dn.deinfer_workspace_bytes(T, [F["q"], F["k"], F["v"]]),
+                          dn.deinfer_workspace_bytes(T, [F["g"], F["u"]])))
+    res = {}
+    for tile in (128, 256):
+        dn.deinfer_set_prefill_token_tile(tile)
+        tk = torch.zeros((T, 24), dtype=xd.dtype, device="cuda")
+        q, k, v = dn.deinfer_lowrank_qkv(xd, F["q"], F["k"], F["v"], ws, t_k=tk)
+        h = dn.deinfer_lowrank_gateup_silu(xd, F["g"], F["u"], ws)
+        a = dn.deinfer_lowrank_linear_act(xd, F["g"], ws, bias=to_dev(b).reshape(-1), act=dn.ACT_GELU)
+        k2 = dn.deinfer_lowrank_up(tk, F["k"], ws)
+        torch.cuda.synchronize()
+        ws.check()
+        res[tile] = [t.clone() for t in (q, k, v, tk, h, a, k2)]
+    dn.deinfer_set_prefill_token_tile(0)
+    for t128, t256 in zip(res[128], res[256]):
+        assert torch.equal(t128.view(torch.int16), t256.view(torch.int16))
+    q, k, v, tk, h, a, k2 = res[128]
+    rq, rk, rv, rtk, rtv = oracle.lowrank_qkv(x.values, *host["q"], *host["k"], *host["v"], return_t=True)
+    for got, ref in ((q, rq), (k, rk), (v, rv), (tk, rtk)):
+        assert max_err(to_host(got), ref) <= TOL[dtype]
+    assert max_err(to_host(h), oracle.lowrank_gateup_silu(x.values, *host["g"], *host["u"])) <= TOL[dtype]
+    assert max_err(to_host(a), oracle.lowrank_linear_act(x.values, *host["g"], b.values.reshape(-1), oracle.ACT_GELU)) <= TOL[dtype]

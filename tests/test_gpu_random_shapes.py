@@ -23,6 +23,15 @@ def dn():
     return dn
 
 
+@pytest.fixture(autouse=True, params=[0, 256], ids=["tiles-auto", "tiles-256"])
+def token_tile(request, dn):
+    """Every test runs with the token tile of the T > 128 kernel chosen per launch (small shapes then
+    take the 128-token tile) and with the 256-token tile forced."""
+    dn.deinfer_set_prefill_token_tile(request.param)
+    yield request.param
+    dn.deinfer_set_prefill_token_tile(0)
+
+
 def draw(case):
     rng = np.random.default_rng(1000 + case)
     T = int(rng.choice([rng.integers(1, 17), rng.integers(17, 33), rng.integers(33, 129), rng.integers(129, 700)]))
