@@ -480,7 +480,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   const int tok_base = tok0 + wt_e * WTOK + rsub;
   uint16_t *dst = out + (long long)tok_base * ldo + col;
   constexpr int NQ = WTOK / RPI;                   // store instructions per wavefront
-  constexpr int NBATCH = (GLU ? 8 : 4) * TB / 4, BQ = NQ / NBATCH;   // ... handled in batches (register budget)
+  constexpr int NBATCH = ((GLU || ROPE) ? 8 : 4) * TB / 4, BQ = NQ / NBATCH;   // ... handled in batches (register budget)
   const bool lane_wide = lane_on && wide;
   // GLU: the gate values of a batch are requested two batches ahead (the first one before the
   // accumulators go through LDS): one batch of silu and stores is shorter than a loaded device's
@@ -498,9 +498,9 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   };
   if (GLU) load_gate(0);
   // ROPE: this lane's 8 table values per row (cosines for the chunks of a head's first half, sines for
-  // the others; the lane 8 further round the row of 16 lanes holds the other kind), one batch ahead
+  // the others; the lane 8 further round the row of 16 lanes holds the other kind), two batches ahead
   // like the gate values.  All lanes load: the table row is clamped to the last token, never skipped.
-  f32x4_t tab[2][ROPE ? BQ : 1][2];
+  f32x4_t tab[GR][ROPE ? BQ : 1][2];
   auto load_tab = [&](int bt) {
     if constexpr (ROPE) {
       static_assert(!ROPE || CPR == 16, "one wavefront's features are one head of 128");
@@ -508,8 +508,8 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       for (int qq = 0; qq < BQ; ++qq) {
         const int tok = min(tok_base + (bt * BQ + qq) * RPI, P.T - 1);
         const float *tb = Q.rope + (long long)tok * 128 + (c & 7) * 8 + (c & 8) * 8;
-        tab[bt & 1][qq][0] = *reinterpret_cast<const f32x4_t *>(tb);
-        tab[bt & 1][qq][1] = *reinterpret_cast<const f32x4_t *>(tb + 4);
+        tab[bt % GR][qq][0] = *reinterpret_cast<const f32x4_t *>(tb);
+        tab[bt % GR][qq][1] = *reinterpret_cast<const f32x4_t *>(tb + 4);
       }
     }
   };
@@ -531,6 +531,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
           *reinterpret_cast<uint2 *>(E + (32 * j + wrow) * PITCH + (((4 * i + g) ^ wswz) * 16) + whalf) = pk[i][j][g];
   }
   if (GLU && NBATCH > 1) load_gate(1);             // (the packed accumulators have left their registers)
+  if (ROPE && NBATCH > 1) load_tab(1);
   // h = silu(g) * u on the bf16 values of both products, one rounding of the result
   auto glu = [&](u32x4_t g, u32x4_t u) -> u32x4_t {
     u32x4_t r;
@@ -566,7 +567,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
         // of a head, the lane 8 further round its row of 16 lanes holds the other element of each pair
         // and needs the same 8 angles: lanes c < 8 load the cosines, the others the sines, and the
         // values cross within the row (all lanes take part: the table row is clamped, not skipped).
-        const f32x4_t m0 = tab[bt & 1][ROPE ? qq : 0][0], m1 = tab[bt & 1][ROPE ? qq : 0][1];
+        const f32x4_t m0 = tab[bt % GR][ROPE ? qq : 0][0], m1 = tab[bt % GR][ROPE ? qq : 0][1];
         const bool first = c < 8;
         u32x4_t r;
 #pragma unroll
@@ -589,7 +590,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #pragma unroll
   for (int bt = 0; bt < NBATCH; ++bt) {
     if (GLU && bt + 2 < NBATCH) load_gate(bt + 2);
-    if (ROPE && bt + 1 < NBATCH) load_tab(bt + 1);
+    if (ROPE && bt + 2 < NBATCH) load_tab(bt + 2);
     if (bt + 1 < NBATCH) read_batch(bt + 1, d[(bt + 1) & 1]);
     store_batch(bt, d[bt & 1]);
 #ifdef DEINFER_PF_TRACE
