@@ -113,11 +113,12 @@ def _scatter_into_pool(torch, pool, rows, table, n_blocks, block_tokens):
     return start
 
 
-def test_rebuild_keys_from_paged_cache_under_one_graph(dn):
+@pytest.mark.parametrize("H,D,fused", [(4, 64, False), (2, 128, True), (4, 64, True)])
+def test_rebuild_keys_from_paged_cache_under_one_graph(dn, H, D, fused):
     """Preparation stage on the host, then ONE captured graph (copy, upward projection at the
     buffer's capacity, rotary embedding) replayed for two different cache states and back."""
     import torch
-    d_in, r, H, D, bt = 264, 96, 4, 64, 16
+    d_in, r, bt = 264, 96, 16
     d_out = H * D
     n_pool, cap_blocks = 64, 24
     cap_tokens = cap_blocks * bt                                   # 384 tokens: the large-T path
@@ -131,6 +132,7 @@ def test_rebuild_keys_from_paged_cache_under_one_graph(dn):
     keys = torch.zeros((cap_tokens, d_out), dtype=torch.bfloat16, device="cuda")
     plan_d = torch.zeros(dn.KV_PLAN_HEADER + 3 * cap_blocks, dtype=torch.int32, device="cuda")
     pos_d = torch.zeros(cap_tokens, dtype=torch.int32, device="cuda")
+    table_d = torch.zeros((cap_tokens, D), dtype=torch.float32, device="cuda")
 
     prepared = []
     for seed, prompt, decode, recycled in states:
@@ -147,8 +149,12 @@ def test_rebuild_keys_from_paged_cache_under_one_graph(dn):
 
     def enqueue():
         dn.deinfer_kv_compact_copy(pool, bt * r * 2, plan_d, buf, stream=stream)
-        dn.deinfer_lowrank_up(buf, p, ws, out=keys, stream=stream)
-        dn.deinfer_rope_inplace(keys, H, D, pos_d, 10000.0, stream=stream)
+        if fused:      # fused = the table of angles and the projection that rotates (in its epilogue for heads of 128)
+            dn.deinfer_rope_table(pos_d, D, 10000.0, table=table_d, stream=stream)
+            dn.deinfer_lowrank_up_rope(buf, p, table_d, ws, out=keys, stream=stream)
+        else:
+            dn.deinfer_lowrank_up(buf, p, ws, out=keys, stream=stream)
+            dn.deinfer_rope_inplace(keys, H, D, pos_d, 10000.0, stream=stream)
 
     results = []
     for step, idx in enumerate((0, 1, 0)):
@@ -216,6 +222,13 @@ def test_rebuild_at_the_benchmark_size(dn):
     t_rows = si.bf16_bits_to_f32(want.reshape(T, pitch)[rows][:, :r]).astype(np.float64)
     ref = pc.rope(oracle.up_projection(t_rows, V.values.astype(np.float64)), pos[rows], H, D)
     assert max_err(to_host(keys[rows]), ref) <= TOL["bf16"]
+    # the same keys from the projection that rotates in its epilogue
+    keys2 = torch.empty_like(keys)
+    tab = dn.deinfer_rope_table(torch.from_numpy(pos).cuda(), D, 10000.0)
+    dn.deinfer_lowrank_up_rope(buf, p, tab, ws, out=keys2)
+    torch.cuda.synchronize()
+    assert max_err(to_host(keys2[rows]), ref) <= TOL["bf16"]
+    assert float((keys2.float() - keys.float()).abs().max()) <= 2.0 ** -7 * float(keys.float().abs().max())
 
 
 @pytest.mark.parametrize("T,D,theta", [(1, 128, 10000.0), (300, 128, 500000.0), (77, 20, 10000.0)])
