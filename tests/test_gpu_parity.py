@@ -483,3 +483,46 @@ def test_token_tiles_give_identical_results(dn, dtype, T):
         assert max_err(to_host(got), ref) <= TOL[dtype]
     assert max_err(to_host(h), oracle.lowrank_gateup_silu(x.values, *host["g"], *host["u"])) <= TOL[dtype]
     assert max_err(to_host(a), oracle.lowrank_linear_act(x.values, *host["g"], b.values.reshape(-1), oracle.ACT_GELU)) <= TOL[dtype]
+
+
+# ------------------------------------------------------------------ calls in flight on two streams
+@pytest.mark.parametrize("T", [8, 64, 300])
+def test_two_streams_with_their_own_workspaces(dn, T):
+    """The library keeps no device state of its own between calls: two chains of calls enqueued on
+    two streams at once, each with its own workspace, give the bits of the same calls run one
+    after the other."""
+    import torch
+    d_in = 264
+    shapes = {"q": (70, 384), "k": (24, 128), "v": (41, 72), "g": (100, 600), "u": (90, 600)}
+    F = {}
+    keep = []
+    for i, (n, (r, d_out)) in enumerate(shapes.items()):
+        U = si.make(71, 10 + 2 * i, (d_in, r), 1.0 / np.sqrt(d_in), "bf16")
+        V = si.make(71, 11 + 2 * i, (r, d_out), 1.0 / np.sqrt(r), "bf16")
+        F[n], k = pair(dn, U, V, packed=True)
+        keep.append(k)
+    xs = [to_dev(si.make(71, 1 + j, (T, d_in), 1.0, "bf16")) for j in range(2)]
+    nbytes = max(dn.deinfer_workspace_bytes(T, [F["q"], F["k"], F["v"]]), dn.deinfer_workspace_bytes(T, [F["g"], F["u"]]))
+    wss = [dn.Workspace(nbytes) for _ in range(2)]
+
+    def chain(j, stream):
+        out = []
+        for rep in range(3):
+            q, k, v = dn.deinfer_lowrank_qkv(xs[j], F["q"], F["k"], F["v"], wss[j], stream=stream)
+            h = dn.deinfer_lowrank_gateup_silu(xs[j], F["g"], F["u"], wss[j], stream=stream)
+            o = dn.deinfer_lowrank_linear(xs[j], F["q"], wss[j], stream=stream)
+            out = [q, k, v, h, o]
+        return out
+
+    want = [chain(j, None) for j in range(2)]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    got = [None, None]
+    for j in range(2):                      # outputs are allocated under the stream that fills them
+        with torch.cuda.stream(streams[j]):
+            got[j] = chain(j, streams[j])
+    torch.cuda.synchronize()
+    for j in range(2):
+        wss[j].check()
+        for a, b in zip(got[j], want[j]):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16))
