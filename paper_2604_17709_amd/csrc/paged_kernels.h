@@ -10,6 +10,7 @@ namespace deinfer {
 constexpr int KV_PLAN_HEADER = 4;            // int32 words before the (src, dst, length) triples
 constexpr int KV_COPY_THREADS = 256;
 constexpr int KV_PIECE = KV_COPY_THREADS * 4 * 16;   // bytes one workgroup moves per step (16 KiB)
+constexpr int KV_LDS_RUNS = 2048;            // run destinations a workgroup keeps in LDS (8 KiB)
 
 // plan: [0] number of runs, [1] number of blocks (sum of the lengths), then the runs in the order
 // of their destinations, which tile [0, plan[1]) without gaps.  A piece p = (destination block,
@@ -25,12 +26,22 @@ __global__ __launch_bounds__(KV_COPY_THREADS) void kv_compact_copy_kernel(
   if (n_runs <= 0 || nb <= 0) return;
   const int *runs = plan + KV_PLAN_HEADER;
   const long long ppb = (block_bytes + KV_PIECE - 1) / KV_PIECE;
+  if ((long long)blockIdx.x >= nb * ppb) return;
+  // The destinations of the runs go to LDS first (one round trip to memory), so that the bisection
+  // of every piece is a handful of LDS reads and not a chain of dependent global loads; run lists
+  // too long for that are bisected in global memory.
+  __shared__ int dst_of[KV_LDS_RUNS];
+  const bool in_lds = n_runs <= KV_LDS_RUNS;
+  if (in_lds) {
+    for (int i = threadIdx.x; i < n_runs; i += KV_COPY_THREADS) dst_of[i] = runs[3 * i + 1];
+    __syncthreads();
+  }
   for (long long p = blockIdx.x; p < nb * ppb; p += gridDim.x) {
     const long long d = p / ppb, c = p - d * ppb;
     int lo = 0, hi = n_runs - 1;               // last run whose destination is <= d
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
-      if (runs[3 * mid + 1] <= d) lo = mid; else hi = mid - 1;
+      if ((in_lds ? dst_of[mid] : runs[3 * mid + 1]) <= d) lo = mid; else hi = mid - 1;
     }
     const long long src0 = runs[3 * lo], dst0 = runs[3 * lo + 1], len = runs[3 * lo + 2];
     const long long off = d - dst0, src = src0 + off;
