@@ -526,3 +526,29 @@ def test_two_streams_with_their_own_workspaces(dn, T):
         wss[j].check()
         for a, b in zip(got[j], want[j]):
             assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+# ------------------------------------------------------------------ MQA shapes, a rank per layer and per projection
+@pytest.mark.parametrize("T", [4, 64, 300])
+def test_mqa_shapes_and_per_layer_ranks(dn, T):
+    """Multi-query attention (one key / value head of 128 features beside 8 query heads) and a
+    different parameter reduction per layer and per projection (Sec. 4.3: q, k, v may carry
+    different ratios; Table 2 lists per-model settings): ranks from the rule of Sec. 2.1 for six
+    "layers", every call against the oracle."""
+    hidden, head = 1024, 128
+    x = si.make(81, 1, (T, hidden), 1.0, "bf16")
+    xd = to_dev(x)
+    for layer, (rq, rk, rv) in enumerate([(0.2, 0.2, 0.2), (0.4, 0.1, 0.3), (0.6, 0.5, 0.0), (0.8, 0.7, 0.9), (0.3, 0.95, 0.5), (0.5, 0.5, 0.5)]):
+        F, host = [], []
+        for i, (rho, d_out) in enumerate(((rq, hidden), (rk, head), (rv, head))):
+            r = dn.deinfer_rank_for_ratio(hidden, d_out, rho)
+            assert r == oracle.rank_for_keep(hidden, d_out, round((1.0 - rho) * 1000), 1000)
+            U = si.make(81, 10 * layer + 2 * i + 2, (hidden, r), 1.0 / np.sqrt(hidden), "bf16")
+            V = si.make(81, 10 * layer + 2 * i + 3, (r, d_out), 1.0 / np.sqrt(r), "bf16")
+            p, _k = pair(dn, U, V, packed=True)
+            F.append(p); host.append((U.values, V.values))
+        ws = ws_for(dn, T, F)
+        q, k, v = dn.deinfer_lowrank_qkv(xd, F[0], F[1], F[2], ws)
+        rq_, rk_, rv_ = oracle.lowrank_qkv(x.values, *host[0], *host[1], *host[2])
+        for got, ref in ((q, rq_), (k, rk_), (v, rv_)):
+            assert max_err(to_host(got), ref) <= TOL["bf16"]
