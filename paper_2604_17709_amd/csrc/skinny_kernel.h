@@ -54,6 +54,10 @@ struct SkProblem {           // one product  act[T x K] . W^T,  W packed as [til
   int n_ftiles;              // 16-feature tiles
   int group0;                // first feature group of this product in the launch
   int kb_per_part;           // k-blocks per k-range (a multiple of SK_KB)
+  // direct launches only (SkParams::direct): where the product goes
+  uint16_t *out;             // row-major, 16-bit storage type
+  long long ldo;
+  int width;                 // valid output columns
 };
 
 struct SkParams {
@@ -64,6 +68,11 @@ struct SkParams {
   SkProblem prob[3];
   float *part;               // [P][NB * 32][n_groups * 128] fp32
   long long part_stride;     // NB * 32 * n_groups * 128
+  // direct = 1 (only with P = 1, where the rectangle is the whole sum): the workgroup rounds and
+  // stores its outputs itself, out = act(sum + bias[column]), and no reduce launch follows
+  int direct;
+  const uint16_t *bias;      // single product only; may be null
+  int act;                   // see act_f32
 #ifdef DEINFER_SK_TRACE
   unsigned long long *trace; // diagnostic build only: per-workgroup wall-clock stamps (100 MHz), 8 words each
 #endif
@@ -238,7 +247,38 @@ __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P)
   tr_loop = wall_clock64();
 #endif
 
-  // ---- partial result: element 4 q + e of block j is feature 8 q + 4 (l / 32) + e, token 32 j + l % 32
+  // ---- result: element 4 q + e of block j is feature 8 q + 4 (l / 32) + e, token 32 j + l % 32
+  if (P.direct) {
+    const int col0 = fblk * 32 + 4 * (lane >> 5);         // first of this lane's columns for q = 0
+    uint16_t *o = Q.out + (long long)(lane & 31) * Q.ldo;
+    const bool vec = (reinterpret_cast<uintptr_t>(Q.out) & 7u) == 0 && (Q.ldo & 3) == 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int col = col0 + 8 * q;
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (P.bias != nullptr) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (col + e < Q.width) bv[e] = cvt_in<DT>(P.bias[col + e]);
+      }
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        if (32 * j + (lane & 31) >= P.T) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = act_f32(acc[j][4 * q + e] + bv[e], P.act);
+        uint16_t *dst = o + (long long)(32 * j) * Q.ldo + col;
+        if (vec && col + 4 <= Q.width) {
+          *reinterpret_cast<uint2 *>(dst) = uint2{pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3])};
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (col + e < Q.width) dst[e] = cvt_out<DT>(v[e]);
+        }
+      }
+    }
+    return;
+  }
   const long long F = (long long)P.n_groups * SK_FEAT;
   float *dst = P.part + (long long)part * P.part_stride + (long long)(lane & 31) * F +
                (long long)g * SK_FEAT + wave * 32 + 4 * (lane >> 5);

@@ -552,3 +552,42 @@ def test_mqa_shapes_and_per_layer_ranks(dn, T):
         rq_, rk_, rv_ = oracle.lowrank_qkv(x.values, *host[0], *host[1], *host[2])
         for got, ref in ((q, rq_), (k, rk_), (v, rv_)):
             assert max_err(to_host(got), ref) <= TOL["bf16"]
+
+
+# ------------------------------------------------------------------ wide outputs: one k-range, no reduce launch
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("T", [40, 128])
+def test_wide_outputs_stored_by_the_streaming_kernel(dn, dtype, T):
+    """More than 128 groups of 128 output features leave one k-range per group: the streaming
+    kernel of 32 < T <= 128 then rounds and stores the outputs itself (bias, activation, three
+    outputs of different width, a pitch that rules out 8-byte stores, a ragged last group)."""
+    import torch
+    d_in = 72
+    x = si.make(91, 1, (T, d_in), 1.0, dtype)
+    xd = to_dev(x)
+    # single pair with bias and GELU, 16530 outputs (129.1 groups), odd output pitch
+    U = si.make(91, 2, (d_in, 40), 1.0 / np.sqrt(d_in), dtype)
+    V = si.make(91, 3, (40, 16530), 1.0 / np.sqrt(40), dtype)
+    b = si.make(91, 4, (1, 16530), 0.5, dtype)
+    p, keep = pair(dn, U, V, packed=True)
+    ws = ws_for(dn, T, [p])
+    for pitch in (16536, 16531):
+        y = torch.full((T, pitch), 3.0, dtype=xd.dtype, device="cuda")
+        dn.deinfer_lowrank_linear_act(xd, p, ws, bias=to_dev(b).reshape(-1), act=dn.ACT_GELU, out=y[:, :16530])
+        ref = oracle.lowrank_linear_act(x.values, U.values, V.values, b.values.reshape(-1), oracle.ACT_GELU)
+        got = to_host(y)
+        assert max_err(got[:, :16530], ref) <= TOL[dtype]
+        assert np.all(got[:, 16530:] == 3.0)
+    ws.check()
+    # three pairs, 16900 outputs together
+    F, host = [], []
+    for i, (r, d_out) in enumerate(((24, 6000), (9, 5500), (33, 5400))):
+        Ui = si.make(91, 10 + 2 * i, (d_in, r), 1.0 / np.sqrt(d_in), dtype)
+        Vi = si.make(91, 11 + 2 * i, (r, d_out), 1.0 / np.sqrt(r), dtype)
+        pi_, _k = pair(dn, Ui, Vi, packed=True)
+        F.append(pi_); host.append((Ui.values, Vi.values))
+    ws3 = ws_for(dn, T, F)
+    q, k, v = dn.deinfer_lowrank_qkv(xd, F[0], F[1], F[2], ws3)
+    ws3.check()
+    for got, ref in zip((q, k, v), oracle.lowrank_qkv(x.values, *host[0], *host[1], *host[2])):
+        assert max_err(to_host(got), ref) <= TOL[dtype]
