@@ -112,9 +112,9 @@ template <int DT, int MF, bool GLU, bool POST = false, bool SPLIT = false, bool 
 __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   static_assert(!(ROPE && (GLU || POST || SPLIT)), "the rotary epilogue goes with a plain product");
   static_assert(TB == 4 || (TB == 2 && !SPLIT), "token blocks per wavefront");
+#if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   constexpr int WTOK = 32 * TB;                    // tokens per wavefront
   constexpr int BT = 2 * WTOK;                     // tokens per workgroup tile
-#if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   PfShared<MF, TB> &S = *reinterpret_cast<PfShared<MF, TB> *>(smem_raw);
   constexpr int NST = pf_stages(TB);               // LDS stage buffers; loads run NST - 1 stages ahead
