@@ -107,15 +107,21 @@ SkPlan skinny_plan(int64_t T, const deinfer_factors_t *const *f, int n) {
   // about one long-lived workgroup per compute unit of a 256-unit device (each keeps enough loads in
   // flight to stream at its share of the HBM rate; the kernel time barely moves between 128 and 1024
   // workgroups): more k-ranges only add partial-sum traffic
-  // (more than 8 k-ranges were measured slower also for the longest k, where 8 ranges give fewer
-  // workgroups than compute units)
   // Never a few workgroups more than compute units: two workgroups fit a unit, so 258 of them on 256
   // units put two pairs on one unit each, and the launch waits for those (traced: 15.4 us instead of
   // 11.5 us for 86 groups x 3 ranges).  Hence the largest P with groups x P <= 256.
   for (int s = 0; s < 2; ++s) {
     const int target = 256;
     int p = target / (pl.groups[s] > 0 ? pl.groups[s] : 1);
-    pl.P[s] = p < 1 ? 1 : p > 8 ? 8 : p;
+    // more than 8 ranges only for a very long k (first stage of the second MLP layer of the largest
+    // models): every range keeps at least 64 k-blocks (70B shapes, k = 28672, 20 groups: 12 ranges,
+    // 70 -> 65 us at T = 128; the 7B shapes, k = 11008, were slower with more than 8)
+    int cap = 8;
+    if (s == 0) {
+      const int by_k = (int)(ceil_div(f[0]->d_in, 32) / 64);
+      cap = by_k > SK_MAX_PARTS ? SK_MAX_PARTS : by_k > 8 ? by_k : 8;
+    }
+    pl.P[s] = p < 1 ? 1 : p > cap ? cap : p;
   }
   pl.t_bytes = (size_t)round_up((int64_t)pl.NB * 32 * (pl.rtot_pad > 0 ? pl.rtot_pad : 32) * 2, 256);
   const size_t p0 = (size_t)pl.P[0] * pl.NB * 32 * (size_t)pl.groups[0] * SK_FEAT * 4;
