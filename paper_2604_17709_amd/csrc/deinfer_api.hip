@@ -87,32 +87,47 @@ Geometry geometry(const deinfer_factors_t *f) {
 // ---- split of a memory-bound call with 16 < T <= 128 tokens
 struct SkPlan {              // split of one call; a pure function of the shapes (also sizes the workspace)
   int NB;                    // 32-token blocks: 1, 2 or 4
-  int groups[2];             // 128-feature groups of stage 1 / stage 2
+  int NW[2];                 // wavefronts per workgroup = 32-feature blocks per feature group, stage 1 / stage 2
+  int groups[2];             // feature groups of stage 1 / stage 2
   int P[2];                  // k-ranges of stage 1 / stage 2
+  bool direct2;              // stage 2 has one k-range and no GLU: the streaming kernel stores the outputs itself
   int64_t rtot_pad;
   size_t t_bytes, part_bytes;
 };
 
-SkPlan skinny_plan(int64_t T, const deinfer_factors_t *const *f, int n) {
+// A non-GLU second stage with at least this many 128-feature groups takes one k-range although two
+// would fit: the streaming kernel then stores the outputs itself, and the saved reduce launch is worth
+// more than the second half of the compute units (measured with 96 groups: 1-3 us per call faster;
+// with 64-80 groups slower)
+constexpr int SK_DIRECT_MIN_GROUPS = 96;
+#ifndef SK_NARROW_NB_MAX
+#define SK_NARROW_NB_MAX 2      // narrower feature groups only up to this many 32-token blocks
+#endif
+#ifndef SK_NARROW_GAIN_PCT
+#define SK_NARROW_GAIN_PCT 115  // ... and only if they give at least this many percent of the workgroups of the 128-feature split
+#endif
+
+SkPlan skinny_plan(int64_t T, const deinfer_factors_t *const *f, int n, bool glu) {
   SkPlan pl;
   pl.NB = T <= 32 ? 1 : T <= 64 ? 2 : 4;
-  pl.groups[0] = pl.groups[1] = 0;
   pl.rtot_pad = 0;
+  int64_t tiles[2][3] = {{0, 0, 0}, {0, 0, 0}};
   for (int i = 0; i < n; ++i) {
     const Geometry ge = geometry(f[i]);
-    pl.groups[0] += (int)ceil_div(ge.n_rtiles, 8);
-    pl.groups[1] += (int)ceil_div(ge.n_otiles, 8);
+    tiles[0][i] = ge.n_rtiles; tiles[1][i] = ge.n_otiles;
     pl.rtot_pad += ge.r_pad;
   }
-  // about one long-lived workgroup per compute unit of a 256-unit device (each keeps enough loads in
-  // flight to stream at its share of the HBM rate; the kernel time barely moves between 128 and 1024
-  // workgroups): more k-ranges only add partial-sum traffic
-  // Never a few workgroups more than compute units: two workgroups fit a unit, so 258 of them on 256
-  // units put two pairs on one unit each, and the launch waits for those (traced: 15.4 us instead of
-  // 11.5 us for 86 groups x 3 ranges).  Hence the largest P with groups x P <= 256.
+  auto groups_of = [&](int s, int nw) {
+    int g = 0;
+    for (int i = 0; i < n; ++i) g += (int)ceil_div(tiles[s][i], (int64_t)(2 * nw));
+    return g;
+  };
+  // About one long-lived workgroup per compute unit of a 256-unit device, and never a few more: two
+  // workgroups fit a unit, so 258 of them on 256 units put two pairs on one unit each, and the launch
+  // waits for those (traced: 15.4 us instead of 11.5 us for 86 groups x 3 ranges).  Hence the largest
+  // number of k-ranges P with groups x P <= 256.
+  const int target = 256;
   for (int s = 0; s < 2; ++s) {
-    const int target = 256;
-    int p = target / (pl.groups[s] > 0 ? pl.groups[s] : 1);
     // more than 8 ranges only for a very long k (first stage of the second MLP layer of the largest
     // models): every range keeps at least 64 k-blocks (70B shapes, k = 28672, 20 groups: 12 ranges,
     // 70 -> 65 us at T = 128; the 7B shapes, k = 11008, were slower with more than 8)
@@ -121,11 +136,26 @@ SkPlan skinny_plan(int64_t T, const deinfer_factors_t *const *f, int n) {
       const int by_k = (int)(ceil_div(f[0]->d_in, 32) / 64);
       cap = by_k > SK_MAX_PARTS ? SK_MAX_PARTS : by_k > 8 ? by_k : 8;
     }
-    pl.P[s] = p < 1 ? 1 : p > cap ? cap : p;
+    const int g4 = groups_of(s, 4);
+    const bool direct = s == 1 && !glu && (g4 > target / 2 || g4 >= SK_DIRECT_MIN_GROUPS);
+    if (direct) cap = 1;
+    auto ranges = [&](int g) { const int p = target / (g > 0 ? g : 1); return p < 1 ? 1 : p > cap ? cap : p; };
+    // Narrower feature groups (96 or 64 features: 3 or 2 wavefronts per workgroup) give more
+    // workgroups without more k-ranges, i.e. without more partial sums, but one activation slab per
+    // group and stage: taken where they fill clearly more of the device than the 128-feature split
+    int nw = 4, g = g4, p = ranges(g4);
+    if (pl.NB <= SK_NARROW_NB_MAX) {
+      for (int cand = 3; cand >= 2; --cand) {
+        const int gc = groups_of(s, cand), pc = ranges(gc);
+        if (gc * pc <= target && gc * pc * 100 >= g * p * SK_NARROW_GAIN_PCT) { nw = cand; g = gc; p = pc; }
+      }
+    }
+    pl.NW[s] = nw; pl.groups[s] = g; pl.P[s] = p;
+    if (s == 1) pl.direct2 = direct;
   }
   pl.t_bytes = (size_t)round_up((int64_t)pl.NB * 32 * (pl.rtot_pad > 0 ? pl.rtot_pad : 32) * 2, 256);
-  const size_t p0 = (size_t)pl.P[0] * pl.NB * 32 * (size_t)pl.groups[0] * SK_FEAT * 4;
-  const size_t p1 = (size_t)pl.P[1] * pl.NB * 32 * (size_t)pl.groups[1] * SK_FEAT * 4;
+  const size_t p0 = (size_t)pl.P[0] * pl.NB * 32 * (size_t)pl.groups[0] * (32 * pl.NW[0]) * 4;
+  const size_t p1 = (size_t)pl.P[1] * pl.NB * 32 * (size_t)pl.groups[1] * (32 * pl.NW[1]) * 4;
   pl.part_bytes = (size_t)round_up((int64_t)(p0 > p1 ? p0 : p1), 256);
   return pl;
 }
@@ -203,9 +233,11 @@ size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
     if (T > 128) tpre = (size_t)round_up((int64_t)tpre, 256) + prefill_split_plan(T, pairs, n).part_bytes;
     scratch = round_up((int64_t)tdec, 256) + round_up((int64_t)tpre, 256);
     if (T <= 128) {          // (the upward-projection-only call uses this schedule for every T <= 128)
-      const SkPlan pl = skinny_plan(T, pairs, n);
-      const size_t sk = pl.t_bytes + pl.part_bytes;
-      if (sk > scratch) scratch = sk;
+      for (int glu = 0; glu < 2; ++glu) {      // (the call is not known here: room for either kind)
+        const SkPlan pl = skinny_plan(T, pairs, n, glu != 0);
+        const size_t sk = pl.t_bytes + pl.part_bytes;
+        if (sk > scratch) scratch = sk;
+      }
     }
   }
   return WS_HEADER + (size_t)round_up((int64_t)scratch, 256);

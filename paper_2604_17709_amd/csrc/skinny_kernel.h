@@ -39,9 +39,7 @@ namespace deinfer {
 #define DEINFER_LDS_PTR
 #endif
 
-constexpr int SK_THREADS = 256;
 constexpr int SK_KB = 4;                   // k-blocks per stage at most (k-ranges are multiples of it)
-constexpr int SK_FEAT = 128;               // features per workgroup
 constexpr int SK_MAX_PARTS = 16;           // k-ranges per product at most
 constexpr int SK_SLABS = 4;                // activation slabs in LDS = weight register sets
 
@@ -81,8 +79,11 @@ struct SkParams {
 // NB = 32-token blocks (1, 2 or 4); KBS = k-blocks per stage (4, or 2: half the slab, so that two
 // workgroups fit a compute unit also with 128 tokens)
 // DT = storage type of weights and activations (DT_BF16 or DT_F16)
-template <int DT, int NB, int KBS>
-__global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P) {
+// NW = wavefronts per workgroup = 32-feature blocks per feature group (4, 3 or 2): narrower groups
+// give more workgroups without more k-ranges (no extra partial sums) at the price of activation
+// traffic, which one slab per group and stage makes proportional to the number of groups.
+template <int DT, int NB, int KBS, int NW>
+__global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const SkParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   constexpr int XROW = KBS * 64;          // bytes per token row of a stage's activation slab
   constexpr int SPR = KBS * 4;            // 16-byte slots per row = lanes per row of a slab load
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P)
   if (P.n_prob > 1 && g >= P.prob[1].group0) pi = 1;
   if (P.n_prob > 2 && g >= P.prob[2].group0) pi = 2;
   const SkProblem &Q = P.prob[pi];
-  const int fblk = (g - Q.group0) * 4 + wave;          // this wavefront's 32-feature block
+  const int fblk = (g - Q.group0) * NW + wave;         // this wavefront's 32-feature block
   const int kb_begin = part * Q.kb_per_part;
   int kb_end = kb_begin + Q.kb_per_part;
   kb_end = kb_end < Q.KB ? kb_end : Q.KB;
@@ -119,11 +120,16 @@ __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P)
   // ---- activations
   const unsigned xbytes = (unsigned)(((long long)(P.T - 1) * Q.lda + Q.K) * 2);
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void *)Q.act, 0, (int)xbytes, 0x00020000);
-  constexpr int NX = NB * 32 / (4 * RPI);               // slab load instructions per wavefront and stage
+  constexpr int NI = NB * 32 / RPI;                     // slab load instructions per stage
+  constexpr int NX = (NI + NW - 1) / NW;                // ... per wavefront (where NW does not divide NI a wavefront repeats
+                                                        // its previous instruction: every wavefront issues the same number)
   unsigned xrow[NX], xchunk[NX];
+  int xm[NX];
 #pragma unroll
   for (int i = 0; i < NX; ++i) {
-    const int m = i * 4 + wave;                         // instruction m covers rows RPI m .. RPI m + RPI - 1
+    int m = i * NW + wave;                              // instruction m covers rows RPI m .. RPI m + RPI - 1
+    if (m >= NI) m -= NW;
+    xm[i] = m;
     const int row = RPI * m + lane / SPR;
     xrow[i] = row < P.T ? (unsigned)row * (unsigned)(Q.lda * 2) : OOB;
     xchunk[i] = (unsigned)(((lane & (SPR - 1)) ^ (row & (SPR - 1))) * 16);
@@ -138,7 +144,7 @@ __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P)
       // chunks beyond K re-read valid columns (k clamped to K - 8), which meet zero weights
       unsigned kb = kbyte0 + xchunk[i];
       kb = kb < xklim ? kb : xklim;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[buf][(i * 4 + wave) * RPI * XROW], 16,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[buf][xm[i] * RPI * XROW], 16,
                                                (xrow[i] + kb) | dead, 0, 0, 0);
     }
   };
@@ -181,7 +187,7 @@ __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P)
       const unsigned dead = fst < n_stages ? 0u : OOB;
       unsigned kb = (unsigned)(kb_begin + fst * KBS) * 64u + xchunk[i];
       kb = kb < xklim ? kb : xklim;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[fbuf][(i * 4 + wave) * RPI * XROW], 16,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[fbuf][xm[i] * RPI * XROW], 16,
                                                (xrow[i] + kb) | dead, 0, 0, 0);
     }
   };
@@ -279,9 +285,9 @@ __global__ __launch_bounds__(SK_THREADS, 2) void skinny_kernel(const SkParams P)
     }
     return;
   }
-  const long long F = (long long)P.n_groups * SK_FEAT;
+  const long long F = (long long)P.n_groups * (32 * NW);
   float *dst = P.part + (long long)part * P.part_stride + (long long)(lane & 31) * F +
-               (long long)g * SK_FEAT + wave * 32 + 4 * (lane >> 5);
+               (long long)g * (32 * NW) + wave * 32 + 4 * (lane >> 5);
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
     if (32 * j + (lane & 31) < P.T) {
