@@ -4,8 +4,10 @@
 // token rows: every weight is used for T <= 128 tokens, so the weights must stream from HBM
 // exactly once at full rate while the activations (a few hundred KiB) come from L2.
 //
-// Work split: the feature axis is cut into groups of 128 features (4 wavefronts x one
-// 32-feature block), the k axis into P ranges; one workgroup = one (group, k-range) rectangle.
+// Work split: the feature axis is cut into groups of 128, 96 or 64 features (NW = 4, 3 or 2
+// wavefronts x one 32-feature block), the k axis into P ranges; one workgroup = one (group,
+// k-range) rectangle.  The host takes the narrower groups where they fill clearly more of the
+// compute units than the 128-feature split with the same or fewer k-ranges.
 //   * weights: every wavefront loads its own fragments straight into registers (two 16-byte
 //     loads per lane and k-block cover two packed 16-feature fragments, non-temporal: they are
 //     never needed again), one stage (4 k-blocks = 8 KiB per wavefront) ahead of the products;
