@@ -588,7 +588,19 @@ int run_group(Group gq) {
     }
   }
   if (!packed) return by_dtype(dtype, [&](auto tag) { return run_generic<decltype(tag)>(gq); });
-  if (gq.T <= 16 && !gq.up_only) return run_decode(gq);
+  if (gq.T <= 16 && !gq.up_only) {
+    // The kernels of run_decode (one workgroup per 16-feature tile, two launches per call) against the
+    // streaming kernels of run_skinny (feature groups x k-ranges, three or four launches): the former
+    // win for the smaller calls of at most 8 tokens; they lose where their tiles do not fit the device
+    // evenly (more rank tiles than compute units: the units that get two take twice as long) or where
+    // the second stage has thousands of tiles, and everywhere from 9 tokens on.  Measured per call on
+    // 7B-, 70B- and OPT-30B-shaped blocks at 1, 8 and 16 tokens.
+    int64_t rtiles = 0, otiles = 0;
+    for (int i = 0; i < gq.n; ++i) { const Geometry ge = geometry(gq.f[i]); rtiles += ge.n_rtiles; otiles += ge.n_otiles; }
+    const int cus = device_cus();
+    if (cus <= 0) return fail(DEINFER_ERR_DEVICE, "no usable HIP device");
+    if (gq.T <= 8 && rtiles <= cus && otiles <= 4 * cus) return run_decode(gq);
+  }
   if (gq.T <= 128) return run_skinny(gq);
   return run_prefill(gq);
 }
