@@ -1,5 +1,6 @@
-// Memory-bound ("decode") kernels for PACKED bf16 factor pairs; the library uses them for calls
-// of at most 16 tokens (one token tile, NT = 1; the code also covers 2, 4 and 8 tiles).
+// Memory-bound ("decode") kernels for PACKED bf16 factor pairs; the library uses them for the
+// smaller calls of at most 8 tokens (one 16-token tile, NT = 1; the code also covers 2, 4 and 8
+// tiles; the host takes the feature-group kernels of skinny_kernel.h where those are faster).
 //
 // A call is three launches on the caller's stream; kernel boundaries are the only
 // synchronisation (on this part a boundary costs about a microsecond, a software barrier
