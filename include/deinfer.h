@@ -100,14 +100,17 @@ int deinfer_set_profile_events(int which, void *start_event, void *stop_event);
 int deinfer_set_trace_buffer(void *buf, size_t bytes);
 
 /*
- * Test and measurement aid: the token tile of the compute-bound (T > 128) kernel.  0 (the
- * default) lets every launch choose: 256-token workgroup tiles, or 128-token tiles while the
- * 256-token tiles of the launch would occupy at most half of the compute units.  128 or 256
- * force that tile for every launch that has the choice (launches with a split k range always use
- * 256).  Results do not depend on the tile: each output element is the same sum taken in the
- * same order.  Process-wide, not thread-safe.
+ * Test and measurement aid: the workgroup tile of the compute-bound (T > 128) kernel.  0 (the
+ * default) lets every launch choose: 256 tokens x 256 features; 128 x 256 while the larger tiles
+ * of the launch would occupy at most half of the compute units; 128 x 128 while that still
+ * holds for the 128 x 256 tiles.  deinfer_set_prefill_token_tile(128 or 256) forces the token
+ * extent for every launch that has the choice (launches with a split k range always use 256),
+ * deinfer_set_prefill_feature_tile(128 or 256) the feature extent of the 128-token tiles
+ * (launches with the rotary epilogue always use 256).  Results do not depend on the tile: each
+ * output element is the same sum taken in the same order.  Process-wide, not thread-safe.
  */
 int deinfer_set_prefill_token_tile(int tokens);
+int deinfer_set_prefill_feature_tile(int features);
 
 /*
  * Measurement aids: what this device delivers on the two rooflines of the path (Sec. 5 reports

@@ -51,7 +51,7 @@ class DeinferError(RuntimeError):
 
 EXPORTS = [
     "deinfer_last_error", "deinfer_version", "deinfer_set_profile_events", "deinfer_set_trace_buffer",
-    "deinfer_set_prefill_token_tile",
+    "deinfer_set_prefill_token_tile", "deinfer_set_prefill_feature_tile",
     "deinfer_rank_for_ratio", "deinfer_probe_stream_read", "deinfer_probe_mfma_bf16",
     "deinfer_packed_bytes", "deinfer_pack_factors",
     "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
@@ -78,6 +78,7 @@ def lib() -> ctypes.CDLL:
         L.deinfer_version.restype = ctypes.c_int
         L.deinfer_set_trace_buffer.argtypes = [_vp, _sz]
         L.deinfer_set_prefill_token_tile.argtypes = [ctypes.c_int]
+        L.deinfer_set_prefill_feature_tile.argtypes = [ctypes.c_int]
         L.deinfer_set_profile_events.argtypes = [ctypes.c_int, _vp, _vp]
         L.deinfer_rank_for_ratio.argtypes = [_i64, _i64, ctypes.c_double, ctypes.POINTER(_i64)]
         L.deinfer_probe_stream_read.argtypes = [_vp, _sz, _vp, _sz, _vp]
@@ -359,6 +360,11 @@ PROBE_SINK_BYTES = 1 << 20
 def deinfer_set_prefill_token_tile(tokens: int) -> None:
     """Test and measurement aid: 0 = chosen per launch, 128 or 256 = forced token tile of the T > 128 kernel."""
     _check(lib().deinfer_set_prefill_token_tile(int(tokens)))
+
+
+def deinfer_set_prefill_feature_tile(features: int) -> None:
+    """Test and measurement aid: 0 = chosen per launch, 128 or 256 = forced feature extent of the 128-token tiles."""
+    _check(lib().deinfer_set_prefill_feature_tile(int(features)))
 
 
 def deinfer_probe_stream_read(buf, nbytes: int, sink, stream=None) -> None:

@@ -27,6 +27,7 @@ thread_local char g_err[512] = "no error";
 unsigned long long *g_trace = nullptr;   // diagnostic stamp buffer (deinfer_set_trace_buffer)
 size_t g_trace_bytes = 0;
 int g_token_tile = 0;                 // 0: chosen per launch; 128 or 256: forced (test and measurement aid)
+int g_feature_tile = 0;               // 0: chosen per launch; 128 or 256: forced where the token tile is 128
 int g_prof_kernel = 0;                   // deinfer_set_profile_events: which internal launch to bracket
 hipEvent_t g_prof_ev[2] = {nullptr, nullptr};
 
@@ -624,6 +625,12 @@ int deinfer_set_profile_events(int which, void *start_event, void *stop_event) {
 int deinfer_set_prefill_token_tile(int tokens) {
   if (tokens != 0 && tokens != 128 && tokens != 256) return fail(DEINFER_ERR_INVALID_ARG, "token tile: 0, 128 or 256, got %d", tokens);
   g_token_tile = tokens;
+  return DEINFER_OK;
+}
+
+int deinfer_set_prefill_feature_tile(int features) {
+  if (features != 0 && features != 128 && features != 256) return fail(DEINFER_ERR_INVALID_ARG, "feature tile: 0, 128 or 256, got %d", features);
+  g_feature_tile = features;
   return DEINFER_OK;
 }
 

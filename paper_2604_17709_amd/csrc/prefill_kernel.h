@@ -141,7 +141,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   unsigned long long e_start = 0, c_wait_all = 0, c_bar_all = 0;
 #endif
   constexpr int MB = MF / 2;                       // 32-feature blocks per wavefront
-  static_assert(MF == 8, "the placement of the operand reads in the loop is written for four 32-feature blocks per wavefront");
+  static_assert(MF == 8 || (MF == 4 && TB == 2 && !ROPE), "the hand-placed loop of the 256-token tile is written for four 32-feature blocks per wavefront");
   f32x16_t acc[MB][TB];                            // [feature block][32-token block]
 #pragma unroll
   for (int i = 0; i < MB; ++i)

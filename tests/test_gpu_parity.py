@@ -20,13 +20,15 @@ def dn():
     return dn
 
 
-@pytest.fixture(autouse=True, params=[0, 256], ids=["tiles-auto", "tiles-256"])
+@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256)], ids=["tiles-auto", "tiles-256", "tiles-128x256"])
 def token_tile(request, dn):
-    """Every test runs with the token tile of the T > 128 kernel chosen per launch (small shapes then
-    take the 128-token tile) and with the 256-token tile forced."""
-    dn.deinfer_set_prefill_token_tile(request.param)
+    """Every test runs with the workgroup tile of the T > 128 kernel chosen per launch (small shapes then
+    take the 128 x 128 tile), with 256-token tiles forced and with 128 x 256 tiles forced."""
+    dn.deinfer_set_prefill_token_tile(request.param[0])
+    dn.deinfer_set_prefill_feature_tile(request.param[1])
     yield request.param
     dn.deinfer_set_prefill_token_tile(0)
+    dn.deinfer_set_prefill_feature_tile(0)
 
 
 def ws_for(dn, T, pairs):
@@ -446,7 +448,7 @@ def test_stages_as_separate_calls(dn, kind, T):
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("T", [129, 700])
 def test_token_tiles_give_identical_results(dn, dtype, T):
-    """128- and 256-token workgroup tiles take the same sums in the same order: the outputs of every
+    """The three workgroup tiles (256 x 256, 128 x 256, 128 x 128) take the same sums in the same order: the outputs of every
     kind of call (grouped, GLU, bias + activation, rank-space outputs) agree bit for bit, and with
     the oracle within the tolerance.  T = 700: ragged last tile for both (188 and 60 rows)."""
     import torch
@@ -464,8 +466,9 @@ def test_token_tiles_give_identical_results(dn, dtype, T):
     ws = dn.Workspace(max(dn.deinfer_workspace_bytes(T, [F["q"], F["k"], F["v"]]),
                           dn.deinfer_workspace_bytes(T, [F["g"], F["u"]])))
     res = {}
-    for tile in (128, 256):
-        dn.deinfer_set_prefill_token_tile(tile)
+    for tile in (128, 129, 256):                   # 128: 128 x 128 tiles, 129: 128 x 256 tiles
+        dn.deinfer_set_prefill_token_tile(128 if tile == 129 else tile)
+        dn.deinfer_set_prefill_feature_tile(256 if tile == 129 else 128 if tile == 128 else 0)
         tk = torch.zeros((T, 24), dtype=xd.dtype, device="cuda")
         q, k, v = dn.deinfer_lowrank_qkv(xd, F["q"], F["k"], F["v"], ws, t_k=tk)
         h = dn.deinfer_lowrank_gateup_silu(xd, F["g"], F["u"], ws)
@@ -475,8 +478,10 @@ def test_token_tiles_give_identical_results(dn, dtype, T):
         ws.check()
         res[tile] = [t.clone() for t in (q, k, v, tk, h, a, k2)]
     dn.deinfer_set_prefill_token_tile(0)
-    for t128, t256 in zip(res[128], res[256]):
+    dn.deinfer_set_prefill_feature_tile(0)
+    for t128, t129, t256 in zip(res[128], res[129], res[256]):
         assert torch.equal(t128.view(torch.int16), t256.view(torch.int16))
+        assert torch.equal(t129.view(torch.int16), t256.view(torch.int16))
     q, k, v, tk, h, a, k2 = res[128]
     rq, rk, rv, rtk, rtv = oracle.lowrank_qkv(x.values, *host["q"], *host["k"], *host["v"], return_t=True)
     for got, ref in ((q, rq), (k, rk), (v, rv), (tk, rtk)):

@@ -23,13 +23,15 @@ def dn():
     return dn
 
 
-@pytest.fixture(autouse=True, params=[0, 256], ids=["tiles-auto", "tiles-256"])
+@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256)], ids=["tiles-auto", "tiles-256", "tiles-128x256"])
 def token_tile(request, dn):
-    """Every test runs with the token tile of the T > 128 kernel chosen per launch (small shapes then
-    take the 128-token tile) and with the 256-token tile forced."""
-    dn.deinfer_set_prefill_token_tile(request.param)
+    """Every test runs with the workgroup tile of the T > 128 kernel chosen per launch (small shapes then
+    take the 128 x 128 tile), with 256-token tiles forced and with 128 x 256 tiles forced."""
+    dn.deinfer_set_prefill_token_tile(request.param[0])
+    dn.deinfer_set_prefill_feature_tile(request.param[1])
     yield request.param
     dn.deinfer_set_prefill_token_tile(0)
+    dn.deinfer_set_prefill_feature_tile(0)
 
 
 def draw(case):
