@@ -47,8 +47,23 @@ constexpr int PF_THREADS = 256;
 constexpr int PF_BT = 256;                 // tokens per workgroup tile
 constexpr int PF_BK = 32;                  // k per pipeline stage (one k-block)
 constexpr int PF_STAGES = 4;               // LDS stage buffers of the 256-token tile
-constexpr int PF_STAGES_TB2 = 6;           // ... of the 128-token tile (half the products per stage: a deeper queue for the same cover)
-constexpr int pf_stages(int tb) { return tb == 4 ? PF_STAGES : PF_STAGES_TB2; }
+constexpr int PF_STAGES_TB2 = 6;           // ... of the 128 x 256 tile (half the products per stage: a deeper queue for the same cover)
+constexpr int PF_STAGES_MF4 = 6;           // ... of the 128 x 128 tile (four stages, which would let two workgroups share a
+                                           // compute unit, measured 3-7 % slower on launches of 32-128 tiles; eight the same as six)
+constexpr int pf_stages(int tb, int mf = 8) { return tb == 4 ? PF_STAGES : mf == 8 ? PF_STAGES_TB2 : PF_STAGES_MF4; }
+
+// s_waitcnt vmcnt(k * LPS + EXTRA) for a run-time k in [C, CMAX] (the instruction takes an immediate)
+template <int C, int CMAX, int LPS, int EXTRA>
+struct PfVmWait {
+  static __device__ __forceinline__ void run(int k) {
+    if (k == C) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C * LPS + EXTRA) : "memory");
+    else PfVmWait<C + 1, CMAX, LPS, EXTRA>::run(k);
+  }
+};
+template <int CMAX, int LPS, int EXTRA>
+struct PfVmWait<CMAX, CMAX, LPS, EXTRA> {
+  static __device__ __forceinline__ void run(int) { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CMAX * LPS + EXTRA) : "memory"); }
+};
 constexpr int PF_XPITCH = PF_BK * 2;       // bytes per token row of the activation tile in LDS
 
 struct PfSeg {             // a run of 16-feature tiles that belongs to one factor
@@ -93,8 +108,8 @@ struct PfParams {
 
 template <int MF, int TB = 4>
 struct PfShared {
-  uint4 w[pf_stages(TB)][2 * MF][64];                       // [stage][feature tile][lane]
-  unsigned char x[pf_stages(TB)][64 * TB * PF_XPITCH];      // [stage][token row * 64 bytes], slots swizzled
+  uint4 w[pf_stages(TB, MF)][2 * MF][64];                   // [stage][feature tile][lane]
+  unsigned char x[pf_stages(TB, MF)][64 * TB * PF_XPITCH];  // [stage][token row * 64 bytes], slots swizzled
 };
 
 // GLU = true: the output buffer already holds the gate values g (bf16); store silu(g) * result.
@@ -117,7 +132,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   constexpr int BT = 2 * WTOK;                     // tokens per workgroup tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   PfShared<MF, TB> &S = *reinterpret_cast<PfShared<MF, TB> *>(smem_raw);
-  constexpr int NST = pf_stages(TB);               // LDS stage buffers; loads run NST - 1 stages ahead
+  constexpr int NST = pf_stages(TB, MF);           // LDS stage buffers; loads run NST - 1 stages ahead
   constexpr int BF_TILES = 2 * MF;                 // 16-feature tiles per workgroup
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wf = wave & 1, wt = wave >> 1;         // wavefront position: features x tokens
@@ -254,12 +269,9 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 #pragma unroll
         for (int i = 0; i < H1; ++i) fetch_part(D - 1, i);
       }
-      static_assert(D == 5, "the waits below are written out for a queue of five stages");
-      if (n_stages > 4) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LPS + H1) : "memory");
-      else if (n_stages == 4) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LPS) : "memory");
-      else if (n_stages == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPS) : "memory");
-      else if (n_stages == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");
-      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      // outstanding at most: the stages after stage 0 (and the half stage D - 1)
+      if (D - 1 < n_stages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS + H1) : "memory");
+      else PfVmWait<0, D - 2, LPS, 0>::run(n_stages - 1);
     }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();          // stage 0 has landed everywhere
@@ -363,11 +375,9 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
       if (STEADY) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS) : "memory");
       } else {
-        const int rem = n_stages - (st + 2);
-        if (rem >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LPS) : "memory");
-        else if (rem == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPS) : "memory");
-        else if (rem == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        int rem = n_stages - (st + 2);
+        rem = rem < 0 ? 0 : rem > D - 2 ? D - 2 : rem;
+        PfVmWait<0, D - 2, LPS, 0>::run(rem);
       }
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();          // ... everywhere, and nobody reads the buffer of stage st - 1 any more
