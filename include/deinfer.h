@@ -103,10 +103,13 @@ int deinfer_set_trace_buffer(void *buf, size_t bytes);
  * Test and measurement aid: the workgroup tile of the compute-bound (T > 128) kernel.  0 (the
  * default) lets every launch choose: 256 tokens x 256 features; 128 x 256 while the larger tiles
  * of the launch would occupy at most half of the compute units; 128 x 128 while that still
- * holds for the 128 x 256 tiles.  deinfer_set_prefill_token_tile(128 or 256) forces the token
+ * holds for the 128 x 256 tiles; a launch of more than one round of 256 x 256 tiles whose last
+ * round would be at most half full runs that round's feature blocks as 128 x 256 tiles in the
+ * same launch.  deinfer_set_prefill_token_tile(128 or 256) forces the token
  * extent for every launch that has the choice (launches with a split k range always use 256),
  * deinfer_set_prefill_feature_tile(128 or 256) the feature extent of the 128-token tiles
- * (launches with the rotary epilogue always use 256).  Results do not depend on the tile: each
+ * (launches with the rotary epilogue always use 256); token tile 384 makes every such launch
+ * run the second half of its feature blocks as 128 x 256 tiles.  Results do not depend on the tile: each
  * output element is the same sum taken in the same order.  Process-wide, not thread-safe.
  */
 int deinfer_set_prefill_token_tile(int tokens);

@@ -623,7 +623,8 @@ int deinfer_set_profile_events(int which, void *start_event, void *stop_event) {
 }
 
 int deinfer_set_prefill_token_tile(int tokens) {
-  if (tokens != 0 && tokens != 128 && tokens != 256) return fail(DEINFER_ERR_INVALID_ARG, "token tile: 0, 128 or 256, got %d", tokens);
+  if (tokens != 0 && tokens != 128 && tokens != 256 && tokens != 384)
+    return fail(DEINFER_ERR_INVALID_ARG, "token tile: 0, 128, 256 or 384 (both shapes in one launch), got %d", tokens);
   g_token_tile = tokens;
   return DEINFER_OK;
 }

@@ -101,6 +101,10 @@ struct PfParams {
   int kb_per_part;         // k-blocks per part
   float *part;             // [n_parts][n_tblocks * 256][n_fblocks * 256] fp32 partial products
   long long part_stride;   // elements between parts
+  // prefill_mixed_kernel only
+  int n_big;               // workgroups with 256 x 256 tiles (they come first)
+  int n_tblocks2;          // ceil(T / 128): token blocks of the 128 x 256 tiles
+  int fb_shift2;           // first feature block (of 256 features) of the 128 x 256 tiles
 #ifdef DEINFER_PF_TRACE
   unsigned long long *trace;   // diagnostic build only: per-workgroup cycle counts
 #endif
@@ -123,8 +127,11 @@ struct PfShared {
 // TB = 32-token blocks per wavefront: 4 (workgroup tile of 256 tokens) or 2 (128 tokens: twice the
 // workgroups, for launches whose 256-token tiles are fewer than the compute units; its loop keeps a
 // whole k-step of operands ahead instead of the hand-placed reads of the TB = 4 loop).
-template <int DT, int MF, bool GLU, bool POST = false, bool SPLIT = false, bool ROPE = false, int TB = 4>
-__global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
+// The body of a workgroup: bid = its index among the workgroups of this tile shape, n_tblocks = token
+// blocks of this tile shape, fb_shift = first feature block of this tile shape (0 unless the launch
+// mixes two shapes, see prefill_mixed_kernel).
+template <int DT, int MF, bool GLU, bool POST, bool SPLIT, bool ROPE, int TB>
+__device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, const int n_tblocks, const int fb_shift) {
   static_assert(!(ROPE && (GLU || POST || SPLIT)), "the rotary epilogue goes with a plain product");
   static_assert(TB == 4 || (TB == 2 && !SPLIT), "token blocks per wavefront");
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
@@ -140,8 +147,8 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   // consecutive workgroups share a feature block and differ in the token block: the token
   // blocks of one feature block run at the same time, spread over the XCDs, so each L2
   // streams those weights once
-  const int tb = blockIdx.x % P.n_tblocks;
-  const int fb_all = blockIdx.x / P.n_tblocks;
+  const int tb = bid % n_tblocks;
+  const int fb_all = bid / n_tblocks + fb_shift;
   int fb = SPLIT ? fb_all % P.n_fblocks : fb_all;
   int pi = 0;                                                   // which product (uniform)
   if (!SPLIT && P.n_prob > 1 && fb >= P.fb0[1]) pi = 1;
@@ -635,8 +642,24 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   }
 #endif
 #else
-  (void)P;
+  (void)P; (void)bid; (void)n_tblocks; (void)fb_shift;
 #endif
+}
+
+template <int DT, int MF, bool GLU, bool POST = false, bool SPLIT = false, bool ROPE = false, int TB = 4>
+__global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
+  prefill_body<DT, MF, GLU, POST, SPLIT, ROPE, TB>(P, (int)blockIdx.x, P.n_tblocks, 0);
+}
+
+// One launch with two tile shapes: the first P.n_big workgroups take 256 x 256 tiles of the feature
+// blocks [0, P.fb_shift2), the others 128 x 256 tiles of the remaining feature blocks.  For large
+// launches whose last round of 256 x 256 tiles would leave more than half of the compute units
+// idle: that round's feature blocks run as twice as many smaller tiles, which take about 0.64 of a
+// large tile's time each.
+template <int DT, bool GLU, bool POST, bool ROPE>
+__global__ __launch_bounds__(PF_THREADS) void prefill_mixed_kernel(const PfParams P) {
+  if ((int)blockIdx.x < P.n_big) prefill_body<DT, 8, GLU, POST, false, ROPE, 4>(P, (int)blockIdx.x, P.n_tblocks, 0);
+  else prefill_body<DT, 8, GLU, POST, false, ROPE, 2>(P, (int)blockIdx.x - P.n_big, P.n_tblocks2, P.fb_shift2);
 }
 
 }  // namespace deinfer

@@ -21,10 +21,11 @@ def dn():
     return dn
 
 
-@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256)], ids=["tiles-auto", "tiles-256", "tiles-128x256"])
+@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256), (384, 0)], ids=["tiles-auto", "tiles-256", "tiles-128x256", "tiles-mixed"])
 def token_tile(request, dn):
     """Every test runs with the workgroup tile of the T > 128 kernel chosen per launch (small shapes then
-    take the 128 x 128 tile), with 256-token tiles forced and with 128 x 256 tiles forced."""
+    take the 128 x 128 tile), with 256-token tiles forced, with 128 x 256 tiles forced, and with both
+    shapes in one launch (the second half of the feature blocks as 128 x 256 tiles)."""
     dn.deinfer_set_prefill_token_tile(request.param[0])
     dn.deinfer_set_prefill_feature_tile(request.param[1])
     yield request.param

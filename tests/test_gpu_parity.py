@@ -20,10 +20,11 @@ def dn():
     return dn
 
 
-@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256)], ids=["tiles-auto", "tiles-256", "tiles-128x256"])
+@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256), (384, 0)], ids=["tiles-auto", "tiles-256", "tiles-128x256", "tiles-mixed"])
 def token_tile(request, dn):
     """Every test runs with the workgroup tile of the T > 128 kernel chosen per launch (small shapes then
-    take the 128 x 128 tile), with 256-token tiles forced and with 128 x 256 tiles forced."""
+    take the 128 x 128 tile), with 256-token tiles forced, with 128 x 256 tiles forced, and with both
+    shapes in one launch (the second half of the feature blocks as 128 x 256 tiles)."""
     dn.deinfer_set_prefill_token_tile(request.param[0])
     dn.deinfer_set_prefill_feature_tile(request.param[1])
     yield request.param
@@ -466,7 +467,7 @@ def test_token_tiles_give_identical_results(dn, dtype, T):
     ws = dn.Workspace(max(dn.deinfer_workspace_bytes(T, [F["q"], F["k"], F["v"]]),
                           dn.deinfer_workspace_bytes(T, [F["g"], F["u"]])))
     res = {}
-    for tile in (128, 129, 256):                   # 128: 128 x 128 tiles, 129: 128 x 256 tiles
+    for tile in (128, 129, 256, 384):              # 128: 128 x 128 tiles, 129: 128 x 256 tiles, 384: two shapes in one launch
         dn.deinfer_set_prefill_token_tile(128 if tile == 129 else tile)
         dn.deinfer_set_prefill_feature_tile(256 if tile == 129 else 128 if tile == 128 else 0)
         tk = torch.zeros((T, 24), dtype=xd.dtype, device="cuda")
@@ -479,9 +480,10 @@ def test_token_tiles_give_identical_results(dn, dtype, T):
         res[tile] = [t.clone() for t in (q, k, v, tk, h, a, k2)]
     dn.deinfer_set_prefill_token_tile(0)
     dn.deinfer_set_prefill_feature_tile(0)
-    for t128, t129, t256 in zip(res[128], res[129], res[256]):
+    for t128, t129, t256, t384 in zip(res[128], res[129], res[256], res[384]):
         assert torch.equal(t128.view(torch.int16), t256.view(torch.int16))
         assert torch.equal(t129.view(torch.int16), t256.view(torch.int16))
+        assert torch.equal(t384.view(torch.int16), t256.view(torch.int16))
     q, k, v, tk, h, a, k2 = res[128]
     rq, rk, rv, rtk, rtv = oracle.lowrank_qkv(x.values, *host["q"], *host["k"], *host["v"], return_t=True)
     for got, ref in ((q, rq), (k, rk), (v, rv), (tk, rtk)):
