@@ -72,6 +72,9 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with "
                                "`python -m paper_2604_17709_amd.build` (there is no fallback path)")
+        # torch first: the library must bind to the HIP runtime that torch has loaded (its own copy), not
+        # load a second one, or its calls see no device
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         FP = ctypes.POINTER(Factors)
         L.deinfer_last_error.restype = ctypes.c_char_p
