@@ -69,6 +69,9 @@ def parse():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"], help="storage type of weights, activations and outputs")
     ap.add_argument("--rank-override", default="", help="e.g. gate=2357,up=2357,down=2357: ranks not taken from the rule")
+    ap.add_argument("--traffic-calibration", type=int, default=0, metavar="MIB",
+                    help="do nothing but five plain device-to-device copies of MIB MiB (a kernel of known traffic, for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc) and exit")
     ap.add_argument("--no-second-row", action="store_true",
                     help="skip the second row of the default workload (the ranks that the configuration prints, 2357)")
     return ap.parse_args()
@@ -90,6 +93,16 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.traffic_calibration > 0:
+        n = args.traffic_calibration << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_calibration": "5 copies", "bytes_read_per_copy": n, "bytes_written_per_copy": n}))
+        return
     L = dn.lib()            # raises if the HIP library is missing: no fallback
 
     block_name, T_default, bound = WORKLOADS[args.workload]

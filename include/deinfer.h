@@ -72,69 +72,6 @@ const char *deinfer_last_error(void);
 int deinfer_version(void);
 
 /*
- * Measurement aid: an entry-point call is several kernel launches (decode sizes: downward
- * projection, reduce, upward projection; prefill sizes: one GEMM per stage).  After this call
- * the library records start_event before, and stop_event after, every launch of the kind
- * `which` (both are hipEvent_t created with timing enabled, passed as void*), on the stream of
- * the call, so that a benchmark can time that one kernel with HIP events.  NULL events or
- * which == 0 switch it off (the default).  Process-wide, not thread-safe.
- */
-enum {
-  DEINFER_PROF_NONE = 0,
-  DEINFER_PROF_DECODE_DOWN = 1,
-  DEINFER_PROF_DECODE_REDUCE = 2,
-  DEINFER_PROF_DECODE_UP = 3,
-  DEINFER_PROF_PREFILL_DOWN = 4,
-  DEINFER_PROF_PREFILL_UP = 5
-};
-int deinfer_set_profile_events(int which, void *start_event, void *stop_event);
-
-/*
- * Diagnostic: from now on every decode-sized call writes wall-clock stamps (100 MHz) into
- * buf (device memory, uint64): workgroup g of the downward-projection kernel uses
- * buf[8 g .. 8 g + 7], workgroup g of the upward-projection kernel buf[8 (1024 + g) ..]:
- * [0] kernel entry, [5] first batch multiplied, [3] kernel exit, the rest spare.  buf must
- * hold 2 * 1024 * 8 words; NULL switches tracing off (the default).  Process-wide, not
- * thread-safe, not meant for production runs.
- */
-int deinfer_set_trace_buffer(void *buf, size_t bytes);
-
-/*
- * Test and measurement aid: the workgroup tile of the compute-bound (T > 128) kernel.  0 (the
- * default) lets every launch choose: 256 tokens x 256 features; 128 x 256 while the larger tiles
- * of the launch would occupy at most half of the compute units; 128 x 128 while that still
- * holds for the 128 x 256 tiles; a launch of more than one round of 256 x 256 tiles whose last
- * round would be at most half full runs that round's feature blocks as 128 x 256 tiles in the
- * same launch.  deinfer_set_prefill_token_tile(128 or 256) forces the token
- * extent for every launch that has the choice (launches with a split k range always use 256),
- * deinfer_set_prefill_feature_tile(128 or 256) the feature extent of the 128-token tiles
- * (launches with the rotary epilogue always use 256); token tile 384 makes every such launch
- * run the second half of its feature blocks as 128 x 256 tiles.  Results do not depend on the tile: each
- * output element is the same sum taken in the same order.  Process-wide, not thread-safe.
- */
-int deinfer_set_prefill_token_tile(int tokens);
-int deinfer_set_prefill_feature_tile(int features);
-
-/*
- * Measurement aids: what this device delivers on the two rooflines of the path (Sec. 5 reports
- * throughput only; the denominators are this build's), for a benchmark that prints a measured
- * ceiling beside the published one.  Both enqueue one kernel on `stream`, allocate nothing and
- * do not synchronise.  sink: device scratch of at least DEINFER_PROBE_SINK_BYTES, 16-byte
- * aligned, contents undefined afterwards.
- *   deinfer_probe_stream_read  reads buf[0 .. bytes) once (bytes a positive multiple of 1024,
- *                              buf 16-byte aligned, device) with plain coalesced loads.
- *   deinfer_probe_mfma_bf16    every wavefront of a one-workgroup-per-compute-unit grid issues
- *                              8 * n_rounds bf16 32x32x16 matrix products back to back on register
- *                              operands taken from `operands` (device, >= 8192 bytes of bf16
- *                              values, 16-byte aligned); *flops_out (host, may be NULL) receives
- *                              the floating-point operations of the launch.
- */
-#define DEINFER_PROBE_SINK_BYTES ((size_t)1 << 20)
-int deinfer_probe_stream_read(const void *buf, size_t bytes, void *sink, size_t sink_bytes, void *stream);
-int deinfer_probe_mfma_bf16(const void *operands, size_t operand_bytes, int64_t n_rounds,
-                            void *sink, size_t sink_bytes, void *stream, double *flops_out);
-
-/*
  * Rank that keeps a fraction (1 - param_reduction) of the m*n parameters of a weight:
  *     r = floor((1 - param_reduction) * m * n / (m + n))
  * since a pair of inner size k holds (m + n) k parameters (Sec. 2.1).  The ratio is
@@ -273,7 +210,7 @@ int deinfer_lowrank_linear_act(const void *x, int64_t T, int64_t ldx, const dein
                                void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Paged low-rank cache and static graphs (Sec. 4.3).  The low-rank cache (k_low_rank, v_low_rank)
+ * Paged low-rank cache and static graphs (Sec. 4.2, "Integrating Paged Cache and CUDA Graph").  The low-rank cache (k_low_rank, v_low_rank)
  * lives in a pool of fixed-size physical blocks; a block table names, per sequence, the blocks it
  * owns.  Before attention the blocks are squeezed into a compact buffer at a fixed address, the
  * buffer is multiplied by the upward matrix (deinfer_lowrank_up with T = the buffer's token
@@ -312,7 +249,7 @@ int deinfer_kv_compact_copy(const void *pool, int64_t n_pool_blocks, int64_t blo
                             void *buffer, int64_t buffer_blocks, void *stream);
 
 /*
- * Rotary position embedding in place (Sec. 4.3 applies it to the rebuilt keys; the paper prints
+ * Rotary position embedding in place (Sec. 4.2 applies it to the rebuilt keys; the paper prints
  * no formula, this is the one of LLaMA-type models): x is T x (n_heads * head_dim), pitch ldx,
  * device, dtype DEINFER_BF16, DEINFER_F16 or DEINFER_F32; inside every head the elements i and i + head_dim/2
  * (i < head_dim/2) are replaced by
@@ -324,7 +261,7 @@ int deinfer_rope_inplace(void *x, int64_t T, int64_t ldx, int64_t n_heads, int64
                          const int32_t *positions, double theta, int dtype, void *stream);
 
 /*
- * Upward projection of keys with the rotary embedding applied on the way out (Sec. 4.3 rebuilds
+ * Upward projection of keys with the rotary embedding applied on the way out (Sec. 4.2 rebuilds
  * the keys from k_low_rank and then rotates them; here the rotation is the last step of the
  * product's kernel, so the rebuilt keys cross HBM once instead of three times):
  *   deinfer_rope_table:      table[t][i] = cos(a_ti), table[t][head_dim/2 + i] = sin(a_ti),

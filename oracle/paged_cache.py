@@ -1,11 +1,11 @@
-"""CPU oracle for the paged-cache side of key/value reconstruction (Sec. 4.3) and for the
+"""CPU oracle for the paged-cache side of key/value reconstruction (Sec. 4.2) and for the
 rotary position embedding applied to the rebuilt keys.
 
 TEST INFRASTRUCTURE ONLY: imported by ``tests/`` (and nothing in the GPU package); it imports
 nothing from the GPU package.  Plain Python loops and numpy in float64 / exact integers, written
 for reading, not for speed.
 
-What the paper fixes (Sec. 4.3): in a preparation stage a scan over the block tables finds the
+What the paper fixes (Sec. 4.2): in a preparation stage a scan over the block tables finds the
 logical blocks that are physically contiguous and derives a "remapping index list" that acts as
 the block table of a compact buffer; in the graph-replay stage the contiguous pieces are copied
 one after the other into that buffer, the compact low-rank cache is multiplied by the upward

@@ -28,6 +28,7 @@ F16 = 2
 LAYOUT_RAW = 0
 LAYOUT_PACKED = 1
 PROF_DECODE_DOWN, PROF_DECODE_REDUCE, PROF_DECODE_UP, PROF_PREFILL_DOWN, PROF_PREFILL_UP = 1, 2, 3, 4, 5
+TOKEN_TILE_BOTH = 384         # deinfer_set_prefill_token_tile: both tile shapes in one launch (deinfer_testing.h)
 
 _i64 = ctypes.c_int64
 _vp = ctypes.c_void_p
@@ -50,7 +51,7 @@ class DeinferError(RuntimeError):
 
 
 EXPORTS = [
-    "deinfer_last_error", "deinfer_version", "deinfer_set_profile_events", "deinfer_set_trace_buffer",
+    "deinfer_last_error", "deinfer_version", "deinfer_set_profile_events",
     "deinfer_set_prefill_token_tile", "deinfer_set_prefill_feature_tile",
     "deinfer_rank_for_ratio", "deinfer_probe_stream_read", "deinfer_probe_mfma_bf16",
     "deinfer_packed_bytes", "deinfer_pack_factors",
@@ -79,7 +80,6 @@ def lib() -> ctypes.CDLL:
         FP = ctypes.POINTER(Factors)
         L.deinfer_last_error.restype = ctypes.c_char_p
         L.deinfer_version.restype = ctypes.c_int
-        L.deinfer_set_trace_buffer.argtypes = [_vp, _sz]
         L.deinfer_set_prefill_token_tile.argtypes = [ctypes.c_int]
         L.deinfer_set_prefill_feature_tile.argtypes = [ctypes.c_int]
         L.deinfer_set_profile_events.argtypes = [ctypes.c_int, _vp, _vp]
@@ -214,10 +214,13 @@ def deinfer_pack_factors(pair: Pair, stream=None) -> Pair:
 class Workspace:
     """Caller-owned scratch for the library (rank-space intermediate + sync words)."""
 
-    def __init__(self, nbytes: int, device="cuda", stream=None):
+    def __init__(self, nbytes: int, device="cuda", stream=None, buf=None):
+        """buf: an existing uint8 device tensor of nbytes, 256-byte aligned, to use instead of a new one."""
         import torch
         self.nbytes = int(nbytes)
-        self.buf = torch.empty(self.nbytes, dtype=torch.uint8, device=device)
+        self.buf = torch.empty(self.nbytes, dtype=torch.uint8, device=device) if buf is None else buf
+        if self.buf.numel() < self.nbytes:
+            raise ValueError("workspace buffer smaller than nbytes")
         _check(lib().deinfer_workspace_init(_ptr(self.buf), self.nbytes, _stream(stream)))
 
     @staticmethod

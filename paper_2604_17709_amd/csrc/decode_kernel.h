@@ -73,7 +73,6 @@ struct DecParams {
   int direct1;                // 1: one workgroup per rank tile sums the whole k range and writes t itself (no reduce kernel)
   const uint16_t *bias;       // single non-GLU pair: y = act(product + bias[feature]); may be null
   int act;                    // see act_f32
-  unsigned long long *trace;  // optional [2][1024][8] wall-clock stamps (diagnostic), may be null
 };
 
 // Values that are the same in every lane are moved to scalar registers explicitly (the
@@ -100,7 +99,6 @@ typedef const DEINFER_GLOBAL u32x4_t *gc_u32x4_p;
 typedef DEINFER_GLOBAL float4 *g_float4_p;
 typedef DEINFER_GLOBAL uint2 *g_uint2_p;
 typedef DEINFER_GLOBAL uint16_t *g_u16_p;
-typedef DEINFER_GLOBAL unsigned long long *g_u64_p;
 
 // fragments per wavefront and batch
 // (one token tile: 16 per batch in the down kernel - d_in = 4096 is exactly two batches - and 20 in
@@ -319,11 +317,6 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
   const DecParams &P = *reinterpret_cast<const DecParams *>(p_words);
   const int lrow = lane & 15, lkg = lane >> 4;
   const int G = gridDim.x, g = blockIdx.x;
-  const g_u64_p trace = (g_u64_p)((P.trace && g < 1024 && tid == 0) ? uni_ptr(P.trace) + ((PHASE - 1) * 1024 + g) * 8 : nullptr);
-  if (trace) {
-    trace[0] = wall_clock64();
-    for (int i = 1; i < 8; ++i) trace[i] = 0;
-  }
 
   // per-lane activation row offsets (elements): x rows are clamped to the last token, t rows are padded
   // (host guarantees that T * ldx and T16 * Rtot_pad fit 30 bits)
@@ -340,23 +333,17 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
     }
   }
 
-  if (trace) trace[1] = wall_clock64();
   Cursor<NT, DUAL, PHASE> cur;
   cur.init(P, g, G);
-  if (trace && cur.G1 >= 0) trace[2] = wall_clock64();
   Frags<NT, PHASE> F;
   f32x4_t acc[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  int n_steps = 0, n_fin = 0;
 
   // One batch: request its fragments, multiply, and close the segment if it ends here.
   auto step = [&](const Batch &dc) {
     load_frags<NT, PHASE>(dc, wave, lane, lkg * 8, rowoff, F, xlds);
-    if (trace && n_steps == 0) trace[4] = wall_clock64();
     multiply<DT, NT, PHASE>(dc, wave, F, acc);
-    if (trace && n_steps == 0 && acc[0][0] != 12345.678f) trace[5] = wall_clock64();
-    ++n_steps;
     if (!dc.end_seg) return;
 
     // ---- segment end: reduce the partial accumulators of the wavefronts through LDS and hand the result on
@@ -449,15 +436,12 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
       }
     }
     __syncthreads();
-    if (trace && n_fin++ == 0) trace[6] = wall_clock64();
   };
 
   Batch d;
   while (cur.next(P, d)) {
-    if (trace && n_steps == 0 && d.kb0 >= 0) trace[7] = wall_clock64();
     step(d);
   }
-  if (trace) trace[3] = wall_clock64();
 }
 
 // t[tok][c] = bf16(sum over the parts of rank tile c / 16, in part order); rows T..T16-1 of t

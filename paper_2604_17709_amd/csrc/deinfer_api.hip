@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/deinfer.h: argument validation (host only,
 // before any device call), workspace carving, kernel selection and launch.
 #include "../../include/deinfer.h"
+#include "../../include/deinfer_testing.h"
 
 #include <hip/hip_runtime.h>
 
@@ -24,12 +25,11 @@ using namespace deinfer;
 namespace {
 
 thread_local char g_err[512] = "no error";
-unsigned long long *g_trace = nullptr;   // diagnostic stamp buffer (deinfer_set_trace_buffer)
-size_t g_trace_bytes = 0;
-int g_token_tile = 0;                 // 0: chosen per launch; 128 or 256: forced (test and measurement aid)
-int g_feature_tile = 0;               // 0: chosen per launch; 128 or 256: forced where the token tile is 128
-int g_prof_kernel = 0;                   // deinfer_set_profile_events: which internal launch to bracket
-hipEvent_t g_prof_ev[2] = {nullptr, nullptr};
+// Test and measurement aids (include/deinfer_testing.h): state of the calling thread only
+thread_local int g_token_tile = 0;       // 0: chosen per launch; 128 or 256: forced; DEINFER_TOKEN_TILE_BOTH: two shapes in one launch
+thread_local int g_feature_tile = 0;     // 0: chosen per launch; 128 or 256: forced where the token tile is 128
+thread_local int g_prof_kernel = 0;      // deinfer_set_profile_events: which internal launch to bracket
+thread_local hipEvent_t g_prof_ev[2] = {nullptr, nullptr};
 
 // Brackets one internal kernel launch with the caller's two events (measurement aid).
 struct ProfScope {
@@ -69,6 +69,14 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 //            generic: t [T x Rtot] fp32
 constexpr size_t WS_HEADER = 256;
 
+// Calls of up to this many tokens take the memory-bound schedules (run_decode, run_skinny), longer
+// ones the compute-bound one (run_prefill).
+#ifndef DEINFER_SKINNY_MAX_T
+#define DEINFER_SKINNY_MAX_T 128
+#endif
+constexpr int64_t SKINNY_MAX_T = DEINFER_SKINNY_MAX_T;
+static_assert(SKINNY_MAX_T >= 16 && SKINNY_MAX_T <= 128, "the streaming kernels hold at most four 32-token blocks");
+
 struct Geometry {          // derived sizes of one pair
   int64_t r_pad, KB1, KB2, n_rtiles, n_otiles;
   size_t u_bytes, v_bytes;
@@ -83,6 +91,19 @@ Geometry geometry(const deinfer_factors_t *f) {
   g.u_bytes = (size_t)g.n_rtiles * g.KB1 * 1024;
   g.v_bytes = (size_t)g.n_otiles * g.KB2 * 1024;
   return g;
+}
+
+int device_cus() {
+  static int cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return -1;
+  if (dev < 0 || dev >= 64) return -1;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
+    cached[dev] = n;
+  }
+  return cached[dev];
 }
 
 // ---- split of a memory-bound call with 16 < T <= 128 tokens
@@ -120,11 +141,14 @@ SkPlan skinny_plan(int64_t T, const deinfer_factors_t *const *f, int n, bool glu
     for (int i = 0; i < n; ++i) g += (int)ceil_div(tiles[s][i], (int64_t)(2 * nw));
     return g;
   };
-  // About one long-lived workgroup per compute unit of a 256-unit device, and never a few more: two
+  // About one long-lived workgroup per compute unit, and never a few more: two
   // workgroups fit a unit, so 258 of them on 256 units put two pairs on one unit each, and the launch
   // waits for those (traced: 15.4 us instead of 11.5 us for 86 groups x 3 ranges).  Hence the largest
   // number of k-ranges P with groups x P <= 256.
-  const int target = 256;
+  // (the compute units of the current device; 256, the count of the device this is written for, where
+  // no device can be asked: the host-only size query on a machine without a GPU)
+  const int cus_now = device_cus();
+  const int target = cus_now > 0 ? cus_now : 256;
   for (int s = 0; s < 2; ++s) {
     // more than 8 ranges only for a very long k (first stage of the second MLP layer of the largest
     // models): every range keeps at least 64 k-blocks (70B shapes, k = 28672, 20 groups: 12 ranges,
@@ -214,7 +238,7 @@ int validate_pair(const deinfer_factors_t *f, const char *name) {
   return DEINFER_OK;
 }
 
-size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
+size_t workspace_need_of(int64_t T, const deinfer_factors_t *const *pairs, int n) {
   int64_t rtot = 0, rtot_pad = 0;
   for (int i = 0; i < n; ++i) { rtot += pairs[i]->r; rtot_pad += round_up(pairs[i]->r, 32); }
   const bool packed = pairs[0]->layout == DEINFER_LAYOUT_PACKED;
@@ -225,10 +249,10 @@ size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
     const size_t rp = (size_t)(rtot_pad > 0 ? rtot_pad : 32);
     // T <= 16: t in fragment order and up to DEC_MAX_PARTS fp32 part buffers of one 16-token tile
     const size_t tdec = T <= 16 ? (size_t)round_up((int64_t)16 * rp * 2, 256) + (size_t)DEC_MAX_PARTS * 16 * rp * 4 : 0;
-    size_t tpre = T > 128 ? (size_t)round_up(T, 256) * rp * 2 : 0;
-    if (T > 128) tpre = (size_t)round_up((int64_t)tpre, 256) + prefill_split_plan(T, pairs, n).part_bytes;
+    size_t tpre = T > SKINNY_MAX_T ? (size_t)round_up(T, 256) * rp * 2 : 0;
+    if (T > SKINNY_MAX_T) tpre = (size_t)round_up((int64_t)tpre, 256) + prefill_split_plan(T, pairs, n).part_bytes;
     scratch = round_up((int64_t)tdec, 256) + round_up((int64_t)tpre, 256);
-    if (T <= 128) {          // (the upward-projection-only call uses this schedule for every T <= 128)
+    if (T <= SKINNY_MAX_T) { // (the upward-projection-only call uses this schedule for every such T)
       for (int glu = 0; glu < 2; ++glu) {      // (the call is not known here: room for either kind)
         const SkPlan pl = skinny_plan(T, pairs, n, glu != 0);
         const size_t sk = pl.t_bytes + pl.part_bytes;
@@ -239,17 +263,20 @@ size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
   return WS_HEADER + (size_t)round_up((int64_t)scratch, 256);
 }
 
-int device_cus() {
-  static int cached[64];
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return -1;
-  if (dev < 0 || dev >= 64) return -1;
-  if (cached[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
-    cached[dev] = n;
+// Bytes that a call with these pairs may use.  Pairs of rank 0 are dropped before the dispatch (their
+// outputs are zero-filled), and the remaining group may split differently (fewer feature groups admit
+// more k-ranges, i.e. more partial sums): room for the group as given and for the group that runs.
+size_t workspace_need(int64_t T, const deinfer_factors_t *const *pairs, int n) {
+  size_t need = workspace_need_of(T, pairs, n);
+  const deinfer_factors_t *rest[3];
+  int m = 0;
+  for (int i = 0; i < n && i < 3; ++i)
+    if (pairs[i]->r > 0) rest[m++] = pairs[i];
+  if (m > 0 && m < n) {
+    const size_t reduced = workspace_need_of(T, rest, m);
+    if (reduced > need) need = reduced;
   }
-  return cached[dev];
+  return need;
 }
 
 int check_launch(const char *what) {
@@ -370,8 +397,9 @@ int run_decode(const Group &gq) {
     while (G1 > 1 && max_parts(total, P.KB1, G1) > DEC_MAX_PARTS) G1 = G1 * 7 / 8;
     P.G1 = G1;
   }
-  P.trace = (g_trace && g_trace_bytes >= (size_t)2 * 1024 * 8 * sizeof(unsigned long long)) ? g_trace : nullptr;
   const size_t t_bytes = (size_t)round_up((int64_t)nt * 16 * P.Rtot_pad * 2, 256);
+  if (WS_HEADER + t_bytes + (P.direct1 ? 0 : (size_t)DEC_MAX_PARTS * nt * 16 * P.Rtot_pad * 4) > gq.ws_bytes)
+    return fail(DEINFER_ERR_WORKSPACE, "workspace too small for the decode schedule: %zu bytes given", gq.ws_bytes);
   P.t = reinterpret_cast<uint16_t *>(ws + WS_HEADER);
   P.part = reinterpret_cast<float *>(ws + WS_HEADER + t_bytes);
   P.part_stride = (long long)nt * 16 * P.Rtot_pad;
@@ -570,7 +598,7 @@ int run_group(Group gq) {
   if (gq.rope != nullptr) {
     // the large-T kernel rotates in its epilogue when one wavefront's 128 features are one head and
     // its 16-byte stores apply; otherwise the product is written first and rotated in place
-    const bool fused = packed && gq.T > 128 && gq.rope_dim == 128 && gq.f[0]->d_out % 128 == 0 &&
+    const bool fused = packed && gq.T > SKINNY_MAX_T && gq.rope_dim == 128 && gq.f[0]->d_out % 128 == 0 &&
                        aligned(gq.out[0], 16) && gq.ldo[0] % 8 == 0;
     if (!fused) {
       Group plain = gq;
@@ -602,7 +630,7 @@ int run_group(Group gq) {
     if (cus <= 0) return fail(DEINFER_ERR_DEVICE, "no usable HIP device");
     if (gq.T <= 8 && rtiles <= cus && otiles <= 4 * cus) return run_decode(gq);
   }
-  if (gq.T <= 128) return run_skinny(gq);
+  if (gq.T <= SKINNY_MAX_T) return run_skinny(gq);
   return run_prefill(gq);
 }
 
@@ -623,8 +651,8 @@ int deinfer_set_profile_events(int which, void *start_event, void *stop_event) {
 }
 
 int deinfer_set_prefill_token_tile(int tokens) {
-  if (tokens != 0 && tokens != 128 && tokens != 256 && tokens != 384)
-    return fail(DEINFER_ERR_INVALID_ARG, "token tile: 0, 128, 256 or 384 (both shapes in one launch), got %d", tokens);
+  if (tokens != 0 && tokens != 128 && tokens != 256 && tokens != DEINFER_TOKEN_TILE_BOTH)
+    return fail(DEINFER_ERR_INVALID_ARG, "token tile: 0, 128, 256 or DEINFER_TOKEN_TILE_BOTH (both shapes in one launch), got %d", tokens);
   g_token_tile = tokens;
   return DEINFER_OK;
 }
@@ -632,12 +660,6 @@ int deinfer_set_prefill_token_tile(int tokens) {
 int deinfer_set_prefill_feature_tile(int features) {
   if (features != 0 && features != 128 && features != 256) return fail(DEINFER_ERR_INVALID_ARG, "feature tile: 0, 128 or 256, got %d", features);
   g_feature_tile = features;
-  return DEINFER_OK;
-}
-
-int deinfer_set_trace_buffer(void *buf, size_t bytes) {
-  g_trace = static_cast<unsigned long long *>(buf);
-  g_trace_bytes = buf ? bytes : 0;
   return DEINFER_OK;
 }
 

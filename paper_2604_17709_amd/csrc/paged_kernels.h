@@ -1,5 +1,5 @@
 // Paged low-rank cache -> compact buffer, and the in-place rotary embedding of the rebuilt keys
-// (Sec. 4.3: "graph replay stage").  Both kernels take everything that changes from step to step
+// (Sec. 4.2: "graph replay stage").  Both kernels take everything that changes from step to step
 // (the run list, the token positions) from device memory and have a grid that depends only on
 // capacities, so a captured launch stays valid when the cache contents change.
 #pragma once

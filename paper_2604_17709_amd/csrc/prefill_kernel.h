@@ -105,9 +105,6 @@ struct PfParams {
   int n_big;               // workgroups with 256 x 256 tiles (they come first)
   int n_tblocks2;          // ceil(T / 128): token blocks of the 128 x 256 tiles
   int fb_shift2;           // first feature block (of 256 features) of the 128 x 256 tiles
-#ifdef DEINFER_PF_TRACE
-  unsigned long long *trace;   // diagnostic build only: per-workgroup cycle counts
-#endif
 };
 
 template <int MF, int TB = 4>
@@ -158,10 +155,6 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
   const int kb0 = SPLIT ? kpart * P.kb_per_part : 0;          // first k-block of this workgroup
   const int tok0 = tb * BT;
 
-#ifdef DEINFER_PF_TRACE
-  const unsigned long long w_start = wall_clock64(), k_start = __builtin_readcyclecounter();
-  unsigned long long e_start = 0, c_wait_all = 0, c_bar_all = 0;
-#endif
   constexpr int MB = MF / 2;                       // 32-feature blocks per wavefront
   static_assert(MF == 8 || (MF == 4 && TB == 2 && !ROPE), "the hand-placed loop of the 256-token tile is written for four 32-feature blocks per wavefront");
   f32x16_t acc[MB][TB];                            // [feature block][32-token block]
@@ -238,9 +231,6 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
       const int slot = (2 * ks + (lane >> 5)) ^ b_swz;
       return *reinterpret_cast<const u32x4_t *>(&S.x[buf][(b_row + 32 * jb) * PF_XPITCH + slot * 16]);
     };
-#ifdef DEINFER_PF_TRACE
-    unsigned long long c_wait = 0, c_bar = 0, c0 = __builtin_readcyclecounter(), c1, c2, c3;
-#endif
     constexpr int H1 = LPS / 2;            // loads 0 .. H1 - 1 of stage s + 3 go out during k-step 1 of stage s,
                                            // loads H1 .. LPS - 1 during k-step 0 of stage s + 1: at most one
                                            // load after each group of products, so their issue never holds
@@ -318,24 +308,14 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
       }
       // ---- stage st + 1 has landed (this wavefront's part), barrier: it has landed everywhere and
       // nobody reads the buffer of stage st - 1 any more, which is where stage st + 3 goes
-#ifdef DEINFER_PF_TRACE
-      c1 = __builtin_readcyclecounter();
-#endif
       if (F2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#ifdef DEINFER_PF_TRACE
-      c2 = __builtin_readcyclecounter();
-#endif
       // bare barrier: the wait above is the only ordering needed (loads into LDS are complete when
       // the counter says so; the buffer about to be refilled was last read a whole k-step ago);
       // the fence of __syncthreads() would drain every outstanding load instead
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-#ifdef DEINFER_PF_TRACE
-      c3 = __builtin_readcyclecounter();
-      c_wait += c2 - c1; c_bar += c3 - c2;
-#endif
       // ---- k-step 1; the operands of the next stage's k-step 0 are read along the way
       // (after the last stage these read a stage buffer nobody writes any more; the values are unused)
 #pragma unroll
@@ -416,14 +396,6 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
         for (; st < n_stages; ++st) stage2(st, no);
       }
     }
-#ifdef DEINFER_PF_TRACE
-    c1 = __builtin_readcyclecounter();
-    if (P.trace && blockIdx.x < 2048 && tid == 0) {
-      unsigned long long *tr = P.trace + blockIdx.x * 8;
-      tr[2] = c0 - k_start; tr[3] = c1 - c0;
-    }
-    e_start = c1; c_wait_all = c_wait; c_bar_all = c_bar;
-#endif
   }
   // (lane-derived values are taken afresh so that none has to live through the main loop)
   int tid_e = threadIdx.x;
@@ -532,10 +504,6 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
   };
   load_tab(0);
   __syncthreads();         // the epilogue reuses the LDS buffers (the loads above are in flight meanwhile)
-#ifdef DEINFER_PF_TRACE
-  unsigned long long es[4];
-  es[0] = __builtin_readcyclecounter();
-#endif
   {
     const int wrow = lane_e & 31, wswz = lane_e & (CPR - 1);
     const int whalf = ((lane_e >> 5) ^ ((lane_e >> 3) & 1)) * 8;
@@ -560,10 +528,6 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
     }
     return r;
   };
-#ifdef DEINFER_PF_TRACE
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  es[1] = __builtin_readcyclecounter();
-#endif
   // LDS reads of the next batch are issued before the stores of this one (different units)
   u32x4_t d[2][BQ];
   auto read_batch = [&](int bt, u32x4_t (&dd)[BQ]) {
@@ -610,10 +574,6 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
     if (ROPE && bt + 2 < NBATCH) load_tab(bt + 2);
     if (bt + 1 < NBATCH) read_batch(bt + 1, d[(bt + 1) & 1]);
     store_batch(bt, d[bt & 1]);
-#ifdef DEINFER_PF_TRACE
-    if (bt == NBATCH / 2 - 1) es[2] = __builtin_readcyclecounter();
-    if (bt == NBATCH - 1) es[3] = __builtin_readcyclecounter();
-#endif
   }
   // rare: output rows that are not 16-byte aligned, or the valid columns end inside this chunk
   if (lane_on && !wide) {
@@ -631,16 +591,6 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
       }
     }
   }
-#ifdef DEINFER_PF_TRACE
-  if (P.trace && blockIdx.x < 2048 && tid == 0) {
-    unsigned long long *tr = P.trace + blockIdx.x * 8;
-    tr[0] = w_start; tr[1] = wall_clock64(); tr[4] = __builtin_readcyclecounter() - e_start;
-    tr[5] = es[0] - e_start; tr[6] = es[1] - es[0]; tr[7] = ((es[2] - es[1]) << 32) | (es[3] - es[2]);
-#if DEINFER_PF_TRACE == 2
-    tr[5] = c_wait_all; tr[6] = c_bar_all;     // loop split instead of the epilogue split
-#endif
-  }
-#endif
 #else
   (void)P; (void)bid; (void)n_tblocks; (void)fb_shift;
 #endif

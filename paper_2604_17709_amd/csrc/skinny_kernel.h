@@ -73,9 +73,6 @@ struct SkParams {
   int direct;
   const uint16_t *bias;      // single product only; may be null
   int act;                   // see act_f32
-#ifdef DEINFER_SK_TRACE
-  unsigned long long *trace; // diagnostic build only: per-workgroup wall-clock stamps (100 MHz), 8 words each
-#endif
 };
 
 // NB = 32-token blocks (1, 2 or 4); KBS = k-blocks per stage (4, or 2: half the slab, so that two
@@ -90,13 +87,14 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
   constexpr int XROW = KBS * 64;          // bytes per token row of a stage's activation slab
   constexpr int SPR = KBS * 4;            // 16-byte slots per row = lanes per row of a slab load
   constexpr int RPI = 64 / SPR;           // rows per slab load instruction
+  // Slot swizzle of a token row: a quarter-wave reads 16 consecutive rows at one logical slot, and the
+  // 16 physical (row, slot) positions must fall into 16 different groups of four banks.  A 256-byte row
+  // spans all 64 banks (the slot alone decides: XOR with row % 16); a 128-byte row spans half of them
+  // (row parity picks the half, so the slot is XORed with (row / 2) % 8).
+  auto swz = [](int row) { return SPR == 16 ? (row & 15) : ((row >> 1) & (SPR - 1)); };
   __shared__ __attribute__((aligned(16))) unsigned char xs[SK_SLABS][NB * 32 * XROW];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-#ifdef DEINFER_SK_TRACE
-  const unsigned long long tr_entry = wall_clock64();
-  unsigned long long tr_first = 0, tr_loop = 0, tr_issue = 0;
-#endif
   // consecutive workgroups share the k-range (the same activation slab, kept hot in L2)
   const int g = blockIdx.x % P.n_groups;
   const int part = blockIdx.x / P.n_groups;
@@ -134,7 +132,7 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
     xm[i] = m;
     const int row = RPI * m + lane / SPR;
     xrow[i] = row < P.T ? (unsigned)row * (unsigned)(Q.lda * 2) : OOB;
-    xchunk[i] = (unsigned)(((lane & (SPR - 1)) ^ (row & (SPR - 1))) * 16);
+    xchunk[i] = (unsigned)(((lane & (SPR - 1)) ^ swz(row)) * 16);
   }
   const unsigned xklim = (unsigned)(Q.K * 2 - 16);
 
@@ -175,7 +173,7 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
   constexpr int STEPS = KBS * 2;
   constexpr int DEPTH = NB >= 4 ? 2 : NB == 2 ? 3 : 6;
   auto read_b = [&](int buf, int step, int j) -> u32x4_t {
-    const int slot = (step * 2 + (lane >> 5)) ^ (lane & (SPR - 1));       // step = 2 * k-block + half: 16-byte slot 2 * step + lane / 32
+    const int slot = (step * 2 + (lane >> 5)) ^ swz(b_row);               // step = 2 * k-block + half: 16-byte slot 2 * step + lane / 32
     return *reinterpret_cast<const u32x4_t *>(&xs[buf][(32 * j + b_row) * XROW + slot * 16]);
   };
   // One load of stage `fst` (index 0 .. 7: weights into wn, 8 .. 8 + NX - 1: activation slab rows into slab fbuf).
@@ -224,9 +222,6 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
   // loads of the next stage have arrived" is one constant wait.
   if (n_stages > 0) {
     u32x4_t w0[KBS * 2], w1[KBS * 2], w2[KBS * 2], w3[KBS * 2];
-#ifdef DEINFER_SK_TRACE
-    tr_issue = wall_clock64();
-#endif
     fetch_w(w0, 0); fetch_x(0, 0);
     fetch_w(w1, 1); fetch_x(1, 1);
     fetch_w(w2, 2); fetch_x(2, 2);
@@ -235,9 +230,6 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((SK_SLABS - 2) * (KBS * 2 + NX)) : "memory");
       __builtin_amdgcn_s_barrier();                     // ... everywhere; nobody reads slab (st - 1) % 4 any more
       asm volatile("" ::: "memory");
-#ifdef DEINFER_SK_TRACE
-      if (st == 0) tr_first = wall_clock64();
-#endif
       compute(w, slab, wn, st + SK_SLABS - 1, slab == 0 ? SK_SLABS - 1 : slab - 1);
     };
     for (int st = 0; st < n_stages; st += 4) {
@@ -251,9 +243,6 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // drain the out-of-range tail loads
   }
-#ifdef DEINFER_SK_TRACE
-  tr_loop = wall_clock64();
-#endif
 
   // ---- result: element 4 q + e of block j is feature 8 q + 4 (l / 32) + e, token 32 j + l % 32
   if (P.direct) {
@@ -300,16 +289,6 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
       }
     }
   }
-#ifdef DEINFER_SK_TRACE
-  if (P.trace && blockIdx.x < 2048 && tid == 0) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    unsigned long long *tr = P.trace + blockIdx.x * 8;
-    tr[0] = tr_entry; tr[1] = tr_first; tr[2] = tr_loop; tr[3] = wall_clock64();
-    tr[4] = __builtin_amdgcn_s_getreg(6164);      // XCC_ID
-    tr[5] = __builtin_amdgcn_s_getreg(63492);     // HW_ID
-    tr[6] = n_stages; tr[7] = tr_issue;
-  }
-#endif
 #else
   (void)P;
 #endif

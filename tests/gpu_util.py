@@ -4,6 +4,8 @@ import numpy as np
 
 import synth_inputs as si
 
+from paper_2604_17709_amd import TOKEN_TILE_BOTH  # noqa: F401  (importing the binding loads nothing)
+
 # bf16 and fp32: the stated bars; fp16: the bf16 bar scaled by the ratio of the unit roundoffs (2^-11 / 2^-8), rounded up
 TOL = {"bf16": 1e-2, "f16": 2e-3, "f32": 1e-5}
 

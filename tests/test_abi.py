@@ -24,9 +24,11 @@ def make(d_in=64, d_out=48, r=16, dtype=dn.BF16, layout=dn.LAYOUT_RAW, U=FAKE, V
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "deinfer.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(deinfer_[a-z0-9_]+)\s*\(", header))
+    declared = set()
+    for name in ("deinfer.h", "deinfer_testing.h"):          # the product surface and the test / measurement aids
+        header = open(os.path.join(ROOT, "include", name)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared |= set(re.findall(r"\b(deinfer_[a-z0-9_]+)\s*\(", header))
     assert {"deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
             "deinfer_lowrank_down", "deinfer_lowrank_up"} <= declared
     L = ctypes.CDLL(dn.LIB_PATH)
@@ -231,6 +233,42 @@ def test_pack_and_workspace_queries_are_host_only():
     assert L.deinfer_workspace_init(FAKE, 16, None) == dn.ERR_WORKSPACE
     assert L.deinfer_workspace_init(FAKE + 4, 1 << 20, None) == dn.ERR_MISALIGNED
     assert L.deinfer_workspace_check(None, 1 << 20, None) == dn.ERR_WORKSPACE
+
+
+def _ws_bytes(T, fs):
+    L = dn.lib()
+    FP = ctypes.POINTER(dn.Factors)
+    arr = (FP * len(fs))(*[ctypes.pointer(f) for f in fs])
+    n = ctypes.c_size_t(0)
+    assert L.deinfer_workspace_bytes(T, arr, len(fs), ctypes.byref(n)) == dn.OK
+    return n.value
+
+
+def test_workspace_covers_the_group_that_runs_when_a_pair_has_rank_zero():
+    """A pair of rank 0 is dropped before the dispatch (its output is zero-filled) and the remaining
+    pairs are split afresh: fewer feature groups can admit more k-ranges, i.e. more partial sums, so
+    the size of the group as given must cover the size of the group that runs."""
+    P = dict(dtype=dn.BF16, layout=dn.LAYOUT_PACKED)
+    # the shape of the report: the reduced group needs 4,202,496 bytes
+    q = make(d_in=512, d_out=4096, r=64, **P)
+    k0 = make(d_in=512, d_out=4096, r=0, **P)
+    v = make(d_in=512, d_out=4096, r=64, **P)
+    assert _ws_bytes(17, [q, k0, v]) >= _ws_bytes(17, [q, v]) >= 4202496
+    import itertools
+    import random
+    rng = random.Random(7)
+    worst = 0
+    for _ in range(400):
+        T = rng.choice([1, 8, 16, 17, 31, 32, 33, 64, 65, 100, 128, 129, 300, 700])
+        d_in = 8 * rng.randint(4, 600)
+        fs = [make(d_in=d_in, d_out=rng.choice([64, 1024, 4096, 11008]), r=rng.choice([0, 0, 16, 64, 364, 1638]), **P)
+              for _ in range(rng.randint(2, 3))]
+        full = _ws_bytes(T, fs)
+        for m in range(1, len(fs) + 1):
+            for sub in itertools.combinations(fs, m):
+                if all(f.r > 0 for f in sub) and all(f.r == 0 for f in fs if not any(f is g for g in sub)):
+                    worst = max(worst, _ws_bytes(T, list(sub)) - full)
+    assert worst <= 0
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -1,4 +1,4 @@
-"""Paged low-rank cache -> compact buffer -> rebuilt keys with rotary embedding (Sec. 4.3), on the
+"""Paged low-rank cache -> compact buffer -> rebuilt keys with rotary embedding (Sec. 4.2), on the
 GPU through the C-ABI, against the CPU oracle: byte-exact for the copy, within the bf16 / fp32
 tolerance for the arithmetic, and replayed from one captured graph with changing block tables."""
 import numpy as np
@@ -7,7 +7,7 @@ import pytest
 import oracle
 import synth_inputs as si
 from oracle import paged_cache as pc
-from gpu_util import TOL, max_err, pair, to_dev, to_host
+from gpu_util import TOKEN_TILE_BOTH, TOL, max_err, pair, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -21,7 +21,7 @@ def dn():
     return dn
 
 
-@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256), (384, 0)], ids=["tiles-auto", "tiles-256", "tiles-128x256", "tiles-mixed"])
+@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256), (TOKEN_TILE_BOTH, 0)], ids=["tiles-auto", "tiles-256", "tiles-128x256", "tiles-mixed"])
 def token_tile(request, dn):
     """Every test runs with the workgroup tile of the T > 128 kernel chosen per launch (small shapes then
     take the 128 x 128 tile), with 256-token tiles forced, with 128 x 256 tiles forced, and with both

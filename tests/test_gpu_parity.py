@@ -6,7 +6,7 @@ import pytest
 
 import oracle
 import synth_inputs as si
-from gpu_util import TOL, max_err, pair, to_dev, to_host
+from gpu_util import TOKEN_TILE_BOTH, TOL, max_err, pair, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -20,7 +20,7 @@ def dn():
     return dn
 
 
-@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256), (384, 0)], ids=["tiles-auto", "tiles-256", "tiles-128x256", "tiles-mixed"])
+@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256), (TOKEN_TILE_BOTH, 0)], ids=["tiles-auto", "tiles-256", "tiles-128x256", "tiles-mixed"])
 def token_tile(request, dn):
     """Every test runs with the workgroup tile of the T > 128 kernel chosen per launch (small shapes then
     take the 128 x 128 tile), with 256-token tiles forced, with 128 x 256 tiles forced, and with both
@@ -139,6 +139,34 @@ def test_group_calls_packed(dn, T):
         assert max_err(to_host(got), ref) <= TOL["bf16"]
     assert max_err(to_host(h), oracle.lowrank_gateup_silu(x.values, *host["g"], *host["u"])) <= TOL["bf16"]
     assert max_err(to_host(y), oracle.lowrank_down(x.values, *host["d"])) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("T", [17, 40, 100, 128, 300])
+def test_qkv_with_a_rank_zero_pair_in_an_exactly_sized_workspace(dn, T):
+    """k has rank 0: its output is zero-filled and q, v run as a group of two, which splits differently
+    from the group of three the workspace was sized for; the workspace has exactly the queried size
+    and a guard region behind it stays untouched."""
+    import torch
+    d_in = 512
+    x = si.make(21, 1, (T, d_in), 1.0, "bf16")
+    F, host = {}, {}
+    for i, (n, (r, d_out)) in enumerate({"q": (64, 4096), "v": (64, 4096)}.items()):
+        U = si.make(21, 10 + 2 * i, (d_in, r), 1.0 / np.sqrt(d_in), "bf16")
+        V = si.make(21, 11 + 2 * i, (r, d_out), 1.0 / np.sqrt(r), "bf16")
+        F[n], _k = pair(dn, U, V, packed=True)
+        host[n] = (U.values, V.values)
+    k0 = dn.deinfer_pack_factors(dn.raw_pair(torch.zeros((d_in, 0), dtype=torch.bfloat16, device="cuda"),
+                                             torch.zeros((0, 4096), dtype=torch.bfloat16, device="cuda")))
+    need = dn.deinfer_workspace_bytes(T, [F["q"], k0, F["v"]])
+    guard = 1 << 20
+    buf = torch.full((need + guard,), 0x5A, dtype=torch.uint8, device="cuda")
+    ws = dn.Workspace(need, buf=buf[:need])
+    q, k, v = dn.deinfer_lowrank_qkv(to_dev(x), F["q"], k0, F["v"], ws)
+    ws.check()
+    assert bool((buf[need:] == 0x5A).all()), "the call wrote past the end of its workspace"
+    assert float(k.abs().max()) == 0.0
+    assert max_err(to_host(q), oracle.lowrank_linear(x.values, *host["q"])) <= TOL["bf16"]
+    assert max_err(to_host(v), oracle.lowrank_linear(x.values, *host["v"])) <= TOL["bf16"]
 
 
 @pytest.mark.parametrize("packed", [False, True])
@@ -467,7 +495,7 @@ def test_token_tiles_give_identical_results(dn, dtype, T):
     ws = dn.Workspace(max(dn.deinfer_workspace_bytes(T, [F["q"], F["k"], F["v"]]),
                           dn.deinfer_workspace_bytes(T, [F["g"], F["u"]])))
     res = {}
-    for tile in (128, 129, 256, 384):              # 128: 128 x 128 tiles, 129: 128 x 256 tiles, 384: two shapes in one launch
+    for tile in (128, 129, 256, TOKEN_TILE_BOTH):  # 128: 128 x 128 tiles, 129: 128 x 256 tiles, the last: two shapes in one launch
         dn.deinfer_set_prefill_token_tile(128 if tile == 129 else tile)
         dn.deinfer_set_prefill_feature_tile(256 if tile == 129 else 128 if tile == 128 else 0)
         tk = torch.zeros((T, 24), dtype=xd.dtype, device="cuda")
@@ -480,7 +508,7 @@ def test_token_tiles_give_identical_results(dn, dtype, T):
         res[tile] = [t.clone() for t in (q, k, v, tk, h, a, k2)]
     dn.deinfer_set_prefill_token_tile(0)
     dn.deinfer_set_prefill_feature_tile(0)
-    for t128, t129, t256, t384 in zip(res[128], res[129], res[256], res[384]):
+    for t128, t129, t256, t384 in zip(res[128], res[129], res[256], res[TOKEN_TILE_BOTH]):
         assert torch.equal(t128.view(torch.int16), t256.view(torch.int16))
         assert torch.equal(t129.view(torch.int16), t256.view(torch.int16))
         assert torch.equal(t384.view(torch.int16), t256.view(torch.int16))

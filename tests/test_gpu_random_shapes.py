@@ -9,7 +9,7 @@ import pytest
 
 import oracle
 import synth_inputs as si
-from gpu_util import TOL, max_err, pair, to_dev, to_host
+from gpu_util import TOKEN_TILE_BOTH, TOL, max_err, pair, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -23,7 +23,7 @@ def dn():
     return dn
 
 
-@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256), (384, 0)], ids=["tiles-auto", "tiles-256", "tiles-128x256", "tiles-mixed"])
+@pytest.fixture(autouse=True, params=[(0, 0), (256, 0), (128, 256), (TOKEN_TILE_BOTH, 0)], ids=["tiles-auto", "tiles-256", "tiles-128x256", "tiles-mixed"])
 def token_tile(request, dn):
     """Every test runs with the workgroup tile of the T > 128 kernel chosen per launch (small shapes then
     take the 128 x 128 tile), with 256-token tiles forced, with 128 x 256 tiles forced, and with both

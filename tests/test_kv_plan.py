@@ -1,4 +1,4 @@
-"""Host side of the paged-cache path (Sec. 4.3, preparation stage): the library's scan against the
+"""Host side of the paged-cache path (Sec. 4.2, preparation stage): the library's scan against the
 oracle's, bit for bit; runs on the CPU (the plan function touches no device)."""
 import ctypes
 
