@@ -156,6 +156,24 @@ int deinfer_lowrank_gateup_silu(const void *x, int64_t T, int64_t ldx,
                                 void *h, int64_t ldh, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * deinfer_lowrank_linear for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * product and same kernels as deinfer_lowrank_linear; the scratch (rank-space intermediate,
+ * partial sums) is a static device array of DEINFER_STATIC_SCRATCH_BYTES inside the library, one
+ * copy per GPU, held until the process ends.  The call allocates nothing (no hipMalloc / hipFree,
+ * no allocating library routine); on the first call per device it looks the array's device address
+ * up.  Limits: calls whose deinfer_workspace_bytes exceeds DEINFER_STATIC_SCRATCH_BYTES return
+ * DEINFER_ERR_WORKSPACE and enqueue nothing (decode-sized calls up to the 70B shapes at 128 tokens
+ * fit).  Every call on one GPU uses that GPU's one array: calls that overlap in time on one GPU
+ * (different streams, or graphs replayed concurrently) race; serialise them or use
+ * deinfer_lowrank_linear with separate workspaces.  Nothing in the array has to survive between
+ * calls and nothing has to be cleared.  Otherwise the contract of deinfer_lowrank_linear.
+ */
+#define DEINFER_STATIC_SCRATCH_BYTES (32u << 20)
+int deinfer_lowrank_linear_static(const void *x, int64_t T, int64_t ldx, const deinfer_factors_t *f,
+                                  void *y, int64_t ldy, void *stream);
+
+/*
  * Upward projection alone (Sec. 2.1 / 4.1: the low-rank KV cache stores k_low_rank = x U_k and
  * v_low_rank = x U_v; keys and values are rebuilt as k = k_low_rank V_k when attention needs
  * them):  y[T x d_out] = t[T x r] . V.   t: device, row-major, pitch ldt >= r, same dtype as

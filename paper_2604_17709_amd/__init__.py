@@ -28,6 +28,7 @@ F16 = 2
 LAYOUT_RAW = 0
 LAYOUT_PACKED = 1
 PROF_DECODE_DOWN, PROF_DECODE_REDUCE, PROF_DECODE_UP, PROF_PREFILL_DOWN, PROF_PREFILL_UP = 1, 2, 3, 4, 5
+STATIC_SCRATCH_BYTES = 32 << 20   # DEINFER_STATIC_SCRATCH_BYTES
 TOKEN_TILE_BOTH = 384         # deinfer_set_prefill_token_tile: both tile shapes in one launch (deinfer_testing.h)
 
 _i64 = ctypes.c_int64
@@ -56,7 +57,7 @@ EXPORTS = [
     "deinfer_rank_for_ratio", "deinfer_probe_stream_read", "deinfer_probe_mfma_bf16",
     "deinfer_packed_bytes", "deinfer_pack_factors",
     "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
-    "deinfer_lowrank_linear", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
+    "deinfer_lowrank_linear", "deinfer_lowrank_linear_static", "deinfer_lowrank_qkv", "deinfer_lowrank_gateup_silu",
     "deinfer_lowrank_down", "deinfer_lowrank_up", "deinfer_lowrank_linear_act",
     "deinfer_lowrank_down_proj", "deinfer_lowrank_up_glu_silu",
     "deinfer_kv_compact_plan", "deinfer_kv_compact_copy", "deinfer_rope_inplace",
@@ -99,6 +100,7 @@ def lib() -> ctypes.CDLL:
         L.deinfer_workspace_check.argtypes = [_vp, _sz, _vp]
         L.deinfer_lowrank_linear.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_down.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
+        L.deinfer_lowrank_linear_static.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp]
         L.deinfer_lowrank_up.argtypes = [_vp, _i64, _i64, FP, _vp, _i64, _vp, _sz, _vp]
         L.deinfer_lowrank_down_proj.argtypes = [_vp, _i64, _i64, ctypes.POINTER(FP), ctypes.c_int,
                                                 ctypes.POINTER(_vp), ctypes.POINTER(_i64), _vp, _sz, _vp]
@@ -261,6 +263,13 @@ def deinfer_lowrank_linear(x, pair: Pair, ws: Workspace, out=None, stream=None):
         out = torch.empty((T, pair.d_out), dtype=x.dtype, device=x.device)
     _check(lib().deinfer_lowrank_linear(_ptr(x), T, _ld(x), ctypes.byref(pair.desc),
                                         _ptr(out), _ld(out), _ptr(ws.buf), ws.nbytes, _stream(stream)))
+    return out
+
+
+def deinfer_lowrank_linear_static(x, pair: Pair, out, stream=None):
+    """y = (x U) V with the library's static device scratch: no workspace, nothing allocated (``out`` is the caller's)."""
+    T = _rows(x, "x")
+    _check(lib().deinfer_lowrank_linear_static(_ptr(x), T, _ld(x), ctypes.byref(pair.desc), _ptr(out), _ld(out), _stream(stream)))
     return out
 
 

@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
 #include "decode_kernel.h"
@@ -892,6 +893,51 @@ int deinfer_lowrank_linear(const void *x, int64_t T, int64_t ldx, const deinfer_
   g.x = x; g.T = T; g.ldx = ldx; g.n = 1; g.f[0] = f; g.out[0] = y; g.ldo[0] = ldy;
   g.glu = false; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = static_cast<hipStream_t>(stream);
   return run_group(g);
+}
+
+// ---- the entry point that takes no workspace: its scratch is a static device array
+}  // extern "C"
+
+namespace {
+// One copy per GPU that loads the library, held until the process ends.  In host code the name is
+// only a handle for hipGetSymbolAddress: the device address it yields (one per device) is what
+// kernels and host calls are given.
+static __device__ __align__(256) unsigned char scratch[DEINFER_STATIC_SCRATCH_BYTES];
+void *g_scratch_ptr[64];                 // per device, set once (under g_scratch_mutex)
+std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up on the first call per device).
+int static_scratch(void **out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return fail(DEINFER_ERR_DEVICE, "no usable HIP device");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void *ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr)
+      return fail(DEINFER_ERR_DEVICE, "cannot locate the static scratch array on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;            // (a static device array starts zero-filled: the status words need no clearing)
+  }
+  *out = g_scratch_ptr[dev];
+  return DEINFER_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int deinfer_lowrank_linear_static(const void *x, int64_t T, int64_t ldx, const deinfer_factors_t *f,
+                                  void *y, int64_t ldy, void *stream) {
+  if (int rc = validate_pair(f, "pair 0")) return rc;
+  if (T < 0) return fail(DEINFER_ERR_INVALID_ARG, "T is negative");
+  const deinfer_factors_t *pairs[1] = {f};
+  const size_t need = workspace_need(T, pairs, 1);
+  if (need > (size_t)DEINFER_STATIC_SCRATCH_BYTES)
+    return fail(DEINFER_ERR_WORKSPACE, "this call needs %zu bytes of scratch, the static scratch array holds %zu: "
+                "use deinfer_lowrank_linear with a workspace of the caller's", need, (size_t)DEINFER_STATIC_SCRATCH_BYTES);
+  void *ws = nullptr;                    // (T == 0 returns before the workspace is looked at)
+  if (T > 0)
+    if (int rc = static_scratch(&ws)) return rc;
+  return deinfer_lowrank_linear(x, T, ldx, f, y, ldy, ws, (size_t)DEINFER_STATIC_SCRATCH_BYTES, stream);
 }
 
 int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_factors_t *f,

@@ -271,6 +271,21 @@ def test_workspace_covers_the_group_that_runs_when_a_pair_has_rank_zero():
     assert worst <= 0
 
 
+def test_static_scratch_entry_point_validates_on_the_host():
+    L = dn.lib()
+    f = make(d_in=4096, d_out=4096, r=1638, layout=dn.LAYOUT_PACKED)
+    assert L.deinfer_lowrank_linear_static(FAKE, 4, 4096, None, FAKE, 4096, None) == dn.ERR_INVALID_ARG
+    assert L.deinfer_lowrank_linear_static(FAKE, -1, 4096, ctypes.byref(f), FAKE, 4096, None) == dn.ERR_INVALID_ARG
+    # more scratch than the static array holds: refused before anything touches a device
+    assert _ws_bytes(1 << 16, [f]) > dn.STATIC_SCRATCH_BYTES
+    assert L.deinfer_lowrank_linear_static(FAKE, 1 << 16, 4096, ctypes.byref(f), FAKE, 4096, None) == dn.ERR_WORKSPACE
+    assert "static scratch" in dn.last_error()
+    assert _ws_bytes(128, [f]) <= dn.STATIC_SCRATCH_BYTES          # decode-sized calls fit
+    assert L.deinfer_lowrank_linear_static(FAKE, 0, 4096, ctypes.byref(f), FAKE, 4096, None) == dn.OK
+    header = open(os.path.join(ROOT, "include", "deinfer.h")).read()
+    assert "#define DEINFER_STATIC_SCRATCH_BYTES (32u << 20)" in header and dn.STATIC_SCRATCH_BYTES == 32 << 20
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(dn, "_lib", None)
     monkeypatch.setattr(dn, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
