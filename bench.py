@@ -11,11 +11,17 @@ several independent copies of the packed weights (>= 1.5 GB in total).
 
 Prints ONE JSON line: metric, value (tokens/s of the step), ms_per_step, per-call timings,
 "roofline" (the dominant launch of the call with the most work, timed with HIP events that the library
-records around that launch, against the HBM or bf16 MFMA peak; "measured_ceiling" inside it is
-what a plain read of the same bytes, or a loop of nothing but matrix products, reaches on the
-same device), for the default workload "second_row_r2357" (the same block with the ranks the
-configuration prints instead of the ones its rule gives) and "cpu_baseline" (the fp64
-oracle on the host's cores, on a bounded sample of the same workload).
+records around that launch on the launch stream, against the HBM or bf16 MFMA peak; "step_frac" inside
+it is the whole step against the same peak; "measured_ceiling" is what a plain read of the same
+bytes, or a loop of nothing but matrix products, reaches on the same device) and "cpu_baseline" (the
+fp64 oracle on the host's cores, on a bounded sample of the same workload).
+
+The default workload is the largest single-GPU configuration, the Llama-70B-shaped layer with GQA at
+60 % parameter reduction, at its decode size (T = 128).  The default run adds, from child processes,
+"prefill" (the same layer at T = 4096, with its own ms_per_step and MFMA roofline) and
+"llama7b_keep80_decode_T64" (the 7B-shaped block at 64 tokens, its sweep over 1 / 8 / 32 tokens and
+"second_row_r2357": the same block with the ranks the configuration prints instead of the ones its
+rule gives).
 
 --workload llama7b_keep80_kv_rebuild times a different step: keys and values of 8192 cached
 tokens rebuilt from the paged low-rank cache (compacting copy, upward projections at the
@@ -51,6 +57,10 @@ WORKLOADS = {
     "opt30b_keep60_decode": ("opt30b_keep60", 64, "hbm"),
     "opt30b_keep60_prefill": ("opt30b_keep60", 4096, "mfma"),
 }
+# The default run: the largest single-GPU configuration (70B-shaped layer with GQA, 60 % parameter
+# reduction) at its decode size; its prefill size and the 7B-shaped block at 64 tokens are timed in child
+# processes and reported as secondary objects of the same JSON line.
+DEFAULT_WORKLOAD = "llama70b_keep40_decode"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
@@ -60,7 +70,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama7b_keep80_decode", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
     ap.add_argument("--T", type=int, default=0, help="tokens per step (0 = the workload's default)")
     ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
                     help="replay the step from a captured HIP graph, or launch each call directly")
@@ -72,6 +82,9 @@ def parse():
     ap.add_argument("--traffic-calibration", type=int, default=0, metavar="MIB",
                     help="do nothing but five plain device-to-device copies of MIB MiB (a kernel of known traffic, for "
                          "scaling the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc) and exit")
+    ap.add_argument("--no-extra-rows", action="store_true",
+                    help="default workload only: skip the secondary rows (the same layer at its prefill size, the 7B-shaped "
+                         "block at 64 tokens with its sweep over smaller batches)")
     ap.add_argument("--no-second-row", action="store_true",
                     help="skip the second row of the default workload (the ranks that the configuration prints, 2357)")
     return ap.parse_args()
@@ -324,12 +337,15 @@ def main():
             kbytes["up"] = w_out + s * T * sum(ranks[p] for p in ps) + s * T * sum(outs)
     entry = {"qkv": "qkv", "o": "linear", "gateup": "gateup_silu" if shape.glu else "linear_act",
              "down": "down" if shape.glu else "linear_act"}[dom]
-    traffic = None
+    # HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs of the same command
+    # (FETCH_SIZE, WRITE_SIZE, scaled by a copy of known size): a committed summary, not measured in this run
+    traffic, traffic_source = None, None
     tfile = os.path.join(ROOT, "profiles", "hbm_traffic_%s_T%d.txt" % (args.workload, T))
     if os.path.exists(tfile):
         for line in open(tfile):
             if line.startswith("traffic_bytes_per_launch"):
                 traffic = float(line.split("=")[1])
+                traffic_source = "profiles/" + os.path.basename(tfile)
     if bound == "hbm":
         ach = kbytes[kdom] / ksec / 1e9
         roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -341,6 +357,7 @@ def main():
     roofline["kernel"] = ("%s kernel (%s%s-projection launch of deinfer_lowrank_%s)"
                           % (("decode_kernel" if T <= 16 else "skinny_kernel") if decode else "prefill_kernel",
                              "last " if (not decode and kdom == "up" and dom == "gateup" and shape.glu) else "", kdom, entry))
+    roofline["traffic_source"] = traffic_source
     roofline["avg_launch_us"] = round(ksec * 1e6, 2)
     roofline["algorithmic_bytes_per_launch"] = kbytes[kdom]
     roofline["algorithmic_flops_per_launch"] = kflops[kdom]
@@ -427,6 +444,7 @@ def main():
         "roofline": roofline,
         "setup_s": round(setup_s, 1),
     }
+    roofline["step_frac"] = out["step_frac_of_roofline"]     # the whole step against the same peak, beside the dominant launch
 
     # ---------------------------------------------------------------- other decode sizes
     if args.sweep and T <= 128:
@@ -458,6 +476,26 @@ def main():
                                        "step_frac_of_roofline": row["step_frac_of_roofline"]}
         except Exception as e:  # noqa: BLE001 - the main row stands on its own
             out["second_row_r2357"] = {"error": "%s: %s" % (type(e).__name__, res.stderr[-300:])}
+
+    # ---------------------------------------------------------------- secondary rows of the default run (child processes)
+    if args.workload == DEFAULT_WORKLOAD and not args.no_extra_rows and not args.rank_override and args.dtype == "bf16" and not args.T:
+        import subprocess
+
+        def child(extra):
+            cmd = [sys.executable, os.path.abspath(__file__), "--steps", str(args.steps), "--warmup", str(args.warmup),
+                   "--launch", args.launch, "--seed", str(args.seed), "--no-cpu-baseline", "--no-extra-rows"] + extra
+            res = subprocess.run(cmd, capture_output=True, text=True)
+            try:
+                return json.loads(res.stdout.strip().splitlines()[-1])
+            except Exception as e:  # noqa: BLE001 - the main row stands on its own
+                return {"error": "%s: %s" % (type(e).__name__, res.stderr[-300:])}
+
+        keep = ("value", "unit", "ms_per_step", "step_frac_of_roofline", "step_GBs", "step_TFLOPs", "calls", "roofline", "config")
+        # free this process's copies of the weights first: the children need the memory bandwidth, not the space
+        row = child(["--workload", "llama70b_keep40_prefill"])
+        out["prefill"] = row if "error" in row else {k_: row[k_] for k_ in keep if k_ in row}
+        row = child(["--workload", "llama7b_keep80_decode", "--sweep"])
+        out["llama7b_keep80_decode_T64"] = row if "error" in row else {k_: row[k_] for k_ in keep + ("sweep", "second_row_r2357") if k_ in row}
 
     # ---------------------------------------------------------------- CPU baseline: the oracle, as it stands
     if not args.no_cpu_baseline:
