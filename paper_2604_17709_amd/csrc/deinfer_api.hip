@@ -181,11 +181,14 @@ SkPlan skinny_plan(int64_t T, const deinfer_factors_t *const *f, int n, bool glu
   return pl;
 }
 
-// ---- k-split of the first stage of a compute-bound call with few token blocks
-// Stage 1 has a long k (d_in) and few features (the ranks): with T of a few hundred tokens its
-// 256 x 256 tiles are far fewer than the compute units.  The k range is then cut into up to 8
-// parts (fp32 partial products, summed by the reduce kernel of the T <= 128 path).  Stage 2
-// (short k, many features) is left whole: its partial products would cost more than they save.
+// ---- k-split of the first stage of a compute-bound call
+// Stage 1 has a long k (d_in) and few features (the ranks), so its 256 x 256 tiles can be far fewer
+// than the compute units (a few hundred tokens), or fill the last round of workgroups badly (160
+// tiles of k = 28672 on 256 units: the second MLP layer of the 70B shapes at 4096 tokens).  The k
+// range is then cut into parts (fp32 partial products, summed by the reduce kernel of the T <= 128
+// path).  Stage 2 (short k, many features) is left whole: its partial products would cost more than
+// they save.  The number of parts minimises an estimate of the launch time in units of one pipeline
+// stage of one tile (about 0.7 us): rounds of workgroups x (stages + epilogue) + the reduce launch.
 struct PfSplitPlan {
   int n_parts, kb_per_part, n_fblocks, n_tblocks;
   size_t part_bytes;          // 0: no split
@@ -200,15 +203,33 @@ PfSplitPlan prefill_split_plan(int64_t T, const deinfer_factors_t *const *f, int
   pl.n_fblocks = (int)ceil_div(tiles, 16);
   pl.n_parts = 1; pl.kb_per_part = (int)KB;
   const int64_t wgs = (int64_t)pl.n_tblocks * pl.n_fblocks;
-  if (wgs <= 0 || wgs > 128 || KB < 16) return pl;
-  int64_t p = 256 / wgs;
-  const int64_t cap = wgs <= 8 ? SK_MAX_PARTS : 8;      // 16 parts only for a handful of tiles
-  if (p > cap) p = cap;
-  if (p > KB / 8) p = KB / 8;                       // at least 8 pipeline stages per part
-  if (p < 2) return pl;
-  pl.kb_per_part = (int)ceil_div(KB, p);
-  pl.n_parts = (int)ceil_div(KB, pl.kb_per_part);   // every part is non-empty
-  pl.part_bytes = (size_t)pl.n_parts * pl.n_tblocks * 256 * (size_t)pl.n_fblocks * 256 * sizeof(float);
+  if (wgs <= 0 || KB < 16) return pl;
+  const int cus_now = device_cus();
+  const int64_t cus = cus_now > 0 ? cus_now : 256;
+  // measured on the device: epilogue of a tile that rounds and stores t (about 8 stages) or stores
+  // its fp32 partial products (about 20: 256 KiB per workgroup, all units at once); a 128 x 256 tile
+  // takes 0.64 of a 256 x 256 tile in the last round of a large launch and 0.78 in a launch of its own
+  // (70B shapes, o-projection at 4096 tokens: 138 us unsplit against 106 + 18 us as two parts); the reduce launch reads its partial products at about 0.3 us per
+  // MB (0.43 stages) after about 4 us (6 stages) of fixed cost
+  constexpr double E_PLAIN = 8.0, E_PART = 20.0, SMALL_TILE = 0.64, SMALL_TILES_ONLY = 0.78, REDUCE_PER_MB = 0.43, REDUCE_FIXED = 6.0;
+  auto rounds = [&](int64_t w, bool two_shapes) {
+    const int64_t full = w / cus, tail = w % cus;
+    if (tail == 0) return (double)full;
+    if (two_shapes && full >= 1 && 2 * tail <= cus) return (double)full + SMALL_TILE;   // the last round as 128 x 256 tiles
+    return (double)full + 1.0;
+  };
+  const double whole = (2 * wgs <= cus ? SMALL_TILES_ONLY : rounds(wgs, true)) * ((double)KB + E_PLAIN);
+  const double part_mb = (double)pl.n_tblocks * 256.0 * (double)pl.n_fblocks * 256.0 * 4.0 / 1.0e6;
+  const int64_t p_max = KB / 8 < SK_MAX_PARTS ? KB / 8 : SK_MAX_PARTS;     // at least 8 pipeline stages per part
+  double best = 0.93 * whole;                                             // a split has to win by 7 %
+  for (int64_t p = 2; p <= p_max; ++p) {
+    const int64_t kbp = ceil_div(KB, p);
+    if (ceil_div(KB, kbp) != p) continue;                                  // every part is non-empty
+    const double est = rounds(wgs * p, false) * ((double)kbp + E_PART) + (double)p * part_mb * REDUCE_PER_MB + REDUCE_FIXED;
+    if (est < best) { best = est; pl.n_parts = (int)p; pl.kb_per_part = (int)kbp; }
+  }
+  if (pl.n_parts > 1)
+    pl.part_bytes = (size_t)pl.n_parts * pl.n_tblocks * 256 * (size_t)pl.n_fblocks * 256 * sizeof(float);
   return pl;
 }
 

@@ -4,11 +4,12 @@
 // with the weights W[F x K] in packed MFMA-fragment order:
 //   stage 1  act = x,  W = [U_a | U_b | U_c]^T (concatenated feature axis), out = t (bf16, one
 //            nearest-even rounding, row-major so that it is stage 2's activation operand);
-//   stage 2  act = t,  W = V^T of one pair, out = y.  The GLU call runs the gate product first
-//            (bf16 result stored in the output buffer) and then the up product, whose epilogue
-//            reads the gate values back and stores silu(gate) * up in their place: both products
-//            keep the full 256 x 256 tile, which a side-by-side accumulation (half the tile per
-//            product, 1.5 x the LDS and L2 traffic per flop) does not.
+//   stage 2  act = t,  W = V^T of one pair, out = y.  The GLU call computes both products of a
+//            tile in one workgroup, one after the other on the same accumulators: the gate product,
+//            then silu of it rounded to the storage type into 128 registers that the main loop
+//            leaves free, then the up product, whose epilogue multiplies the two: the full-width
+//            gate and up results never leave the registers (a side-by-side accumulation, half the
+//            tile per product, would need 1.5 x the LDS traffic per flop).
 // t makes one round trip through HBM / Infinity Cache (<= 75 MB, a few percent of the MFMA
 // time); a 256-row t tile does not fit the 160 KB LDS at these ranks.
 //
@@ -113,7 +114,8 @@ struct PfShared {
   unsigned char x[pf_stages(TB, MF)][64 * TB * PF_XPITCH];  // [stage][token row * 64 bytes], slots swizzled
 };
 
-// GLU = true: the output buffer already holds the gate values g (bf16); store silu(g) * result.
+// GLU = true: two products per tile, P.prob[0] (gate) and P.prob[1] (up, same feature tiles and output):
+// out = silu(gate product) * up product.
 // POST = true: bias and activation of the non-GLU MLP sub-layer on the fp32 accumulators.
 // SPLIT = true: this workgroup multiplies only its part of the k range and stores the fp32
 // accumulators to a partial buffer (the sum and the epilogue are a second, small kernel's).
@@ -165,8 +167,12 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const PfProblem &Q = P.prob[pi];
-  {
+  // GLU: silu(gate product), rounded once to the storage type, kept in registers (as pairs) while the
+  // up product is accumulated: element [i][j][g] holds the four values of accumulator elements 4 g .. 4 g + 3
+  uint2 gpk[GLU ? MB : 1][GLU ? TB : 1][4];
+  // One product of this workgroup's tile: acc += act . W^T over the whole k range of Q.  between() runs
+  // once the first pipeline stages have been requested and before they are waited for.
+  auto product = [&](const PfProblem &Q, auto &&between) {
     // ---- load assignment (every instruction moves 1 KiB: lane l -> LDS base + 16 l).
     // Buffer addressing: a scalar resource descriptor, a scalar byte offset for the k position
     // and one 32-bit per-lane offset, which leaves the registers to the accumulators; reads
@@ -246,6 +252,9 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
       if (n_stages > 2) {
 #pragma unroll
         for (int i = 0; i < H1; ++i) fetch_part(2, i);
+      }
+      between();
+      if (n_stages > 2) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS + H1) : "memory");
       } else if (n_stages > 1) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");
@@ -266,6 +275,7 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
 #pragma unroll
         for (int i = 0; i < H1; ++i) fetch_part(D - 1, i);
       }
+      between();
       // outstanding at most: the stages after stage 0 (and the half stage D - 1)
       if (D - 1 < n_stages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS + H1) : "memory");
       else PfVmWait<0, D - 2, LPS, 0>::run(n_stages - 1);
@@ -396,7 +406,41 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
         for (; st < n_stages; ++st) stage2(st, no);
       }
     }
+  };
+  if constexpr (GLU) {
+    // Both products of the tile in this workgroup (Sec. 4.1: gate and up share x and the output
+    // columns): the gate product first; its silu goes into registers while the up product's first
+    // stages are on their way; the full-width gate and up results never reach memory.
+    product(P.prob[0], [] {});
+    __syncthreads();       // every wavefront has read its last gate-product operands: the stage buffers are free
+    product(P.prob[1], [&] {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < TB; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            // (the sums are taken out of the accumulator registers here, by hand: the compiler would
+            // move all 256 of them to ordinary registers at the end of the gate product's loop, where
+            // they would have to live through the requests above)
+            float z[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(z[e]) : "a"(acc[i][j][4 * g + e]));
+              acc[i][j][4 * g + e] = 0.f;
+            }
+            gpk[i][j][g].x = pack2<DT>(silu_f32(z[0]), silu_f32(z[1]));
+            gpk[i][j][g].y = pack2<DT>(silu_f32(z[2]), silu_f32(z[3]));
+            // (the packed values are made opaque here: otherwise the compiler defers silu to the
+            // epilogue and keeps all 256 raw gate sums alive through the second product's loop)
+            asm volatile("" : "+v"(gpk[i][j][g].x), "+v"(gpk[i][j][g].y));
+          }
+    });
+  } else {
+    product(P.prob[pi], [] {});
   }
+  const PfProblem &Q = P.prob[pi];         // (GLU: the gate problem; output buffer and width are the same for both)
   // (lane-derived values are taken afresh so that none has to live through the main loop)
   int tid_e = threadIdx.x;
   asm volatile("" : "+v"(tid_e));
@@ -418,8 +462,11 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
         }
     return;
   }
-  // accumulators -> bf16 pairs first (registers only): it overlaps the wait for the slowest wavefront
-  uint2 pk[MB][TB][4];
+  // accumulators -> bf16 pairs first (registers only): it overlaps the wait for the slowest wavefront.
+  // (GLU: not ahead of the barrier: 128 registers of pairs beside the 128 of the gate values would not
+  // fit; every pair is formed right before it is written to LDS instead)
+  uint2 pk[GLU ? 1 : MB][GLU ? 1 : TB][4];
+  if constexpr (!GLU) {
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -439,10 +486,11 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = act_f32(v[e] + b[e], Q.post_act);
         }
-        pk[i][j][g].x = pack2<DT>(v[0], v[1]);
-        pk[i][j][g].y = pack2<DT>(v[2], v[3]);
+        pk[GLU ? 0 : i][GLU ? 0 : j][g].x = pack2<DT>(v[0], v[1]);
+        pk[GLU ? 0 : i][GLU ? 0 : j][g].y = pack2<DT>(v[2], v[3]);
       }
     }
+  }
 
   // ---- epilogue: through LDS (free once the barrier below has passed), so that the global
   // stores are 16 bytes per lane and whole contiguous rows per group of lanes (storing straight
@@ -469,23 +517,9 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
   const int tok_base = tok0 + wt_e * WTOK + rsub;
   uint16_t *dst = out + (long long)tok_base * ldo + col;
   constexpr int NQ = WTOK / RPI;                   // store instructions per wavefront
-  constexpr int NBATCH = ((GLU || ROPE) ? 8 : 4) * TB / 4, BQ = NQ / NBATCH;   // ... handled in batches (register budget)
+  constexpr int NBATCH = (ROPE ? 8 : 4) * TB / 4, BQ = NQ / NBATCH;   // ... handled in batches (register budget)
   const bool lane_wide = lane_on && wide;
-  // GLU: the gate values of a batch are requested two batches ahead (the first one before the
-  // accumulators go through LDS): one batch of silu and stores is shorter than a loaded device's
-  // memory latency
-  constexpr int GR = 3;                            // gate batches in registers: loads run two batches ahead
-  u32x4_t gate[GR][GLU ? BQ : 1];
-  auto load_gate = [&](int bt) {
-#pragma unroll
-    for (int qq = 0; qq < BQ; ++qq) {
-      const int q = bt * BQ + qq;
-      gate[bt % GR][GLU ? qq : 0] = u32x4_t{0u, 0u, 0u, 0u};
-      if (lane_wide && tok_base + q * RPI < P.T)
-        gate[bt % GR][GLU ? qq : 0] = *reinterpret_cast<const u32x4_t *>(dst + (long long)(q * RPI) * ldo);
-    }
-  };
-  if (GLU) load_gate(0);
+  constexpr int GR = 3;                            // table batches in registers: loads run two batches ahead
   // ROPE: this lane's 8 table values per row (cosines for the chunks of a head's first half, sines for
   // the others; the lane 8 further round the row of 16 lanes holds the other kind), two batches ahead
   // like the gate values.  All lanes load: the table row is clamped to the last token, never skipped.
@@ -512,22 +546,25 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
 #pragma unroll
       for (int j = 0; j < TB; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-          *reinterpret_cast<uint2 *>(E + (32 * j + wrow) * PITCH + (((4 * i + g) ^ wswz) * 16) + whalf) = pk[i][j][g];
-  }
-  if (GLU && NBATCH > 1) load_gate(1);             // (the packed accumulators have left their registers)
-  if (ROPE && NBATCH > 1) load_tab(1);
-  // h = silu(g) * u on the bf16 values of both products, one rounding of the result
-  auto glu = [&](u32x4_t g, u32x4_t u) -> u32x4_t {
-    u32x4_t r;
+        for (int g = 0; g < 4; ++g) {
+          uint2 w;
+          if constexpr (GLU) {     // h = silu(gate) * up in fp32, one rounding of the result
+            const uint2 sg = gpk[GLU ? i : 0][GLU ? j : 0][g];
+            float u[4];            // (read out of the accumulator registers one by one, see the gate product above)
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float h0 = silu_f32(lo_f32<DT>(g[w])) * lo_f32<DT>(u[w]);
-      const float h1 = silu_f32(hi_f32<DT>(g[w])) * hi_f32<DT>(u[w]);
-      r[w] = pack2<DT>(h0, h1);
-    }
-    return r;
-  };
+            for (int e = 0; e < 4; ++e) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(u[e]) : "a"(acc[i][j][4 * g + e]));
+            w.x = pack2<DT>(u[0] * lo_f32<DT>(sg.x), u[1] * hi_f32<DT>(sg.x));
+            w.y = pack2<DT>(u[2] * lo_f32<DT>(sg.y), u[3] * hi_f32<DT>(sg.y));
+          } else {
+            w = pk[GLU ? 0 : i][GLU ? 0 : j][g];
+          }
+          *reinterpret_cast<uint2 *>(E + (32 * j + wrow) * PITCH + (((4 * i + g) ^ wswz) * 16) + whalf) = w;
+          // (one pair at a time, in source order: scheduled freely, all 256 sums are read out of the
+          // accumulator registers first, which does not fit beside the gate values)
+          if constexpr (GLU) __builtin_amdgcn_sched_barrier(0);
+        }
+  }
+  if (ROPE && NBATCH > 1) load_tab(1);
   // LDS reads of the next batch are issued before the stores of this one (different units)
   u32x4_t d[2][BQ];
   auto read_batch = [&](int bt, u32x4_t (&dd)[BQ]) {
@@ -542,7 +579,6 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
     for (int qq = 0; qq < BQ; ++qq) {
       const int q = bt * BQ + qq;
       if (((q * RPI) >> 3) & 1) dd[qq] = u32x4_t{dd[qq][2], dd[qq][3], dd[qq][0], dd[qq][1]};
-      if (GLU) dd[qq] = glu(gate[bt % GR][GLU ? qq : 0], dd[qq]);
       if constexpr (ROPE) {
         // This lane's chunk c holds features 8 (c % 8) .. + 7 of the first (c < 8) or the second half
         // of a head, the lane 8 further round its row of 16 lanes holds the other element of each pair
@@ -570,7 +606,6 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
   read_batch(0, d[0]);
 #pragma unroll
   for (int bt = 0; bt < NBATCH; ++bt) {
-    if (GLU && bt + 2 < NBATCH) load_gate(bt + 2);
     if (ROPE && bt + 2 < NBATCH) load_tab(bt + 2);
     if (bt + 1 < NBATCH) read_batch(bt + 1, d[(bt + 1) & 1]);
     store_batch(bt, d[bt & 1]);
@@ -586,7 +621,6 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
       for (int e = 0; e < 8; ++e) {
         if (col + e >= width) break;
         unsigned v = (d[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
-        if (GLU) v = cvt_out<DT>(silu_f32(cvt_in<DT>(o[e])) * cvt_in<DT>((uint16_t)v));
         o[e] = (uint16_t)v;
       }
     }
