@@ -53,6 +53,14 @@ int deinfer_set_prefill_token_tile(int tokens);
 int deinfer_set_prefill_feature_tile(int features);
 
 /*
+ * The second stage of a GLU call of 17 to 128 tokens for the calls of THIS THREAD: 0 (the default)
+ * lets every call choose between the launch that multiplies both products in one workgroup (no
+ * partial sums; taken where its workgroups fill most of one round of the compute units) and the
+ * split with partial sums and a combining launch; 1 forces the former, -1 the latter.
+ */
+int deinfer_set_decode_glu_one_launch(int mode);
+
+/*
  * What this device delivers on the two rooflines of the path (Sec. 5.2 "Throughput Analysis"
  * reports throughput only; the denominators are this build's), for a benchmark that prints a
  * measured ceiling beside the published one.  Both enqueue one kernel on `stream`, allocate

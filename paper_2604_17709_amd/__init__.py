@@ -53,7 +53,7 @@ class DeinferError(RuntimeError):
 
 EXPORTS = [
     "deinfer_last_error", "deinfer_version", "deinfer_set_profile_events",
-    "deinfer_set_prefill_token_tile", "deinfer_set_prefill_feature_tile",
+    "deinfer_set_prefill_token_tile", "deinfer_set_prefill_feature_tile", "deinfer_set_decode_glu_one_launch",
     "deinfer_rank_for_ratio", "deinfer_probe_stream_read", "deinfer_probe_mfma_bf16",
     "deinfer_packed_bytes", "deinfer_pack_factors",
     "deinfer_workspace_bytes", "deinfer_workspace_init", "deinfer_workspace_check",
@@ -83,6 +83,7 @@ def lib() -> ctypes.CDLL:
         L.deinfer_version.restype = ctypes.c_int
         L.deinfer_set_prefill_token_tile.argtypes = [ctypes.c_int]
         L.deinfer_set_prefill_feature_tile.argtypes = [ctypes.c_int]
+        L.deinfer_set_decode_glu_one_launch.argtypes = [ctypes.c_int]
         L.deinfer_set_profile_events.argtypes = [ctypes.c_int, _vp, _vp]
         L.deinfer_rank_for_ratio.argtypes = [_i64, _i64, ctypes.c_double, ctypes.POINTER(_i64)]
         L.deinfer_probe_stream_read.argtypes = [_vp, _sz, _vp, _sz, _vp]
@@ -375,6 +376,11 @@ PROBE_SINK_BYTES = 1 << 20
 def deinfer_set_prefill_token_tile(tokens: int) -> None:
     """Test and measurement aid: 0 = chosen per launch, 128 or 256 = forced token tile of the T > 128 kernel."""
     _check(lib().deinfer_set_prefill_token_tile(int(tokens)))
+
+
+def deinfer_set_decode_glu_one_launch(mode: int) -> None:
+    """Test and measurement aid: 0 = chosen per call, 1 = the one-launch GLU second stage forced, -1 = never."""
+    _check(lib().deinfer_set_decode_glu_one_launch(int(mode)))
 
 
 def deinfer_set_prefill_feature_tile(features: int) -> None:

@@ -17,6 +17,7 @@
 #include "pack_kernels.h"
 #include "prefill_kernel.h"
 #include "skinny_kernel.h"
+#include "skinny_glu_kernel.h"
 #include "stream_kernel.h"
 #include "probe_kernels.h"
 #include "paged_kernels.h"
@@ -29,6 +30,7 @@ thread_local char g_err[512] = "no error";
 // Test and measurement aids (include/deinfer_testing.h): state of the calling thread only
 thread_local int g_token_tile = 0;       // 0: chosen per launch; 128 or 256: forced; DEINFER_TOKEN_TILE_BOTH: two shapes in one launch
 thread_local int g_feature_tile = 0;     // 0: chosen per launch; 128 or 256: forced where the token tile is 128
+thread_local int g_glu_width = 0;        // deinfer_set_decode_glu_one_launch: 0 chosen per call; 1 forced; -1 never
 thread_local int g_prof_kernel = 0;      // deinfer_set_profile_events: which internal launch to bracket
 thread_local hipEvent_t g_prof_ev[2] = {nullptr, nullptr};
 
@@ -676,6 +678,12 @@ int deinfer_set_prefill_token_tile(int tokens) {
   if (tokens != 0 && tokens != 128 && tokens != 256 && tokens != DEINFER_TOKEN_TILE_BOTH)
     return fail(DEINFER_ERR_INVALID_ARG, "token tile: 0, 128, 256 or DEINFER_TOKEN_TILE_BOTH (both shapes in one launch), got %d", tokens);
   g_token_tile = tokens;
+  return DEINFER_OK;
+}
+
+int deinfer_set_decode_glu_one_launch(int mode) {
+  if (mode != 0 && mode != 1 && mode != -1) return fail(DEINFER_ERR_INVALID_ARG, "GLU second stage: 0, 1 or -1, got %d", mode);
+  g_glu_width = mode;
   return DEINFER_OK;
 }
 

@@ -473,6 +473,45 @@ def test_stages_as_separate_calls(dn, kind, T):
         assert max_err(to_host(h), to_host(h_fused)) <= 2.0 ** -6
 
 
+# ------------------------------------------------------------------ the one-launch second stage of the GLU call
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("T", [17, 32, 40, 64, 100, 128])
+def test_glu_second_stage_in_one_launch(dn, dtype, T):
+    """Both products of the GLU call in one workgroup (no partial sums), forced for small shapes that
+    would not choose it: ragged widths (not a multiple of 32, of 8), different ranks for gate and up
+    (neither a multiple of 32), fused and staged entry points, against the oracle; and against the
+    split with partial sums that it replaces."""
+    import torch
+    d_in = 520
+    shapes = {"g": (100, 1234), "u": (75, 1234)}
+    x = si.make(33, 1, (T, d_in), 1.0, dtype)
+    F, host = {}, {}
+    for i, (n, (r, d_out)) in enumerate(shapes.items()):
+        U = si.make(33, 10 + 2 * i, (d_in, r), 1.0 / np.sqrt(d_in), dtype)
+        V = si.make(33, 11 + 2 * i, (r, d_out), 1.0 / np.sqrt(r), dtype)
+        F[n], _k = pair(dn, U, V, packed=True)
+        host[n] = (U.values, V.values)
+    xd = to_dev(x)
+    ws = dn.Workspace(dn.deinfer_workspace_bytes(T, [F["g"], F["u"]]))
+    try:
+        dn.deinfer_set_decode_glu_one_launch(-1)
+        h_split = dn.deinfer_lowrank_gateup_silu(xd, F["g"], F["u"], ws)
+        dn.deinfer_set_decode_glu_one_launch(1)
+        h = torch.full((T, 1240), 9.0, dtype=xd.dtype, device="cuda")       # pitch > width: nothing may be written past d_out
+        dn.deinfer_lowrank_gateup_silu(xd, F["g"], F["u"], ws, out=h[:, :1234])
+        tg, tu = dn.deinfer_lowrank_down_proj(xd, [F["g"], F["u"]], ws)
+        h_staged = dn.deinfer_lowrank_up_glu_silu(tg, tu, F["g"], F["u"], ws)
+        ws.check()
+    finally:
+        dn.deinfer_set_decode_glu_one_launch(0)
+    ref = oracle.lowrank_gateup_silu(x.values, *host["g"], *host["u"])
+    assert max_err(to_host(h[:, :1234]), ref) <= TOL[dtype]
+    assert max_err(to_host(h_staged), ref) <= TOL[dtype]
+    assert float((h[:, 1234:].float() - 9.0).abs().max()) == 0.0
+    assert max_err(to_host(h[:, :1234]), to_host(h_split)) <= 2.0 ** -6
+    assert max_err(to_host(h_staged), oracle.up_glu_silu(to_host(tg), host["g"][1], to_host(tu), host["u"][1])) <= TOL[dtype]
+
+
 # ------------------------------------------------------------------ the two token tiles of the T > 128 kernel
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("T", [129, 700])
