@@ -24,8 +24,25 @@ _i64 = ctypes.c_int64
 _dp = ctypes.POINTER(ctypes.c_double)
 
 
+_SAN_SO = os.path.join(_HERE, "libdeinfer_oracle_san.so")
+
+
+def build_sanitized() -> str:
+    """The same source under AddressSanitizer and UndefinedBehaviorSanitizer (errors abort).  The
+    process that loads it needs gcc's libasan preloaded; set DEINFER_ORACLE_SO to the returned path."""
+    if (not os.path.exists(_SAN_SO)) or os.path.getmtime(_SAN_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O1", "-g", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+               "-o", _SAN_SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SAN_SO
+
+
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (-O2, OpenMP over token rows). Returns the .so path."""
+    """Compile the oracle with gcc (-O2, OpenMP over token rows). Returns the .so path.
+    DEINFER_ORACLE_SO names a build to load instead (the sanitized one, see build_sanitized)."""
+    if os.environ.get("DEINFER_ORACLE_SO"):
+        return os.environ["DEINFER_ORACLE_SO"]
     if force or (not os.path.exists(_SO)) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
                "-ffp-contract=off", "-o", _SO, _SRC, "-lm"]

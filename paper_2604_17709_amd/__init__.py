@@ -13,7 +13,8 @@ import os
 from typing import Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdeinfer.so")
+# DEINFER_LIBRARY_PATH names another build of the library to load (e.g. the host-sanitized one of build.py)
+LIB_PATH = os.environ.get("DEINFER_LIBRARY_PATH") or os.path.join(_HERE, "libdeinfer.so")
 
 OK = 0
 ERR_INVALID_ARG = -1
