@@ -46,6 +46,8 @@ WORKLOADS = {
     "llama7b_keep60_prefill": ("llama7b_keep60", 8192, "mfma"),
     "llama7b_keep40_prefill": ("llama7b_keep40", 8192, "mfma"),
     "llama13b_keep60_mixed": ("llama13b_keep60", 8256, "mfma"),
+    # a chunk of a chunked prefill: between the decode sizes and the large prefill (first stages split over k)
+    "llama7b_keep60_chunked_prefill": ("llama7b_keep60", 512, "mfma"),
     "llama70b_keep40_decode": ("llama70b_keep40", 128, "hbm"),
     "llama70b_keep40_prefill": ("llama70b_keep40", 4096, "mfma"),
     # keys and values of cached tokens rebuilt from the paged low-rank cache (a different step, see kv_rebuild)
@@ -327,14 +329,9 @@ def main():
     kflops = {"down": 2.0 * T * sum(ranks[p] * proj[p][0] for p in ps),
               "up": 2.0 * T * sum(ranks[p] * proj[p][1] for p in ps), "reduce": 0.0}
     if not decode:
-        # the GLU call launches the gate product and then the up product, whose epilogue also reads
-        # the gate values back and writes h: the library's profiling events end up around the second
-        if dom == "gateup" and shape.glu:
-            pl = ps[-1]
-            kflops["up"] = 2.0 * T * ranks[pl] * proj[pl][1]
-            kbytes["up"] = s * ranks[pl] * proj[pl][1] + s * T * ranks[pl] + s * T * proj[pl][1] * 2
-        else:       # the upward projections of all pairs of the call are one launch
-            kbytes["up"] = w_out + s * T * sum(ranks[p] for p in ps) + s * T * sum(outs)
+        # the upward projections of all pairs of the call are one launch (the GLU call: both products
+        # of a tile in one workgroup, h stored once)
+        kbytes["up"] = w_out + s * T * sum(ranks[p] for p in ps) + s * T * sum(outs)
     entry = {"qkv": "qkv", "o": "linear", "gateup": "gateup_silu" if shape.glu else "linear_act",
              "down": "down" if shape.glu else "linear_act"}[dom]
     # HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs of the same command
@@ -354,9 +351,12 @@ def main():
         ach = kflops[kdom] / ksec / 1e12
         roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
-    roofline["kernel"] = ("%s kernel (%s%s-projection launch of deinfer_lowrank_%s)"
-                          % (("decode_kernel" if T <= 16 else "skinny_kernel") if decode else "prefill_kernel",
-                             "last " if (not decode and kdom == "up" and dom == "gateup" and shape.glu) else "", kdom, entry))
+    # (which kernel a launch is: the tile kernels up to 8 tokens, the streaming kernels up to 128 - for the
+    # GLU call's second stage skinny_glu_kernel where its workgroups fill most of the device, else
+    # skinny_kernel / stream_kernel -, prefill_kernel beyond; the rocprofv3 summaries under profiles/ name it)
+    kname = ("decode_kernel" if T <= 8 else "skinny_glu_kernel / skinny_kernel" if (dom == "gateup" and shape.glu and kdom == "up")
+             else "skinny_kernel") if decode else "prefill_kernel"
+    roofline["kernel"] = "%s (%s-projection launch of deinfer_lowrank_%s)" % (kname, kdom, entry)
     roofline["traffic_source"] = traffic_source
     roofline["avg_launch_us"] = round(ksec * 1e6, 2)
     roofline["algorithmic_bytes_per_launch"] = kbytes[kdom]
