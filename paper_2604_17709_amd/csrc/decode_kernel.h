@@ -344,6 +344,13 @@ __global__ __launch_bounds__(DEC_THREADS, 2) void decode_kernel(const DecParams 
   auto step = [&](const Batch &dc) {
     load_frags<NT, PHASE>(dc, wave, lane, lkg * 8, rowoff, F, xlds);
     multiply<DT, NT, PHASE>(dc, wave, F, acc);
+    // Every request of this batch has been consumed by now, so this wait costs nothing; it is here for
+    // the compiler's wait-count pass.  Requests and products sit in separate branches on the same
+    // wave-uniform conditions, which the pass cannot pair up: without a wait that it can see it takes
+    // a request of the previous batch as possibly still in flight when the next batch computes its
+    // addresses, and where the register allocator reuses a fragment register for an address it then
+    // waits for ALL requests before each new one (seen: 20 serialised round trips in the up kernel).
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0), other counters untouched
     if (!dc.end_seg) return;
 
     // ---- segment end: reduce the partial accumulators of the wavefronts through LDS and hand the result on
