@@ -178,11 +178,12 @@ int deinfer_lowrank_linear_static(const void *x, int64_t T, int64_t ldx, const d
  * v_low_rank = x U_v; keys and values are rebuilt as k = k_low_rank V_k when attention needs
  * them):  y[T x d_out] = t[T x r] . V.   t: device, row-major, pitch ldt >= r, same dtype as
  * the pair.  f must describe a whole valid pair, as for every other call, although only f->V,
- * f->r and f->d_out enter the product.  With PACKED pairs t must be 16-byte
- * aligned with ldt % 8 == 0 and ldt >= r rounded up to a multiple of 8, and the columns
- * r .. (r rounded up to 8) - 1 of every row must hold finite values (they meet zero weights).
- * The rows written by deinfer_lowrank_qkv's t_k / t_v outputs into a zero-filled buffer of
- * such a pitch qualify.  Otherwise the contract of deinfer_lowrank_linear.
+ * f->r and f->d_out enter the product.  Only the columns 0 .. r - 1 of every row are read,
+ * whatever lies behind them in the row (the rest of a wider cache line, another tensor, NaN).
+ * With PACKED pairs, rows with r % 8 == 0, a 16-byte aligned t and ldt % 8 == 0 are read in
+ * place; any other rows are first copied, zero padded, into the workspace (one small launch
+ * more; the room is part of deinfer_workspace_bytes).  Otherwise the contract of
+ * deinfer_lowrank_linear.
  */
 int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_factors_t *f,
                        void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
@@ -199,8 +200,8 @@ int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_fact
  *   dtype (bf16 / fp16: one rounding); f, t_out, ldt: host arrays of n_pairs entries.  No upward
  *   projection runs and V is not read.
  * deinfer_lowrank_up_glu_silu: h = silu(t_gate V_gate) * (t_up V_up), the second stage of
- *   deinfer_lowrank_gateup_silu alone; t_gate / t_up as the t of deinfer_lowrank_up (same
- *   alignment and padding rules for PACKED pairs), both pairs share d_out.
+ *   deinfer_lowrank_gateup_silu alone; t_gate / t_up as the t of deinfer_lowrank_up (read in
+ *   place or copied first by the same rule, both together), both pairs share d_out.
  * Otherwise the contract of deinfer_lowrank_linear.
  */
 int deinfer_lowrank_down_proj(const void *x, int64_t T, int64_t ldx,

@@ -291,7 +291,7 @@ def deinfer_lowrank_down_proj(x, pairs, ws: Workspace, t_out=None, stream=None):
     import torch
     T = _rows(x, "x")
     n = len(pairs)
-    if t_out is None:       # pitch rounded up to 8 elements, zero padding: what deinfer_lowrank_up wants for packed pairs
+    if t_out is None:       # pitch rounded up to 8 elements: rows that deinfer_lowrank_up reads in place where r % 8 == 0
         t_out = [torch.zeros((T, max((p.r + 7) // 8 * 8, 8)), dtype=x.dtype, device=x.device)[:, :p.r] for p in pairs]
     fa = (ctypes.POINTER(Factors) * n)(*[ctypes.pointer(p.desc) for p in pairs])
     ta = (_vp * n)(*[_ptr(t) for t in t_out])

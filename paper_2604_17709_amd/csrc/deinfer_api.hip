@@ -326,6 +326,7 @@ struct Group {
   void *t_out[3]; int64_t ldt[3];          // optional rank-space outputs
   bool glu;
   bool up_only;                            // x is the rank-space intermediate t: only the upward projection runs
+  bool rows_padded;                        // up_only: x (x2) already is the zero-padded copy in the workspace
   const void *bias; int act;               // single non-GLU pair only: y = act(product + bias), bias per output feature
   bool down_only;                          // only the downward projections run; every pair hands out its t through t_out
   const void *x2; int64_t ldx2;            // up_only GLU call: rank-space rows of the second (up) pair
@@ -555,10 +556,39 @@ int run_group(Group gq) {
     return fail(DEINFER_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", gq.ws_bytes, need);
   const bool packed = gq.f[0]->layout == DEINFER_LAYOUT_PACKED;
   if (packed && gq.up_only) {
-    if (!aligned(gq.x, 16) || gq.ldx % 8 != 0 || gq.ldx < round_up(gq.f[0]->r, 8) ||
-        (gq.glu && (!aligned(gq.x2, 16) || gq.ldx2 % 8 != 0 || gq.ldx2 < round_up(gq.f[1]->r, 8))))
-      return fail(DEINFER_ERR_MISALIGNED,
-                  "packed pairs need 16-byte aligned rank-space rows with ldt %% 8 == 0 and ldt >= r rounded up to 8");
+    // The packed kernels read the activation operand in 16-byte chunks of 8 columns; the chunk that
+    // holds column r - 1 of a rank that is no multiple of 8 would reach past the caller's valid
+    // columns (the weights there are zero, but 0 x NaN is NaN).  Such rows, and rows that are not
+    // 16-byte aligned with a pitch of whole chunks, are first copied into the workspace, where a full
+    // call keeps its own rank-space intermediate, with zeros in the padding columns: one small launch
+    // more.  Rows with r % 8 == 0, 16-byte alignment and ldt % 8 == 0 are read in place.
+    bool repack = false;
+    for (int i = 0; i < gq.n && !gq.rows_padded; ++i) {
+      const void *xi = i == 1 ? gq.x2 : gq.x;
+      const int64_t ld = i == 1 ? gq.ldx2 : gq.ldx;
+      if (gq.f[i]->r % 8 != 0 || !aligned(xi, 16) || ld % 8 != 0) repack = true;
+    }
+    if (repack) {
+      int64_t pitch = 0, col[3] = {0, 0, 0};
+      for (int i = 0; i < gq.n; ++i) { col[i] = pitch; pitch += round_up(gq.f[i]->r, 32); }
+      // (T rows of `pitch` columns fit the region of the intermediate of either schedule: it has at
+      // least T rows of the 32-padded ranks; the bound is checked, not assumed)
+      if (WS_HEADER + (size_t)gq.T * (size_t)pitch * 2 > gq.ws_bytes || gq.T * pitch >= (1ll << 30))
+        return fail(DEINFER_ERR_WORKSPACE, "workspace too small for the padded copy of the rank-space rows");
+      uint16_t *t = reinterpret_cast<uint16_t *>(static_cast<char *>(gq.ws) + WS_HEADER);
+      for (int i = 0; i < gq.n; ++i) {
+        const int64_t width = round_up(gq.f[i]->r, 32);
+        if (width == 0) continue;
+        const int64_t cnt = gq.T * width;
+        hipLaunchKernelGGL(pad_rows16_kernel, dim3((unsigned)ceil_div(cnt, (int64_t)256)), dim3(256), 0, gq.stream,
+                           static_cast<const uint16_t *>(i == 1 ? gq.x2 : gq.x), i == 1 ? gq.ldx2 : gq.ldx,
+                           t + col[i], pitch, (int)gq.T, (int)gq.f[i]->r, (int)width);
+        if (int rc = check_launch("padded copy of the rank-space rows")) return rc;
+      }
+      gq.x = t; gq.ldx = pitch;
+      if (gq.n > 1) { gq.x2 = t + col[1]; gq.ldx2 = pitch; }
+      gq.rows_padded = true;
+    }
   } else if (packed) {
     if (!aligned(gq.x, 16) || gq.ldx % 8 != 0 || gq.f[0]->d_in % 8 != 0)
       return fail(DEINFER_ERR_MISALIGNED,

@@ -118,4 +118,15 @@ __global__ void copy2d_kernel(const TS *S, int64_t lds, TD *D, int64_t ldd, int 
   }
 }
 
+// Rows of 16-bit elements copied with zero padding: D[row][c] = c < n_valid ? S[row][c] : 0 for
+// c < N (the caller's rank-space rows brought to the 16-byte row layout the packed kernels read,
+// with exact zeros where the zero-padded weights are met).
+__global__ void pad_rows16_kernel(const uint16_t *S, int64_t lds, uint16_t *D, int64_t ldd, int M, int n_valid, int N) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < (int64_t)M * N) {
+    int64_t r = i / N, c = i % N;
+    D[r * ldd + c] = c < n_valid ? S[r * lds + c] : (uint16_t)0;
+  }
+}
+
 }  // namespace deinfer

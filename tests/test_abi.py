@@ -105,12 +105,12 @@ def test_up_projection_argument_validation():
     assert _up(make(), ws=None) == dn.ERR_WORKSPACE
     # the rank-space operand is narrower than d_in: a pitch between r and d_in is fine
     assert _up(make(d_in=64, r=16), T=0, ldt=16) == dn.OK
-    # packed pairs: 16-byte rows, pitch a multiple of 8 and at least r rounded up to 8
+    # packed pairs: any pitch >= r and any element-aligned pointer is accepted (rows that are not whole
+    # 16-byte chunks are copied, zero padded, into the workspace first); half an element is not
     pk = dict(layout=dn.LAYOUT_PACKED, r=12)
-    assert _up(make(**pk), ldt=12) == dn.ERR_MISALIGNED         # covers r but not whole 16-byte chunks
-    assert _up(make(**pk), ldt=20) == dn.ERR_MISALIGNED
-    assert _up(make(**pk), ldt=16, t=FAKE + 0x200002) == dn.ERR_MISALIGNED
-    assert _up(make(**pk), T=0, ldt=16, t=None, y=None, ws=None, ws_bytes=0) == dn.OK
+    assert _up(make(**pk), ldt=11) == dn.ERR_INVALID_ARG
+    assert _up(make(**pk), ldt=16, t=FAKE + 0x200001) == dn.ERR_MISALIGNED
+    assert _up(make(**pk), T=0, ldt=12, t=None, y=None, ws=None, ws_bytes=0) == dn.OK
 
 
 def test_up_rope_argument_validation():

@@ -6,6 +6,7 @@ import pytest
 
 import oracle
 import synth_inputs as si
+from oracle import paged_cache as pc
 from gpu_util import TOKEN_TILE_BOTH, TOL, max_err, pair, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
@@ -337,6 +338,44 @@ def test_up_projection_alone(dn, packed, T):
     y = dn.deinfer_lowrank_up(t_dev[:, :r], p, ws)
     ref = oracle.up_projection(tt.values, V.values)
     assert max_err(to_host(y), ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("kind", ["plain", "rope", "glu"])
+@pytest.mark.parametrize("T", [3, 40, 128, 300])
+def test_up_projection_reads_only_the_rank_columns(dn, T, kind):
+    """Packed pairs, rank-space rows that sit inside a wider buffer full of NaN, at an odd pitch and
+    an address that is only element aligned: nothing but columns 0 .. r - 1 enters the product."""
+    import torch
+    r, d_in, d_out = 204 + 6, 136, 512                 # r % 8 == 2
+    _, U, V = gen(47, 4, d_in, r, d_out, "bf16")
+    _, U2, V2 = gen(48, 4, d_in, r - 3, d_out, "bf16")
+    tt = si.make(47, 9, (T, r), 1.0, "bf16")
+    tu = si.make(48, 9, (T, r - 3), 1.0, "bf16")
+    p, keep = pair(dn, U, V, packed=True)
+    p2, keep2 = pair(dn, U2, V2, packed=True)
+    ws = ws_for(dn, T, [p, p2])
+    def embedded(rows, width):
+        buf = torch.full((T, width + 7), float("nan"), dtype=torch.bfloat16, device="cuda")
+        buf[:, 3:3 + width] = to_dev(rows)
+        return buf[:, 3:3 + width]
+    t_dev, u_dev = embedded(tt, r), embedded(tu, r - 3)
+    assert t_dev.data_ptr() % 16 != 0 and t_dev.stride(0) % 8 != 0
+    if kind == "plain":
+        y = dn.deinfer_lowrank_up(t_dev, p, ws)
+        ref = oracle.up_projection(tt.values, V.values)
+    elif kind == "rope":
+        pos = torch.arange(T, dtype=torch.int32, device="cuda") * 3 + 1
+        tab = dn.deinfer_rope_table(pos, 128)
+        y = torch.empty((T, d_out), dtype=torch.bfloat16, device="cuda")
+        dn.deinfer_lowrank_up_rope(t_dev, p, tab, ws, out=y)
+        ref = pc.rope(oracle.up_projection(tt.values, V.values), pos.cpu().numpy(), d_out // 128, 128)
+    else:
+        y = dn.deinfer_lowrank_up_glu_silu(t_dev, u_dev, p, p2, ws)
+        ref = oracle.up_glu_silu(tt.values, V.values, tu.values, V2.values)
+    ws.check()
+    got = to_host(y)
+    assert np.isfinite(got).all()
+    assert max_err(got, ref) <= TOL["bf16"]
 
 
 @pytest.mark.parametrize("T", [8, 64, 300])
