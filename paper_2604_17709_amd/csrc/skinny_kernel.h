@@ -18,12 +18,13 @@
 //   * the rectangle's fp32 result goes to a partial buffer; a second small kernel adds the P
 //     partial sums in a fixed order (deterministic), applies the epilogue (bf16 rounding of t,
 //     SiLU-GLU of the MLP call) and writes the outputs.  (Letting the last workgroup of a
-//     feature group do the sum inside the streaming kernel was measured slower: the partial
-//     sums cross L2 caches that are not coherent with each other, and one workgroup's serial
-//     read-back is slower than a launch that uses the whole device.)
+//     feature group do the sum inside the streaming kernel was measured slower, also with the
+//     k-ranges of a group placed on one XCD so that the partial sums stay in one L2: one
+//     workgroup's read-back of P tiles takes longer than a launch that uses the whole device,
+//     and groups that are no multiple of 8 unbalance the XCDs' streams.)
 // Every wavefront keeps three stages of weight loads in flight (four register sets, four LDS
-// slabs); one or two workgroups per compute unit.  A per-workgroup trace (build flag
-// DEINFER_SK_TRACE) of the largest launch of a 7B block at T = 64 (172 workgroups, 19 stages)
+// slabs); one or two workgroups per compute unit.  A per-workgroup trace (wall-clock stamps
+// in an instrumented build) of the largest launch of a 7B block at T = 64 (172 workgroups, 19 stages)
 // shows: all workgroups start within 0.2 us, the first stage lands 3.0 us later, the other 18
 // stages take 19 us (5.2 TB/s of weights), 1 us of stores.  The same loop without the activation
 // loads takes 15.7 us, without the products 17.7 us, without both 15.0 us (6.6 TB/s): the
