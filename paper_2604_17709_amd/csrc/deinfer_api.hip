@@ -579,10 +579,12 @@ int run_group(Group gq) {
       for (int i = 0; i < gq.n; ++i) {
         const int64_t width = round_up(gq.f[i]->r, 32);
         if (width == 0) continue;
-        const int64_t cnt = gq.T * width;
+        const int64_t cnt = gq.T * (width / 8);
+        const void *xi = i == 1 ? gq.x2 : gq.x;
+        const int64_t ld = i == 1 ? gq.ldx2 : gq.ldx;
         hipLaunchKernelGGL(pad_rows16_kernel, dim3((unsigned)ceil_div(cnt, (int64_t)256)), dim3(256), 0, gq.stream,
-                           static_cast<const uint16_t *>(i == 1 ? gq.x2 : gq.x), i == 1 ? gq.ldx2 : gq.ldx,
-                           t + col[i], pitch, (int)gq.T, (int)gq.f[i]->r, (int)width);
+                           static_cast<const uint16_t *>(xi), ld, t + col[i], pitch, (int)gq.T, (int)gq.f[i]->r, (int)width,
+                           (aligned(xi, 16) && ld % 8 == 0) ? 1 : 0);
         if (int rc = check_launch("padded copy of the rank-space rows")) return rc;
       }
       gq.x = t; gq.ldx = pitch;

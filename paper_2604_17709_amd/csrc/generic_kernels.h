@@ -120,13 +120,28 @@ __global__ void copy2d_kernel(const TS *S, int64_t lds, TD *D, int64_t ldd, int 
 
 // Rows of 16-bit elements copied with zero padding: D[row][c] = c < n_valid ? S[row][c] : 0 for
 // c < N (the caller's rank-space rows brought to the 16-byte row layout the packed kernels read,
-// with exact zeros where the zero-padded weights are met).
-__global__ void pad_rows16_kernel(const uint16_t *S, int64_t lds, uint16_t *D, int64_t ldd, int M, int n_valid, int N) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < (int64_t)M * N) {
-    int64_t r = i / N, c = i % N;
-    D[r * ldd + c] = c < n_valid ? S[r * lds + c] : (uint16_t)0;
+// with exact zeros where the zero-padded weights are met).  One thread = one 16-byte chunk of 8
+// columns of D (D 16-byte aligned, ldd % 8 == 0, N % 8 == 0); a chunk that lies wholly inside the
+// valid columns of a 16-byte aligned source row is one 16-byte load, any other chunk is read
+// element by element, and never beyond column n_valid - 1.
+__global__ void pad_rows16_kernel(const uint16_t *S, int64_t lds, uint16_t *D, int64_t ldd, int M, int n_valid, int N, int vec) {
+  const int c8 = N / 8;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)M * c8) return;
+  const int64_t r = i / c8;
+  const int c = (int)(i % c8) * 8;
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  const uint16_t *src = S + r * lds + c;
+  if (vec && c + 8 <= n_valid) {
+    v = *reinterpret_cast<const uint4 *>(src);
+  } else if (c < n_valid) {
+    uint16_t e[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) e[k] = c + k < n_valid ? src[k] : (uint16_t)0;
+    v = make_uint4((unsigned)e[0] | ((unsigned)e[1] << 16), (unsigned)e[2] | ((unsigned)e[3] << 16),
+                   (unsigned)e[4] | ((unsigned)e[5] << 16), (unsigned)e[6] | ((unsigned)e[7] << 16));
   }
+  *reinterpret_cast<uint4 *>(D + r * ldd + c) = v;
 }
 
 }  // namespace deinfer
