@@ -7,7 +7,9 @@ tokens: deinfer_lowrank_qkv -> deinfer_lowrank_linear (o) -> deinfer_lowrank_gat
 RoPE and residual adds are not part of the path and are not run).  Inputs are seeded
 synthetic tensors of the named shape, resident in HBM before the timed region.  To keep
 the 256 MB last-level cache from serving the weights, consecutive steps rotate through
-several independent copies of the packed weights (>= 1.5 GB in total).
+several independent copies of the packed weights (>= 1.5 GB in total).  The K steps are
+timed twice, replayed from a captured HIP graph and with every call launched directly, and
+the faster of the two is reported (config.launch names it, config.launch_ms holds both).
 
 Prints ONE JSON line: metric, value (tokens/s of the step), ms_per_step, per-call timings,
 "roofline" (the dominant launch of the call with the most work, timed with HIP events that the library
@@ -74,8 +76,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
     ap.add_argument("--T", type=int, default=0, help="tokens per step (0 = the workload's default)")
-    ap.add_argument("--launch", default="graph", choices=["graph", "direct"],
-                    help="replay the step from a captured HIP graph, or launch each call directly")
+    ap.add_argument("--launch", default="auto", choices=["auto", "graph", "direct"],
+                    help="replay the step from a captured HIP graph, launch each call directly, or (auto) time the "
+                         "K steps both ways and report the faster one (both times are kept in config.launch_ms)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time the other decode batch sizes")
     ap.add_argument("--seed", type=int, default=1)
@@ -219,7 +222,7 @@ def main():
     calls = [make_calls(c, sh) for c in copies]
 
     graphs = None
-    launch_mode = args.launch
+    launch_mode = "graph" if args.launch == "auto" else args.launch
     with torch.cuda.stream(stream):
         run_calls(calls[0])
     stream.synchronize()
@@ -258,6 +261,19 @@ def main():
             step(i)
     stream.synchronize()
     sec_per_step = timed(step, args.steps)
+    launch_ms = {launch_mode: round(sec_per_step * 1e3, 5)}
+    if args.launch == "auto" and graphs is not None:
+        # the same K steps with every call launched directly (on this ROCm a replayed graph node costs a
+        # little more than a launch the host has queued ahead); the faster way is the one reported
+        direct = lambda i: run_calls(calls[i % n_copies])
+        with torch.cuda.stream(stream):
+            for i in range(args.warmup):
+                direct(i)
+        stream.synchronize()
+        sec_direct = timed(direct, args.steps)
+        launch_ms["direct"] = round(sec_direct * 1e3, 5)
+        if sec_direct < sec_per_step:
+            sec_per_step, launch_mode, step = sec_direct, "direct", direct
     ws.check(stream)
 
     # ---------------------------------------------------------------- per-call timing (HIP events on the launch stream)
@@ -311,7 +327,11 @@ def main():
         tot, cnt = 0.0, 0
         with torch.cuda.stream(stream):
             for i in range(n + 3):
+                # twice in a row on different weight copies: the events keep the brackets of the second
+                # call, whose launches were queued while the first ran (a launch that finds the device
+                # idle after a synchronisation takes 10 - 15 us longer between its events)
                 run_calls(calls[i % n_copies], (dom,))
+                run_calls(calls[(i + 1) % n_copies], (dom,))
                 stream.synchronize()
                 if i >= 3:
                     tot += e0.elapsed_time(e1); cnt += 1
@@ -320,8 +340,6 @@ def main():
 
     n_k = max(10, min(args.steps, 50))
     ktimes = {k: time_kernel(v, n_k) for k, v in kinds.items()}
-    kdom = max(ktimes, key=lambda k: ktimes[k])
-    ksec = ktimes[kdom]
     w_in = s * sum(ranks[p] * proj[p][0] for p in ps)       # U factors of the call
     w_out = s * sum(ranks[p] * proj[p][1] for p in ps)      # V factors of the call
     kbytes = {"down": w_in + s * T * proj[ps[0]][0], "up": w_out + s * T * sum(outs),
@@ -332,6 +350,10 @@ def main():
         # the upward projections of all pairs of the call are one launch (the GLU call: both products
         # of a tile in one workgroup, h stored once)
         kbytes["up"] = w_out + s * T * sum(ranks[p] for p in ps) + s * T * sum(outs)
+    # the dominant launch: the one with the most algorithmic work of the bounding kind (the slower of equals)
+    kwork = kbytes if bound == "hbm" else kflops
+    kdom = max(ktimes, key=lambda k: (kwork[k], ktimes[k]))
+    ksec = ktimes[kdom]
     entry = {"qkv": "qkv", "o": "linear", "gateup": "gateup_silu" if shape.glu else "linear_act",
              "down": "down" if shape.glu else "linear_act"}[dom]
     # HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs of the same command
@@ -354,8 +376,10 @@ def main():
     # (which kernel a launch is: the tile kernels up to 8 tokens, the streaming kernels up to 128 - for the
     # GLU call's second stage skinny_glu_kernel where its workgroups fill most of the device, else
     # skinny_kernel / stream_kernel -, prefill_kernel beyond; the rocprofv3 summaries under profiles/ name it)
-    kname = ("decode_kernel" if T <= 8 else "skinny_glu_kernel / skinny_kernel" if (dom == "gateup" and shape.glu and kdom == "up")
-             else "skinny_kernel") if decode else "prefill_kernel"
+    tiles16 = lambda n: (n + 15) // 16
+    small = (T <= 8 and sum(tiles16(ranks[p]) for p in ps) <= 256 and sum(tiles16(proj[p][1]) for p in ps) <= 1024)
+    kname = ("decode_kernel" if small else "skinny_glu_kernel / skinny_kernel" if (dom == "gateup" and shape.glu and kdom == "up" and T > 16)
+             else "skinny_kernel / stream_kernel") if decode else "prefill_kernel"
     roofline["kernel"] = "%s (%s-projection launch of deinfer_lowrank_%s)" % (kname, kdom, entry)
     roofline["traffic_source"] = traffic_source
     roofline["avg_launch_us"] = round(ksec * 1e6, 2)
@@ -435,7 +459,7 @@ def main():
         "config": {"workload": "%s T=%d (%s of one block)" % (args.workload, T, "qkv+o+gateup_silu+down" if shape.glu else
                                                               "qkv+o+linear_act(bias, ReLU)+linear_act(bias)"),
                    "ranks": ranks, "weight_MB": round(weight_bytes / 1e6, 1), "weight_copies": n_copies,
-                   "launch": launch_mode},
+                   "launch": launch_mode, "launch_ms": launch_ms},
         "step_GBs": round(step_bytes / sec_per_step / 1e9, 1),
         "step_TFLOPs": round(step_flops / sec_per_step / 1e12, 2),
         "step_frac_of_roofline": round((step_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS) if bound == "hbm"
@@ -456,8 +480,24 @@ def main():
             with torch.cuda.stream(stream):
                 for i in range(10):
                     run_calls(sub[i % n_copies])
-            sec = timed(lambda i: run_calls(sub[i % n_copies]), args.steps)
-            sweep["T=%d" % Ts] = {"tokens_per_s": round(Ts / sec, 1), "us_per_step": round(sec * 1e6, 2), "launch": "direct"}
+            stream.synchronize()
+            sub_step, mode = (lambda i: run_calls(sub[i % n_copies])), "direct"
+            if launch_mode == "graph":       # as the main measurement: the step replayed from a graph per weight copy, if that won there
+                try:
+                    sub_graphs = []
+                    for i in range(n_copies):
+                        g = torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(g, stream=stream):
+                            run_calls(sub[i])
+                        sub_graphs.append(g)
+                    sub_step, mode = (lambda i: sub_graphs[i % n_copies].replay()), "graph"
+                except Exception as e:  # noqa: BLE001 - report and keep the direct launches
+                    print("graph capture failed in the sweep (%s); using direct launches" % e, file=sys.stderr)
+            with torch.cuda.stream(stream):
+                for i in range(args.warmup):
+                    sub_step(i)
+            sec = timed(sub_step, args.steps)
+            sweep["T=%d" % Ts] = {"tokens_per_s": round(Ts / sec, 1), "us_per_step": round(sec * 1e6, 2), "launch": mode}
         out["sweep"] = sweep
 
     # ---------------------------------------------------------------- second row: the ranks the configuration prints
