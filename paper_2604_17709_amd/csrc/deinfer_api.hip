@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 
 #include "common.h"
@@ -97,16 +98,16 @@ Geometry geometry(const deinfer_factors_t *f) {
 }
 
 int device_cus() {
-  static int cached[64];
+  static std::atomic<int> cached[64];       // (threads may race to fill an entry: they store the same value)
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return -1;
   if (dev < 0 || dev >= 64) return -1;
-  if (cached[dev] == 0) {
-    int n = 0;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
-    cached[dev] = n;
+    cached[dev].store(n, std::memory_order_relaxed);
   }
-  return cached[dev];
+  return n;
 }
 
 // ---- split of a memory-bound call with 16 < T <= 128 tokens
