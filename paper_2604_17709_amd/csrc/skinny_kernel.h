@@ -42,6 +42,21 @@ namespace deinfer {
 #define DEINFER_LDS_PTR
 #endif
 
+// The activation operand is read in 16-byte chunks of 8 columns.  Where the valid columns K of a row are
+// no multiple of 8 (the caller's rank-space rows of an upward projection alone), the chunk that holds
+// column K - 1 also holds columns that are not the kernel's to use (the weights there are zero, but
+// 0 x NaN is NaN): once that chunk has landed in LDS its elements K % 8 .. 7 are set to zero.  Chunks
+// that lie wholly beyond K fetch the row's first chunk instead (any finite values: zero weights).
+__device__ __forceinline__ void lds_zero_chunk_tail(unsigned char *chunk, int n_keep) {      // n_keep = K % 8 in 1 .. 7
+  u32x4_t v = *reinterpret_cast<u32x4_t *>(chunk);
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const int keep = n_keep - 2 * d;
+    v[d] &= keep >= 2 ? 0xffffffffu : keep == 1 ? 0x0000ffffu : 0u;
+  }
+  *reinterpret_cast<u32x4_t *>(chunk) = v;
+}
+
 constexpr int SK_KB = 4;                   // k-blocks per stage at most (k-ranges are multiples of it)
 constexpr int SK_MAX_PARTS = 16;           // k-ranges per product at most
 constexpr int SK_SLABS = 4;                // activation slabs in LDS = weight register sets
@@ -50,7 +65,8 @@ struct SkProblem {           // one product  act[T x K] . W^T,  W packed as [til
   const uint16_t *act;       // row-major bf16
   long long lda;
   const uint4 *frags;
-  int K;                     // valid k (columns of act)
+  int K;                     // valid k (columns of act), at least 8; columns K .. (K rounded up to 8) - 1 of a row
+                             // are readable memory of unknown contents
   int KB;                    // 32-wide k-blocks of the packed weights (zero padded)
   int n_ftiles;              // 16-feature tiles
   int group0;                // first feature group of this product in the launch
@@ -119,7 +135,7 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
   const bool wtile_ok = (int)wtile < Q.n_ftiles;
   constexpr unsigned OOB = 0x7ffffff0u;
   // ---- activations
-  const unsigned xbytes = (unsigned)(((long long)(P.T - 1) * Q.lda + Q.K) * 2);
+  const unsigned xbytes = (unsigned)(((long long)(P.T - 1) * Q.lda + ((Q.K + 7) & ~7)) * 2);
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void *)Q.act, 0, (int)xbytes, 0x00020000);
   constexpr int NI = NB * 32 / RPI;                     // slab load instructions per stage
   constexpr int NX = (NI + NW - 1) / NW;                // ... per wavefront (where NW does not divide NI a wavefront repeats
@@ -135,16 +151,21 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
     xrow[i] = row < P.T ? (unsigned)row * (unsigned)(Q.lda * 2) : OOB;
     xchunk[i] = (unsigned)(((lane & (SPR - 1)) ^ swz(row)) * 16);
   }
-  const unsigned xklim = (unsigned)(Q.K * 2 - 16);
+  const unsigned xkend = (unsigned)(((Q.K + 7) >> 3) * 16);      // bytes of a row up to the end of the chunk that holds column K - 1
+  // the chunk with columns that are not to be used: its stage (of this workgroup's k-range) and its slot there
+  const int krem = Q.K & 7;
+  const int kb_fix = Q.K >> 5;
+  const int st_fix = (krem != 0 && kb_fix >= kb_begin && kb_fix < kb_end) ? (kb_fix - kb_begin) / KBS : -1;
+  const int slot_fix = ((kb_fix - kb_begin) % KBS) * 4 + ((Q.K >> 3) & 3);
 
   auto fetch_x = [&](int st, int buf) {
     const unsigned kbyte0 = (unsigned)(kb_begin + st * KBS) * 64u;
     const unsigned dead = st < n_stages ? 0u : OOB;     // uniform; OR-ed in: no branch around the loads
 #pragma unroll
     for (int i = 0; i < NX; ++i) {
-      // chunks beyond K re-read valid columns (k clamped to K - 8), which meet zero weights
+      // chunks beyond K read the row's first chunk, which meets zero weights
       unsigned kb = kbyte0 + xchunk[i];
-      kb = kb < xklim ? kb : xklim;
+      kb = kb < xkend ? kb : 0u;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[buf][xm[i] * RPI * XROW], 16,
                                                (xrow[i] + kb) | dead, 0, 0, 0);
     }
@@ -187,7 +208,7 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
       const int i = idx - KBS * 2;
       const unsigned dead = fst < n_stages ? 0u : OOB;
       unsigned kb = (unsigned)(kb_begin + fst * KBS) * 64u + xchunk[i];
-      kb = kb < xklim ? kb : xklim;
+      kb = kb < xkend ? kb : 0u;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[fbuf][xm[i] * RPI * XROW], 16,
                                                (xrow[i] + kb) | dead, 0, 0, 0);
     }
@@ -231,6 +252,12 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((SK_SLABS - 2) * (KBS * 2 + NX)) : "memory");
       __builtin_amdgcn_s_barrier();                     // ... everywhere; nobody reads slab (st - 1) % 4 any more
       asm volatile("" ::: "memory");
+      if (st == st_fix) {                               // (uniform) the chunk that holds column K - 1 is in this slab
+        if (tid < NB * 32) lds_zero_chunk_tail(&xs[slab][tid * XROW + ((slot_fix ^ swz(tid)) * 16)], krem);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
       compute(w, slab, wn, st + SK_SLABS - 1, slab == 0 ? SK_SLABS - 1 : slab - 1);
     };
     for (int st = 0; st < n_stages; st += 4) {

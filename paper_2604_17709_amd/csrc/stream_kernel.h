@@ -16,6 +16,7 @@
 // Activation traffic is T / 32 times the weight traffic (2 x at T = 64) and comes from L2.
 #pragma once
 #include "common.h"
+#include "skinny_kernel.h"
 
 namespace deinfer {
 
@@ -32,7 +33,8 @@ struct StProblem {           // one product
   const uint16_t *act;       // row-major bf16 [T x K]
   long long lda;
   const uint4 *frags;
-  int K;                     // valid k (columns of act)
+  int K;                     // valid k (columns of act), at least 8; columns K .. (K rounded up to 8) - 1 of a row
+                             // are readable memory of unknown contents (lds_zero_chunk_tail in skinny_kernel.h)
   int KB;                    // 32-wide k-blocks of the packed weights (zero padded)
   int n_ftiles;              // 16-feature tiles
   int block0;                // first 32-feature block of this product in the launch
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P)
                              ? wtile * (unsigned)Q.KB * 1024u + (unsigned)(((lane & 15) + 16 * (lane >> 5)) * 16) : OOB;
   // ---- activations: 16 rows x 64 bytes per load instruction; lane l holds slot l % 4 of row l / 4
   // and fetches k-chunk slot ^ ((row >> 2) & 3)
-  const unsigned xbytes = (unsigned)(((long long)(P.T - 1) * Q.lda + Q.K) * 2);
+  const unsigned xbytes = (unsigned)(((long long)(P.T - 1) * Q.lda + ((Q.K + 7) & ~7)) * 2);
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void *)Q.act, 0, (int)xbytes, 0x00020000);
   constexpr int NXI = NB * 2;                          // load instructions per k-block
   unsigned xrow[NXI];
@@ -103,8 +105,13 @@ __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P)
     xrow[i] = row < P.T ? (unsigned)row * (unsigned)(Q.lda * 2) : OOB;
   }
   const unsigned xchunk = (unsigned)((((lane & 3) ^ ((lane >> 4) & 3))) * 16);
-  const unsigned xklim = (unsigned)(Q.K * 2 - 16);
+  const unsigned xkend = (unsigned)(((Q.K + 7) >> 3) * 16);      // bytes of a row up to the end of the chunk that holds column K - 1
   unsigned char *const slab0 = lds + wave * (ST_SLOTS * SLAB);      // this wavefront's slabs
+  // the chunk with columns that are not to be used: its slot (of this wavefront's k range), k-block and position there
+  const int krem = Q.K & 7;
+  const int kb_fix = Q.K >> 5;
+  const int s_fix = (krem != 0 && kb_fix >= kb_begin && kb_fix < kb_end) ? (kb_fix - kb_begin) / ST_SKB : -1;
+  const int kbi_fix = (kb_fix - kb_begin) % ST_SKB;
 
   auto fetch = [&](u32x4_t (&w)[ST_SKB * 2], int slot, int buf) {
 #pragma unroll
@@ -114,9 +121,9 @@ __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P)
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
         w[kbi * 2 + ks] = __builtin_amdgcn_raw_buffer_load_b128(wres, live ? wlane : OOB, kb * 1024 + ks * 512, 2);
-      // chunks beyond K re-read valid columns (k clamped to K - 8), which meet zero weights
+      // chunks beyond K read the row's first chunk, which meets zero weights
       unsigned kbyte = (unsigned)kb * 64u + xchunk;
-      kbyte = kbyte < xklim ? kbyte : xklim;
+      kbyte = kbyte < xkend ? kbyte : 0u;
 #pragma unroll
       for (int i = 0; i < NXI; ++i)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS3 void *)(slab0 + buf * SLAB + (kbi * NB * 32 + 16 * i) * 64), 16,
@@ -158,6 +165,11 @@ __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P)
     auto slot = [&](const u32x4_t (&w)[ST_SKB * 2], u32x4_t (&wn)[ST_SKB * 2], int s, int buf) {
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((ST_SLOTS - 2) * LPS) : "memory");   // slot s has arrived
       fetch(wn, s + ST_SLOTS - 1, buf == 0 ? ST_SLOTS - 1 : buf - 1);              // slab (s - 1) % 4 is free: this wavefront read it
+      if (s == s_fix) {                                 // (uniform) this wavefront's own slab: no barrier, LDS accesses of a wavefront stay in order
+        if (lane < NB * 32)
+          lds_zero_chunk_tail(slab0 + buf * SLAB + (kbi_fix * NB * 32 + lane) * 64 + ((((Q.K >> 3) & 3) ^ ((lane >> 2) & 3)) * 16), krem);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      }
       compute(w, buf);
     };
     for (int s = 0; s < n_slots; s += 4) {

@@ -340,26 +340,37 @@ def test_up_projection_alone(dn, packed, T):
     assert max_err(to_host(y), ref) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("layout", ["odd", "aligned"])
 @pytest.mark.parametrize("kind", ["plain", "rope", "glu"])
 @pytest.mark.parametrize("T", [3, 40, 128, 300])
-def test_up_projection_reads_only_the_rank_columns(dn, T, kind):
-    """Packed pairs, rank-space rows that sit inside a wider buffer full of NaN, at an odd pitch and
-    an address that is only element aligned: nothing but columns 0 .. r - 1 enters the product."""
+@pytest.mark.parametrize("r", [210, 77, 5])
+def test_up_projection_reads_only_the_rank_columns(dn, T, kind, layout, r):
+    """Packed pairs, rank-space rows that sit inside a wider buffer full of NaN: nothing but columns
+    0 .. r - 1 enters the product.  "odd": an odd pitch and an address that is only element aligned
+    (the rows are copied first); "aligned": 16-byte aligned rows with a pitch of whole 16-byte
+    chunks (read in place up to 128 tokens, the kernels zero what they read beyond column r - 1)."""
     import torch
-    r, d_in, d_out = 204 + 6, 136, 512                 # r % 8 == 2
+    d_in, d_out = 136, 512
+    r2 = r + 9 if r > 8 else 3                          # the up pair of the GLU call: another rank, another residue
     _, U, V = gen(47, 4, d_in, r, d_out, "bf16")
-    _, U2, V2 = gen(48, 4, d_in, r - 3, d_out, "bf16")
+    _, U2, V2 = gen(48, 4, d_in, r2, d_out, "bf16")
     tt = si.make(47, 9, (T, r), 1.0, "bf16")
-    tu = si.make(48, 9, (T, r - 3), 1.0, "bf16")
+    tu = si.make(48, 9, (T, r2), 1.0, "bf16")
     p, keep = pair(dn, U, V, packed=True)
     p2, keep2 = pair(dn, U2, V2, packed=True)
     ws = ws_for(dn, T, [p, p2])
     def embedded(rows, width):
-        buf = torch.full((T, width + 7), float("nan"), dtype=torch.bfloat16, device="cuda")
-        buf[:, 3:3 + width] = to_dev(rows)
-        return buf[:, 3:3 + width]
-    t_dev, u_dev = embedded(tt, r), embedded(tu, r - 3)
-    assert t_dev.data_ptr() % 16 != 0 and t_dev.stride(0) % 8 != 0
+        if layout == "odd":
+            buf = torch.full((T, width + 7), float("nan"), dtype=torch.bfloat16, device="cuda")
+            view = buf[:, 3:3 + width]
+            assert view.data_ptr() % 16 != 0 and view.stride(0) % 8 != 0
+        else:
+            buf = torch.full((T, (width + 7) // 8 * 8 + 8), float("nan"), dtype=torch.bfloat16, device="cuda")
+            view = buf[:, :width]
+            assert view.data_ptr() % 16 == 0 and view.stride(0) % 8 == 0
+        view.copy_(to_dev(rows))
+        return view
+    t_dev, u_dev = embedded(tt, r), embedded(tu, r2)
     if kind == "plain":
         y = dn.deinfer_lowrank_up(t_dev, p, ws)
         ref = oracle.up_projection(tt.values, V.values)
@@ -376,6 +387,37 @@ def test_up_projection_reads_only_the_rank_columns(dn, T, kind):
     got = to_host(y)
     assert np.isfinite(got).all()
     assert max_err(got, ref) <= TOL["bf16"]
+
+
+def test_up_projection_reads_only_the_rank_columns_wide_layers(dn):
+    """The same with the widths that take the other kernels of the 17 .. 128-token range: a GLU second
+    stage in one launch (forced) and second stages with several k-ranges."""
+    import torch
+    T, r, r2, d_in, d_out = 96, 1638, 1003, 64, 4096
+    _, U, V = gen(51, 4, d_in, r, d_out, "bf16")
+    _, U2, V2 = gen(52, 4, d_in, r2, d_out, "bf16")
+    tt = si.make(51, 9, (T, r), 1.0, "bf16")
+    tu = si.make(52, 9, (T, r2), 1.0, "bf16")
+    p, keep = pair(dn, U, V, packed=True)
+    p2, keep2 = pair(dn, U2, V2, packed=True)
+    ws = ws_for(dn, T, [p, p2])
+    def embedded(rows, width):
+        buf = torch.full((T, (width + 7) // 8 * 8 + 8), float("nan"), dtype=torch.bfloat16, device="cuda")
+        buf[:, :width] = to_dev(rows)
+        return buf[:, :width]
+    t_dev, u_dev = embedded(tt, r), embedded(tu, r2)
+    y = dn.deinfer_lowrank_up(t_dev, p, ws)
+    assert max_err(to_host(y), oracle.up_projection(tt.values, V.values)) <= TOL["bf16"]
+    ref = oracle.up_glu_silu(tt.values, V.values, tu.values, V2.values)
+    for mode in (0, 1, -1):
+        dn.deinfer_set_decode_glu_one_launch(mode)
+        try:
+            h = dn.deinfer_lowrank_up_glu_silu(t_dev, u_dev, p, p2, ws)
+        finally:
+            dn.deinfer_set_decode_glu_one_launch(0)
+        got = to_host(h)
+        assert np.isfinite(got).all() and max_err(got, ref) <= TOL["bf16"]
+    ws.check()
 
 
 @pytest.mark.parametrize("T", [8, 64, 300])
