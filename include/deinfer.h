@@ -180,10 +180,9 @@ int deinfer_lowrank_linear_static(const void *x, int64_t T, int64_t ldx, const d
  * the pair.  f must describe a whole valid pair, as for every other call, although only f->V,
  * f->r and f->d_out enter the product.  Only the columns 0 .. r - 1 of every row are read,
  * whatever lies behind them in the row (the rest of a wider cache line, another tensor, NaN).
- * With PACKED pairs, rows with a 16-byte aligned t and ldt % 8 == 0 are read in place for
- * T <= 128 (r >= 8) and, for more tokens, when r % 8 == 0; any other rows are first copied, zero
- * padded, into the workspace (one small launch more; the room is part of
- * deinfer_workspace_bytes).  Otherwise the contract of
+ * With PACKED pairs, rows with a 16-byte aligned t and ldt % 8 == 0 are read in place
+ * (r >= 8 or r % 8 == 0); any other rows are first copied, zero padded, into the workspace (one
+ * small launch more; the room is part of deinfer_workspace_bytes).  Otherwise the contract of
  * deinfer_lowrank_linear.
  */
 int deinfer_lowrank_up(const void *t, int64_t T, int64_t ldt, const deinfer_factors_t *f,

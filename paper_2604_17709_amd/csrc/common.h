@@ -114,4 +114,19 @@ template <int DT> __device__ __forceinline__ f32x4_t mfma16(const u32x4_t &a, co
 #endif
 }
 
+// The activation operand is read in 16-byte chunks of 8 columns.  Where the valid columns K of a row are
+// no multiple of 8 (the caller's rank-space rows of an upward projection alone), the chunk that holds
+// column K - 1 also holds columns that are not the kernel's to use (the weights there are zero, but
+// 0 x NaN is NaN): once that chunk has landed in LDS its elements K % 8 .. 7 are set to zero.  Chunks
+// that lie wholly beyond K fetch the row's first chunk instead (any finite values: zero weights).
+__device__ __forceinline__ void lds_zero_chunk_tail(unsigned char *chunk, int n_keep) {      // n_keep = K % 8 in 1 .. 7
+  u32x4_t v = *reinterpret_cast<u32x4_t *>(chunk);
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const int keep = n_keep - 2 * d;
+    v[d] &= keep >= 2 ? 0xffffffffu : keep == 1 ? 0x0000ffffu : 0u;
+  }
+  *reinterpret_cast<u32x4_t *>(chunk) = v;
+}
+
 }  // namespace deinfer

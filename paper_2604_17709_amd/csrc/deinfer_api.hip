@@ -559,19 +559,16 @@ int run_group(Group gq) {
   if (packed && gq.up_only) {
     // The packed kernels read the activation operand in 16-byte chunks of 8 columns; the chunk that
     // holds column r - 1 of a rank that is no multiple of 8 reaches past the caller's valid columns
-    // (the weights there are zero, but 0 x NaN is NaN).  The kernels for up to SKINNY_MAX_T tokens set
-    // those elements to zero once the chunk is in LDS (lds_zero_chunk_tail), so 16-byte aligned rows
-    // with a pitch of whole chunks are read in place there (r >= 8).  For more tokens such rows are
-    // read in place when r % 8 == 0.  Any other rows are first copied into the workspace, where a full
+    // (the weights there are zero, but 0 x NaN is NaN).  The kernels set those elements to zero once
+    // the chunk is in LDS (lds_zero_chunk_tail), so 16-byte aligned rows with a pitch of whole chunks
+    // are read in place (r >= 8).  Any other rows are first copied into the workspace, where a full
     // call keeps its own rank-space intermediate, with zeros in the padding columns: one small launch more.
-    const bool in_kernel_fix = gq.T <= SKINNY_MAX_T;
     bool repack = false;
     for (int i = 0; i < gq.n && !gq.rows_padded; ++i) {
       const void *xi = i == 1 ? gq.x2 : gq.x;
       const int64_t ld = i == 1 ? gq.ldx2 : gq.ldx;
       const int64_t r = gq.f[i]->r;
-      if (!aligned(xi, 16) || ld % 8 != 0) repack = true;
-      else if (r % 8 != 0 && (!in_kernel_fix || r < 8)) repack = true;
+      if (!aligned(xi, 16) || ld % 8 != 0 || (r % 8 != 0 && r < 8)) repack = true;
     }
     if (repack) {
       int64_t pitch = 0, col[3] = {0, 0, 0};

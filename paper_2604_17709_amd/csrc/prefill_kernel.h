@@ -116,7 +116,9 @@ struct PfShared {
 
 // GLU = true: two products per tile, P.prob[0] (gate) and P.prob[1] (up, same feature tiles and output):
 // out = silu(gate product) * up product.
-// POST = true: bias and activation of the non-GLU MLP sub-layer on the fp32 accumulators.
+// POST = PF_POST_BIAS_ACT: bias and activation of the non-GLU MLP sub-layer on the fp32 accumulators;
+// PF_POST_TAIL: the activation rows' valid columns K may be no multiple of 8 (the caller's rank-space rows
+// of an upward projection alone): what the last chunk holds beyond column K - 1 is set to zero in LDS.
 // SPLIT = true: this workgroup multiplies only its part of the k range and stores the fp32
 // accumulators to a partial buffer (the sum and the epilogue are a second, small kernel's).
 // DT = storage type of weights, activations and outputs (DT_BF16 or DT_F16).
@@ -129,9 +131,13 @@ struct PfShared {
 // The body of a workgroup: bid = its index among the workgroups of this tile shape, n_tblocks = token
 // blocks of this tile shape, fb_shift = first feature block of this tile shape (0 unless the launch
 // mixes two shapes, see prefill_mixed_kernel).
-template <int DT, int MF, bool GLU, bool POST, bool SPLIT, bool ROPE, int TB>
+constexpr int PF_POST_NONE = 0, PF_POST_BIAS_ACT = 1, PF_POST_TAIL = 2;
+
+template <int DT, int MF, bool GLU, int POSTK, bool SPLIT, bool ROPE, int TB>
 __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, const int n_tblocks, const int fb_shift) {
+  constexpr bool POST = POSTK == PF_POST_BIAS_ACT, TAIL = POSTK == PF_POST_TAIL;
   static_assert(!(ROPE && (GLU || POST || SPLIT)), "the rotary epilogue goes with a plain product");
+  static_assert(!(TAIL && SPLIT), "only a second stage reads caller rows");
   static_assert(TB == 4 || (TB == 2 && !SPLIT), "token blocks per wavefront");
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   constexpr int WTOK = 32 * TB;                    // tokens per wavefront
@@ -208,8 +214,22 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
     const int n_stages = SPLIT ? (Q.KB - kb0 < P.kb_per_part ? Q.KB - kb0 : P.kb_per_part) : Q.KB;
 
     // one load instruction (index 0 .. LPS - 1) of stage st: weight tiles first, then activation rows.
-    // Activation chunks beyond K re-read valid columns (k clamped to K - 8), which meet zero weights.
-    const unsigned xchunk = (unsigned)(chunk * 16), xklim = (unsigned)(Q.K * 2 - 16);
+    // Activation chunks beyond K read the row's first chunk, which meets zero weights.
+    const unsigned xchunk = (unsigned)(chunk * 16);
+    const unsigned xkend = (unsigned)(((Q.K + 7) >> 3) * 16);    // bytes of a row up to the end of the chunk that holds column K - 1
+    // Valid columns K that are no multiple of 8 (the caller's rank-space rows of an upward projection alone):
+    // the stage whose tile holds the chunk with column K - 1; once it has landed, the elements of that chunk
+    // beyond K - 1 are set to zero (lds_zero_chunk_tail in common.h).  -1: nothing to do (every other call).
+    const int krem = Q.K & 7;
+    const int st_fix = (TAIL && krem != 0) ? (Q.K >> 5) - kb0 : -1;
+    auto fix_tail = [&](int buf) {
+      int row = threadIdx.x;
+      asm volatile("" : "+v"(row));
+      if (row < 64 * TB) lds_zero_chunk_tail(&S.x[buf][row * PF_XPITCH + ((((Q.K >> 3) & 3) ^ ((row >> 2) & 3)) * 16)], krem);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    };
     auto fetch_part = [&](int st, int idx) {
       const int buf = st % NST;
       if (idx < WT) {
@@ -218,7 +238,7 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
       } else {
         const int i = idx - WT;
         unsigned kb = (unsigned)(st + kb0) * (PF_BK * 2) + xchunk;
-        kb = kb < xklim ? kb : xklim;
+        kb = kb < xkend ? kb : 0u;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LOCAL void *)&S.x[buf][16 * (4 * i + uwave) * PF_XPITCH], 16,
                                                  xrow[i] + kb, 0, 0, 0);
       }
@@ -283,6 +303,9 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();          // stage 0 has landed everywhere
     asm volatile("" ::: "memory");
+    if constexpr (TAIL) {
+      if (st_fix == 0) fix_tail(0);
+    }
     // Operand reads run two groups of products ahead of their use (a group = the MB products that
     // share one token operand, about 130 cycles): with the four wavefronts reading in step and the
     // incoming tiles being written, one group of cover left the products waiting for LDS.
@@ -326,6 +349,11 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
+      // (the chunk that holds column K - 1 is in the last stage: only the stages that run without further
+      // requests can precede it, so the steady-state loop carries no branch for this)
+      if constexpr (TAIL && !F2 && !F3) {
+        if (st + 1 == st_fix) fix_tail(nbuf);           // (uniform)
+      }
       // ---- k-step 1; the operands of the next stage's k-step 0 are read along the way
       // (after the last stage these read a stage buffer nobody writes any more; the values are unused)
 #pragma unroll
@@ -379,6 +407,9 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();          // ... everywhere, and nobody reads the buffer of stage st - 1 any more
       asm volatile("" ::: "memory");
+      if constexpr (TAIL && !STEADY) {
+        if (st + 1 == st_fix) fix_tail(nbuf);
+      }
 #pragma unroll
       for (int j = 0; j < TB; ++j) {
 #pragma unroll
@@ -630,7 +661,7 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
 #endif
 }
 
-template <int DT, int MF, bool GLU, bool POST = false, bool SPLIT = false, bool ROPE = false, int TB = 4>
+template <int DT, int MF, bool GLU, int POST = PF_POST_NONE, bool SPLIT = false, bool ROPE = false, int TB = 4>
 __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
   prefill_body<DT, MF, GLU, POST, SPLIT, ROPE, TB>(P, (int)blockIdx.x, P.n_tblocks, 0);
 }
@@ -640,7 +671,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_kernel(const PfParams P) {
 // launches whose last round of 256 x 256 tiles would leave more than half of the compute units
 // idle: that round's feature blocks run as twice as many smaller tiles, which take about 0.64 of a
 // large tile's time each.
-template <int DT, bool GLU, bool POST, bool ROPE>
+template <int DT, bool GLU, int POST, bool ROPE>
 __global__ __launch_bounds__(PF_THREADS) void prefill_mixed_kernel(const PfParams P) {
   if ((int)blockIdx.x < P.n_big) prefill_body<DT, 8, GLU, POST, false, ROPE, 4>(P, (int)blockIdx.x, P.n_tblocks, 0);
   else prefill_body<DT, 8, GLU, POST, false, ROPE, 2>(P, (int)blockIdx.x - P.n_big, P.n_tblocks2, P.fb_shift2);

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(128 * NW, 1) void skinny_glu_kernel(const SkGluPara
   const unsigned xbytes = (unsigned)(((long long)(P.T - 1) * Q.lda + ((Q.K + 7) & ~7)) * 2);
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void *)Q.act, 0, (int)xbytes, 0x00020000);
   const unsigned xkend = (unsigned)(((Q.K + 7) >> 3) * 16);      // bytes of a row up to the end of the chunk that holds column K - 1
-  // the chunk with columns that are not to be used (lds_zero_chunk_tail in skinny_kernel.h): its stage and slot,
+  // the chunk with columns that are not to be used (lds_zero_chunk_tail in common.h): its stage and slot,
   // per product; the barrier that follows the fix is taken by every wavefront when either product has one there
   const int krem = Q.K & 7;
   const int st_fix = krem != 0 ? (Q.K >> 5) / KBS : -1;

@@ -34,7 +34,7 @@ struct StProblem {           // one product
   long long lda;
   const uint4 *frags;
   int K;                     // valid k (columns of act), at least 8; columns K .. (K rounded up to 8) - 1 of a row
-                             // are readable memory of unknown contents (lds_zero_chunk_tail in skinny_kernel.h)
+                             // are readable memory of unknown contents (lds_zero_chunk_tail in common.h)
   int KB;                    // 32-wide k-blocks of the packed weights (zero padded)
   int n_ftiles;              // 16-feature tiles
   int block0;                // first 32-feature block of this product in the launch
