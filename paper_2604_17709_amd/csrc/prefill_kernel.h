@@ -214,9 +214,11 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
     const int n_stages = SPLIT ? (Q.KB - kb0 < P.kb_per_part ? Q.KB - kb0 : P.kb_per_part) : Q.KB;
 
     // one load instruction (index 0 .. LPS - 1) of stage st: weight tiles first, then activation rows.
-    // Activation chunks beyond K read the row's first chunk, which meets zero weights.
+    // Activation chunks beyond K re-read a chunk of valid columns (the last one; PF_POST_TAIL: the first one),
+    // which meets zero weights.
     const unsigned xchunk = (unsigned)(chunk * 16);
     const unsigned xkend = (unsigned)(((Q.K + 7) >> 3) * 16);    // bytes of a row up to the end of the chunk that holds column K - 1
+    const unsigned xklim = (unsigned)(Q.K * 2 - 16);             // (K a multiple of 8: the last chunk)
     // Valid columns K that are no multiple of 8 (the caller's rank-space rows of an upward projection alone):
     // the stage whose tile holds the chunk with column K - 1; once it has landed, the elements of that chunk
     // beyond K - 1 are set to zero (lds_zero_chunk_tail in common.h).  -1: nothing to do (every other call).
@@ -238,7 +240,7 @@ __device__ __forceinline__ void prefill_body(const PfParams &P, const int bid, c
       } else {
         const int i = idx - WT;
         unsigned kb = (unsigned)(st + kb0) * (PF_BK * 2) + xchunk;
-        kb = kb < xkend ? kb : 0u;
+        kb = TAIL ? (kb < xkend ? kb : 0u) : (kb < xklim ? kb : xklim);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LOCAL void *)&S.x[buf][16 * (4 * i + uwave) * PF_XPITCH], 16,
                                                  xrow[i] + kb, 0, 0, 0);
       }

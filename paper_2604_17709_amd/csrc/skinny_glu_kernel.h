@@ -38,7 +38,8 @@ constexpr size_t sk_glu_lds_bytes(int NB) { return (size_t)SG_SLABS * 2 * NB * 3
 // block w of the same output features.  (What a compute unit can take in, weights from HBM and slabs
 // from L2 together, grows with the wavefronts that issue loads: measured 51 GB/s with four and 65 GB/s
 // with eight at equal shares of both, and at 128 tokens the slabs are as many bytes as the weights.)
-template <int DT, int NB, int NW>
+// TAIL: as in skinny_kernel.h (rank-space rows whose valid columns are no multiple of 8).
+template <int DT, int NB, int NW, bool TAIL = false>
 __global__ __launch_bounds__(128 * NW, 1) void skinny_glu_kernel(const SkGluParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   constexpr int KBS = SG_KBS, XROW = SG_XROW;
@@ -64,13 +65,14 @@ __global__ __launch_bounds__(128 * NW, 1) void skinny_glu_kernel(const SkGluPara
   const unsigned xbytes = (unsigned)(((long long)(P.T - 1) * Q.lda + ((Q.K + 7) & ~7)) * 2);
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void *)Q.act, 0, (int)xbytes, 0x00020000);
   const unsigned xkend = (unsigned)(((Q.K + 7) >> 3) * 16);      // bytes of a row up to the end of the chunk that holds column K - 1
+  const unsigned xklim = (unsigned)(Q.K * 2 - 16);               // (K a multiple of 8: the last chunk)
   // the chunk with columns that are not to be used (lds_zero_chunk_tail in common.h): its stage and slot,
   // per product; the barrier that follows the fix is taken by every wavefront when either product has one there
   const int krem = Q.K & 7;
-  const int st_fix = krem != 0 ? (Q.K >> 5) / KBS : -1;
+  const int st_fix = (TAIL && krem != 0) ? (Q.K >> 5) / KBS : -1;
   const int slot_fix = ((Q.K >> 5) % KBS) * 4 + ((Q.K >> 3) & 3);
-  const int st_fix_gate = (P.gate.K & 7) != 0 ? (P.gate.K >> 5) / KBS : -1;
-  const int st_fix_up = (P.up.K & 7) != 0 ? (P.up.K >> 5) / KBS : -1;
+  const int st_fix_gate = (TAIL && (P.gate.K & 7) != 0) ? (P.gate.K >> 5) / KBS : -1;
+  const int st_fix_up = (TAIL && (P.up.K & 7) != 0) ? (P.up.K >> 5) / KBS : -1;
   constexpr int NI = NB * 32 / RPI;                     // slab load instructions per stage and product
   constexpr int NX = NI / NW;                           // ... per wavefront of the product
   static_assert(NI % NW == 0, "every wavefront issues the same number of slab loads");
@@ -99,9 +101,9 @@ __global__ __launch_bounds__(128 * NW, 1) void skinny_glu_kernel(const SkGluPara
     } else {
       const int i = idx - NWL;
       const unsigned dead = fst * KBS < KBq ? 0u : OOB;
-      // chunks beyond K read the row's first chunk, which meets zero weights
+      // chunks beyond K re-read a chunk of valid columns (the last one; TAIL: the first one), which meets zero weights
       unsigned kb = (unsigned)(fst * KBS) * 64u + xchunk[i];
-      kb = kb < xkend ? kb : 0u;
+      kb = TAIL ? (kb < xkend ? kb : 0u) : (kb < xklim ? kb : xklim);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)(slabs + fbuf * 2 * SLAB + xm[i] * RPI * XROW), 16,
                                                (xrow[i] + kb) | dead, 0, 0, 0);
     }
@@ -161,13 +163,15 @@ __global__ __launch_bounds__(128 * NW, 1) void skinny_glu_kernel(const SkGluPara
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((SG_SLABS - 2) * NLOAD) : "memory");
       __builtin_amdgcn_s_barrier();                     // stage st has arrived everywhere; nobody reads stage buffer (st - 1) % 4 any more
       asm volatile("" ::: "memory");
-      if (st == st_fix_gate || st == st_fix_up) {       // (uniform over the workgroup)
-        const int row = fw * 64 + lane;                 // the product's wavefronts share out its slab's rows
-        if (st == st_fix && row < NB * 32)
-          lds_zero_chunk_tail(slabs + slab * 2 * SLAB + row * XROW + ((slot_fix ^ swz(row)) * 16), krem);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
+      if constexpr (TAIL) {
+        if (st == st_fix_gate || st == st_fix_up) {     // (uniform over the workgroup)
+          const int row = fw * 64 + lane;               // the product's wavefronts share out its slab's rows
+          if (st == st_fix && row < NB * 32)
+            lds_zero_chunk_tail(slabs + slab * 2 * SLAB + row * XROW + ((slot_fix ^ swz(row)) * 16), krem);
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+        }
       }
       compute(w, slab, wn, st + SG_SLABS - 1, slab == 0 ? SG_SLABS - 1 : slab - 1);
     };

@@ -83,7 +83,11 @@ struct SkParams {
 // NW = wavefronts per workgroup = 32-feature blocks per feature group (4, 3 or 2): narrower groups
 // give more workgroups without more k-ranges (no extra partial sums) at the price of activation
 // traffic, which one slab per group and stage makes proportional to the number of groups.
-template <int DT, int NB, int KBS, int NW>
+// TAIL: the valid columns K of the activation rows may be no multiple of 8 (the caller's rank-space rows of
+// an upward projection alone): what the last chunk holds beyond column K - 1 is cleared in LDS
+// (lds_zero_chunk_tail in common.h).  A variant of its own: as a run-time branch per stage the step cost
+// 2 % of every call's time.
+template <int DT, int NB, int KBS, int NW, bool TAIL = false>
 __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const SkParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   constexpr int XROW = KBS * 64;          // bytes per token row of a stage's activation slab
@@ -137,10 +141,11 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
     xchunk[i] = (unsigned)(((lane & (SPR - 1)) ^ swz(row)) * 16);
   }
   const unsigned xkend = (unsigned)(((Q.K + 7) >> 3) * 16);      // bytes of a row up to the end of the chunk that holds column K - 1
+  const unsigned xklim = (unsigned)(Q.K * 2 - 16);               // (K a multiple of 8: the last chunk)
   // the chunk with columns that are not to be used: its stage (of this workgroup's k-range) and its slot there
   const int krem = Q.K & 7;
   const int kb_fix = Q.K >> 5;
-  const int st_fix = (krem != 0 && kb_fix >= kb_begin && kb_fix < kb_end) ? (kb_fix - kb_begin) / KBS : -1;
+  const int st_fix = (TAIL && krem != 0 && kb_fix >= kb_begin && kb_fix < kb_end) ? (kb_fix - kb_begin) / KBS : -1;
   const int slot_fix = ((kb_fix - kb_begin) % KBS) * 4 + ((Q.K >> 3) & 3);
 
   auto fetch_x = [&](int st, int buf) {
@@ -148,9 +153,9 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
     const unsigned dead = st < n_stages ? 0u : OOB;     // uniform; OR-ed in: no branch around the loads
 #pragma unroll
     for (int i = 0; i < NX; ++i) {
-      // chunks beyond K read the row's first chunk, which meets zero weights
+      // chunks beyond K re-read a chunk of valid columns (the last one; TAIL: the first one), which meets zero weights
       unsigned kb = kbyte0 + xchunk[i];
-      kb = kb < xkend ? kb : 0u;
+      kb = TAIL ? (kb < xkend ? kb : 0u) : (kb < xklim ? kb : xklim);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[buf][xm[i] * RPI * XROW], 16,
                                                (xrow[i] + kb) | dead, 0, 0, 0);
     }
@@ -193,7 +198,7 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
       const int i = idx - KBS * 2;
       const unsigned dead = fst < n_stages ? 0u : OOB;
       unsigned kb = (unsigned)(kb_begin + fst * KBS) * 64u + xchunk[i];
-      kb = kb < xkend ? kb : 0u;
+      kb = TAIL ? (kb < xkend ? kb : 0u) : (kb < xklim ? kb : xklim);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS_PTR void *)&xs[fbuf][xm[i] * RPI * XROW], 16,
                                                (xrow[i] + kb) | dead, 0, 0, 0);
     }
@@ -237,11 +242,13 @@ __global__ __launch_bounds__(64 * NW, NW >= 3 ? 2 : 1) void skinny_kernel(const 
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((SK_SLABS - 2) * (KBS * 2 + NX)) : "memory");
       __builtin_amdgcn_s_barrier();                     // ... everywhere; nobody reads slab (st - 1) % 4 any more
       asm volatile("" ::: "memory");
-      if (st == st_fix) {                               // (uniform) the chunk that holds column K - 1 is in this slab
-        if (tid < NB * 32) lds_zero_chunk_tail(&xs[slab][tid * XROW + ((slot_fix ^ swz(tid)) * 16)], krem);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
+      if constexpr (TAIL) {
+        if (st == st_fix) {                             // (uniform) the chunk that holds column K - 1 is in this slab
+          if (tid < NB * 32) lds_zero_chunk_tail(&xs[slab][tid * XROW + ((slot_fix ^ swz(tid)) * 16)], krem);
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+        }
       }
       compute(w, slab, wn, st + SK_SLABS - 1, slab == 0 ? SK_SLABS - 1 : slab - 1);
     };

@@ -56,7 +56,8 @@ struct StParams {
 };
 
 // NB = 32-token blocks (1 or 2)
-template <int DT, int NB>
+// TAIL: as in skinny_kernel.h (rank-space rows whose valid columns are no multiple of 8)
+template <int DT, int NB, bool TAIL = false>
 __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the body uses device-only builtins; the host pass only needs the stub
   constexpr int ST_SKB = 2 / NB;                                    // k-blocks per slot: 16 KiB of slab per wavefront
@@ -106,11 +107,12 @@ __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P)
   }
   const unsigned xchunk = (unsigned)((((lane & 3) ^ ((lane >> 4) & 3))) * 16);
   const unsigned xkend = (unsigned)(((Q.K + 7) >> 3) * 16);      // bytes of a row up to the end of the chunk that holds column K - 1
+  const unsigned xklim = (unsigned)(Q.K * 2 - 16);               // (K a multiple of 8: the last chunk)
   unsigned char *const slab0 = lds + wave * (ST_SLOTS * SLAB);      // this wavefront's slabs
   // the chunk with columns that are not to be used: its slot (of this wavefront's k range), k-block and position there
   const int krem = Q.K & 7;
   const int kb_fix = Q.K >> 5;
-  const int s_fix = (krem != 0 && kb_fix >= kb_begin && kb_fix < kb_end) ? (kb_fix - kb_begin) / ST_SKB : -1;
+  const int s_fix = (TAIL && krem != 0 && kb_fix >= kb_begin && kb_fix < kb_end) ? (kb_fix - kb_begin) / ST_SKB : -1;
   const int kbi_fix = (kb_fix - kb_begin) % ST_SKB;
 
   auto fetch = [&](u32x4_t (&w)[ST_SKB * 2], int slot, int buf) {
@@ -121,9 +123,9 @@ __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P)
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
         w[kbi * 2 + ks] = __builtin_amdgcn_raw_buffer_load_b128(wres, live ? wlane : OOB, kb * 1024 + ks * 512, 2);
-      // chunks beyond K read the row's first chunk, which meets zero weights
+      // chunks beyond K re-read a chunk of valid columns (the last one; TAIL: the first one), which meets zero weights
       unsigned kbyte = (unsigned)kb * 64u + xchunk;
-      kbyte = kbyte < xkend ? kbyte : 0u;
+      kbyte = TAIL ? (kbyte < xkend ? kbyte : 0u) : (kbyte < xklim ? kbyte : xklim);
 #pragma unroll
       for (int i = 0; i < NXI; ++i)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (DEINFER_LDS3 void *)(slab0 + buf * SLAB + (kbi * NB * 32 + 16 * i) * 64), 16,
@@ -165,10 +167,12 @@ __global__ __launch_bounds__(ST_THREADS, 2) void stream_kernel(const StParams P)
     auto slot = [&](const u32x4_t (&w)[ST_SKB * 2], u32x4_t (&wn)[ST_SKB * 2], int s, int buf) {
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((ST_SLOTS - 2) * LPS) : "memory");   // slot s has arrived
       fetch(wn, s + ST_SLOTS - 1, buf == 0 ? ST_SLOTS - 1 : buf - 1);              // slab (s - 1) % 4 is free: this wavefront read it
-      if (s == s_fix) {                                 // (uniform) this wavefront's own slab: no barrier, LDS accesses of a wavefront stay in order
-        if (lane < NB * 32)
-          lds_zero_chunk_tail(slab0 + buf * SLAB + (kbi_fix * NB * 32 + lane) * 64 + ((((Q.K >> 3) & 3) ^ ((lane >> 2) & 3)) * 16), krem);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      if constexpr (TAIL) {
+        if (s == s_fix) {                               // (uniform) this wavefront's own slab: no barrier, LDS accesses of a wavefront stay in order
+          if (lane < NB * 32)
+            lds_zero_chunk_tail(slab0 + buf * SLAB + (kbi_fix * NB * 32 + lane) * 64 + ((((Q.K >> 3) & 3) ^ ((lane >> 2) & 3)) * 16), krem);
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
       }
       compute(w, buf);
     };
