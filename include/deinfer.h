@@ -147,9 +147,11 @@ int deinfer_lowrank_qkv(const void *x, int64_t T, int64_t ldx,
  * GLU-type MLP first sub-layer (Sec. 4.1 "activation computation", Table 2 GLU-based):
  *   h = silu((x U_g) V_g) * ((x U_u) V_u),   silu(z) = z / (1 + exp(-z)),
  * element-wise product, evaluated in fp32 and rounded once.  Both pairs share d_in
- * and d_out (= FFN width).  The full-width gate and up results never reach memory: for T > 128
- * both products of an output tile are accumulated in one workgroup's registers; for T <= 128 they
- * are fp32 partial sums in the workspace until the kernel that sums them applies the activation.
+ * and d_out (= FFN width).  The full-width gate and up results are never stored as such: for T > 128,
+ * and for 17 .. 128 tokens where the layer is wide enough to fill the device that way, both
+ * products of an output tile are accumulated in one workgroup and h is stored once; otherwise
+ * they are fp32 partial sums in the workspace until the kernel that sums them applies the
+ * activation.
  */
 int deinfer_lowrank_gateup_silu(const void *x, int64_t T, int64_t ldx,
                                 const deinfer_factors_t *fgate, const deinfer_factors_t *fup,
