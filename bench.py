@@ -275,6 +275,12 @@ def main():
         if sec_direct < sec_per_step:
             sec_per_step, launch_mode, step = sec_direct, "direct", direct
     ws.check(stream)
+    # spread of the step time: the same steps once more in ten chunks, each timed on its own (the value
+    # reported above is the mean over the K steps of the timed run; this says how far chunks scatter)
+    n_chunk = max(1, args.steps // 10)
+    chunk_ms = sorted(timed(step, n_chunk) * 1e3 for _ in range(10))
+    spread = {"steps_per_chunk": n_chunk, "min": round(chunk_ms[0], 5), "median": round(0.5 * (chunk_ms[4] + chunk_ms[5]), 5),
+              "max": round(chunk_ms[-1], 5)}
 
     # ---------------------------------------------------------------- per-call timing (HIP events on the launch stream)
     def time_call(name, n):
@@ -460,6 +466,7 @@ def main():
                                                               "qkv+o+linear_act(bias, ReLU)+linear_act(bias)"),
                    "ranks": ranks, "weight_MB": round(weight_bytes / 1e6, 1), "weight_copies": n_copies,
                    "launch": launch_mode, "launch_ms": launch_ms},
+        "ms_per_step_chunks": spread,
         "step_GBs": round(step_bytes / sec_per_step / 1e9, 1),
         "step_TFLOPs": round(step_flops / sec_per_step / 1e12, 2),
         "step_frac_of_roofline": round((step_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS) if bound == "hbm"
@@ -530,7 +537,7 @@ def main():
             except Exception as e:  # noqa: BLE001 - the main row stands on its own
                 return {"error": "%s: %s" % (type(e).__name__, res.stderr[-300:])}
 
-        keep = ("value", "unit", "ms_per_step", "step_frac_of_roofline", "step_GBs", "step_TFLOPs", "calls", "roofline", "config")
+        keep = ("value", "unit", "ms_per_step", "ms_per_step_chunks", "step_frac_of_roofline", "step_GBs", "step_TFLOPs", "calls", "roofline", "config")
         # free this process's copies of the weights first: the children need the memory bandwidth, not the space
         row = child(["--workload", "llama70b_keep40_prefill"])
         out["prefill"] = row if "error" in row else {k_: row[k_] for k_ in keep if k_ in row}
