@@ -246,21 +246,29 @@ def main():
         else:
             run_calls(calls[i % n_copies])
 
-    def timed(fn, n):
+    ev_ms = {}                     # the same region between two events on the launch stream (device time only)
+
+    def timed(fn, n, tag=None):
+        ea = torch.cuda.Event(enable_timing=True); eb = torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t_a = time.perf_counter()
         with torch.cuda.stream(stream):
+            ea.record(stream)
             for i in range(n):
                 fn(i)
+            eb.record(stream)
         stream.synchronize()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t_a) / n
+        t_b = time.perf_counter()
+        if tag is not None:
+            ev_ms[tag] = round(ea.elapsed_time(eb) / n, 5)
+        return (t_b - t_a) / n
 
     with torch.cuda.stream(stream):
         for i in range(args.warmup):
             step(i)
     stream.synchronize()
-    sec_per_step = timed(step, args.steps)
+    sec_per_step = timed(step, args.steps, launch_mode)
     launch_ms = {launch_mode: round(sec_per_step * 1e3, 5)}
     if args.launch == "auto" and graphs is not None:
         # the same K steps with every call launched directly (on this ROCm a replayed graph node costs a
@@ -270,7 +278,7 @@ def main():
             for i in range(args.warmup):
                 direct(i)
         stream.synchronize()
-        sec_direct = timed(direct, args.steps)
+        sec_direct = timed(direct, args.steps, "direct")
         launch_ms["direct"] = round(sec_direct * 1e3, 5)
         if sec_direct < sec_per_step:
             sec_per_step, launch_mode, step = sec_direct, "direct", direct
@@ -467,6 +475,9 @@ def main():
                    "ranks": ranks, "weight_MB": round(weight_bytes / 1e6, 1), "weight_copies": n_copies,
                    "launch": launch_mode, "launch_ms": launch_ms},
         "ms_per_step_chunks": spread,
+        # the timed K steps between two events on the launch stream: without the host's share of the
+        # bracket (first launch, wake-up after the synchronisation), which counts for a small K
+        "ms_per_step_device": ev_ms.get(launch_mode),
         "step_GBs": round(step_bytes / sec_per_step / 1e9, 1),
         "step_TFLOPs": round(step_flops / sec_per_step / 1e12, 2),
         "step_frac_of_roofline": round((step_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS) if bound == "hbm"
@@ -537,7 +548,7 @@ def main():
             except Exception as e:  # noqa: BLE001 - the main row stands on its own
                 return {"error": "%s: %s" % (type(e).__name__, res.stderr[-300:])}
 
-        keep = ("value", "unit", "ms_per_step", "ms_per_step_chunks", "step_frac_of_roofline", "step_GBs", "step_TFLOPs", "calls", "roofline", "config")
+        keep = ("value", "unit", "ms_per_step", "ms_per_step_chunks", "ms_per_step_device", "step_frac_of_roofline", "step_GBs", "step_TFLOPs", "calls", "roofline", "config")
         # free this process's copies of the weights first: the children need the memory bandwidth, not the space
         row = child(["--workload", "llama70b_keep40_prefill"])
         out["prefill"] = row if "error" in row else {k_: row[k_] for k_ in keep if k_ in row}
